@@ -1,0 +1,160 @@
+"""ctypes front end of the CPU oracle (oracle/dt_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+CPU-baseline leg of the benchmark.  The product package never imports it.
+
+Arrays are numpy: float32 for fp32 data, uint16 (raw bf16 bit patterns) for bf16 data.
+Every function handles ONE sequence; callers loop over a batch.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "dt_oracle.c")
+_LIB = os.path.join(_HERE, "libdt_oracle.so")
+
+TT_MAX, D_MAX, K_MAX = 128, 8, 32
+F32, BF16 = 0, 1
+GREEDY, STOCHASTIC = 0, 1
+
+
+def build(force=False):
+    """Compile the oracle with gcc (plain C, -O2, OpenMP over independent outputs)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp",
+                               "-ffp-contract=off", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.ref_uniform.restype = C.c_float
+        _lib.ref_uniform.argtypes = [C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint32]
+    return _lib
+
+
+def _dt(a):
+    if a.dtype == np.float32:
+        return F32
+    if a.dtype == np.uint16:
+        return BF16
+    raise TypeError("oracle arrays are float32 or uint16 (bf16 bits), got %s" % a.dtype)
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def _check(rc, what):
+    if rc < 0:
+        raise RuntimeError("%s failed with code %d" % (what, rc))
+    return rc
+
+
+def topk_rows(logits, k):
+    """A1: per-row top-k (logit desc, id asc) and log-sum-exp.  logits [R, V]."""
+    logits = np.ascontiguousarray(logits)
+    R, V = logits.shape
+    val = np.empty((R, k), np.float32)
+    idx = np.empty((R, k), np.int32)
+    lse = np.empty(R, np.float32)
+    _check(lib().ref_topk_rows(_p(logits), _dt(logits), C.c_int64(R), V, C.c_int64(V), k,
+                               _p(val), _p(idx), _p(lse)), "ref_topk_rows")
+    return val, idx, lse
+
+
+def build_tree(rows, TT, d, k, root_token=0, TT_cap=TT_MAX):
+    """A1-A4 for one sequence.  rows [>= 1+(d-1)k, V].  Returns a dict of node arrays."""
+    rows = np.ascontiguousarray(rows)
+    R, V = rows.shape
+    W = (TT_cap + 63) // 64
+    n = C.c_int32(0)
+    tokens = np.full(TT_cap, -1, np.int32)
+    parents = np.full(TT_cap, -1, np.int32)
+    depth = np.zeros(TT_cap, np.int32)
+    score = np.zeros(TT_cap, np.float32)
+    logp = np.zeros(TT_cap, np.float32)
+    src_row = np.full(TT_cap, -1, np.int32)
+    mask = np.zeros((TT_cap, W), np.uint64)
+    margin = C.c_float(0)
+    _check(lib().ref_build_tree(_p(rows), _dt(rows), V, C.c_int64(V), R, TT, d, k, root_token, TT_cap,
+                                C.byref(n), _p(tokens), _p(parents), _p(depth), _p(score), _p(logp),
+                                _p(src_row), _p(mask), C.byref(margin)), "ref_build_tree")
+    N = n.value
+    return dict(n_nodes=N, tokens=tokens[:N], parents=parents[:N], depth=depth[:N], score=score[:N],
+                logp=logp[:N], src_row=src_row[:N], anc_mask=mask[:N], min_margin=margin.value)
+
+
+def tree_attention(q, k_tree, v_tree, k_prefix, v_prefix, anc_mask, scale, samples=None, TT_cap=TT_MAX):
+    """A5 for one sequence.  q [N,Hq,D]; k_tree/v_tree [N,Hkv,D]; k_prefix/v_prefix [L,Hkv,D].
+
+    samples: optional int array [n,2] of (node, head) pairs -> output [n, D]; else [N,Hq,D].
+    Output float32 (on the bf16 grid for bf16 inputs).
+    """
+    q = np.ascontiguousarray(q)
+    k_tree, v_tree = np.ascontiguousarray(k_tree), np.ascontiguousarray(v_tree)
+    k_prefix, v_prefix = np.ascontiguousarray(k_prefix), np.ascontiguousarray(v_prefix)
+    N, Hq, D = q.shape
+    Hkv = k_tree.shape[1]
+    L = k_prefix.shape[0]
+    anc_mask = np.ascontiguousarray(anc_mask, np.uint64)
+    assert anc_mask.shape == (N, (TT_cap + 63) // 64)
+    if samples is not None:
+        samples = np.asarray(samples, np.int32).reshape(-1, 2)
+        sn, sh = np.ascontiguousarray(samples[:, 0]), np.ascontiguousarray(samples[:, 1])
+        out = np.empty((len(sn), D), np.float32)
+        ns = len(sn)
+    else:
+        sn = sh = None
+        out = np.empty((N, Hq, D), np.float32)
+        ns = 0
+    _check(lib().ref_tree_attention(_dt(q), Hq, Hkv, D, C.c_float(scale), _p(q), _p(k_tree), _p(v_tree), N,
+                                    _p(k_prefix), _p(v_prefix), L, C.c_int64(Hkv * D), C.c_int64(D),
+                                    _p(anc_mask), TT_cap, _p(sn), _p(sh), ns, _p(out)), "ref_tree_attention")
+    return out
+
+
+def accept(mode, target, tokens, parents, depth, logp=None, temperature=1.0, d_cap=D_MAX,
+           seed=0, step=0, seq=0):
+    """A6-A7 for one sequence.  target [N, V] (row i = target logits after node i)."""
+    target = np.ascontiguousarray(target)
+    N, V = target.shape
+    tokens = np.ascontiguousarray(tokens, np.int32)
+    parents = np.ascontiguousarray(parents, np.int32)
+    depth = np.ascontiguousarray(depth, np.int32)
+    logp = None if logp is None else np.ascontiguousarray(logp, np.float32)
+    alen, best = C.c_int32(0), C.c_int32(0)
+    path = np.empty(d_cap + 1, np.int32)
+    out_tok = np.empty(d_cap + 1, np.int32)
+    amax = np.empty(N, np.int32)
+    accepted = np.empty(N, np.uint8)
+    margin = C.c_float(0)
+    _check(lib().ref_accept(mode, C.c_float(temperature), _p(target), _dt(target), V, C.c_int64(V), N,
+                            _p(tokens), _p(parents), _p(depth), _p(logp), d_cap,
+                            C.c_uint64(seed), C.c_uint64(step), C.c_uint32(seq),
+                            C.byref(alen), C.byref(best), _p(path), _p(out_tok), _p(amax), _p(accepted),
+                            C.byref(margin)), "ref_accept")
+    return dict(accept_len=alen.value, best_node=best.value, path_nodes=path, out_tokens=out_tok,
+                node_argmax=amax, accepted=accepted.astype(bool), min_margin=margin.value)
+
+
+def philox4x32(ctr, key):
+    c = (C.c_uint32 * 4)(*ctr)
+    k = (C.c_uint32 * 2)(*key)
+    o = (C.c_uint32 * 4)()
+    lib().ref_philox4x32(c, k, o)
+    return tuple(int(x) for x in o)
+
+
+def uniform(seed, step, seq, node):
+    return float(lib().ref_uniform(seed, step, seq, node))

@@ -1,0 +1,63 @@
+"""Brute-force statements of the tree build and of greedy acceptance, on token STRINGS.
+
+No pool indices, slots or row arithmetic here: a candidate is the tuple of tokens from
+the root to it, its parent is the tuple without the last token, sets are Python sets and
+orders are Python tuple sorts.  A toy "draft model" maps a token string to a logit row.
+Used to pin the oracle's bookkeeping on tiny inputs (V <= 8, d <= 3, k <= 3).
+"""
+import numpy as np
+from scipy.special import logsumexp
+
+
+def toy_logits(seed, string, V, sigma=2.0):
+    """Deterministic float32 logit row of a token string (a toy draft or target model)."""
+    h = np.random.SeedSequence([seed, len(string)] + [int(t) + 1 for t in string])
+    return (np.random.Generator(np.random.PCG64(h)).standard_normal(V) * sigma).astype(np.float32)
+
+
+def brute_tree(draft_fn, V, TT, d, k):
+    """Returns (kept strings in level-major order of their discovery, score dict)."""
+    def topk(string):
+        x = draft_fn(string).astype(np.float64)
+        lse = logsumexp(x)
+        order = sorted(range(V), key=lambda t: (-x[t], t))[:k]
+        return [(t, x[t] - lse) for t in order if x[t] > -np.inf]
+
+    score = {}
+    levels = []
+    frontier = [()]          # strings to expand at this level
+    for level in range(1, d + 1):
+        cands = []
+        for s in frontier:
+            for t, lp in topk(s):
+                c = s + (t,)
+                score[c] = (score[s] if s else 0.0) + lp
+                cands.append(c)
+        levels.append(cands)
+        if not cands:
+            break
+        ranked = sorted(cands, key=lambda c: -score[c])
+        frontier = ranked[:k]
+    everyone = [c for lv in levels for c in lv]
+    ranked = sorted(everyone, key=lambda c: -score[c])
+    kept = set(ranked[:max(TT - 1, 0)])
+    return kept, score
+
+
+def brute_greedy_accept(strings, target_fn):
+    """strings: set of kept token strings (the tree without the root).
+
+    Enumerates every root-to-node path; the accepted path is the longest one all of whose
+    tokens equal the target arg max after the preceding string.  Returns (path string, bonus).
+    """
+    def amax(s):
+        x = target_fn(s)
+        return int(np.flatnonzero(x == x.max())[0])
+
+    best = ()
+    for s in sorted(strings, key=lambda c: (len(c), c)):
+        if all(s[:j] in strings or j == 0 for j in range(len(s))) and \
+           all(s[j] == amax(s[:j]) for j in range(len(s))):
+            if len(s) > len(best):
+                best = s
+    return best, amax(best)

@@ -1,0 +1,187 @@
+"""Pins of the oracle's tree build (A2-A4): brute force on token strings, special cases that
+have a closed form, and structural invariants of the outputs."""
+import itertools
+
+import numpy as np
+import pytest
+
+import dt_synth
+from oracle import ref
+from tests._brute import brute_tree, toy_logits
+from tests._drive import node_strings, rows_from_fn
+
+
+def closure_by_matrix_squaring(parents):
+    """Reflexive-transitive closure of the parent relation, by boolean matrix squaring."""
+    n = len(parents)
+    A = np.eye(n, dtype=bool)
+    for i in range(1, n):
+        A[i, parents[i]] = True
+    for _ in range(8):
+        A = (A.astype(np.int32) @ A.astype(np.int32)) > 0
+    return A
+
+
+def mask_to_matrix(mask, n):
+    M = np.zeros((n, n), bool)
+    for i in range(n):
+        for j in range(n):
+            M[i, j] = (int(mask[i, j // 64]) >> (j % 64)) & 1
+    return M
+
+
+def check_invariants(t, TT, d, k):
+    n = t["n_nodes"]
+    assert 1 <= n <= TT
+    assert t["parents"][0] == -1 and t["depth"][0] == 0
+    assert (t["depth"][:n] <= d).all()
+    assert (np.diff(t["depth"][:n]) >= 0).all()                 # level-major node order
+    for i in range(1, n):
+        p = t["parents"][i]
+        assert 0 <= p < i and t["depth"][i] == t["depth"][p] + 1
+        assert t["score"][i] <= t["score"][p] + 0.0             # log-probs are <= 0
+    M = mask_to_matrix(t["anc_mask"], n)
+    assert np.array_equal(M, closure_by_matrix_squaring(t["parents"][:n]))
+    assert np.array_equal(M.sum(1), t["depth"][:n] + 1)         # popcount = depth + 1
+    for p in range(n):
+        kids = [i for i in range(1, n) if t["parents"][i] == p]
+        assert len(kids) <= k
+        toks = [int(t["tokens"][i]) for i in kids]
+        assert len(set(toks)) == len(toks)                      # sibling tokens distinct
+    # bits above n are never set
+    for i in range(n):
+        for j in range(n, t["anc_mask"].shape[1] * 64):
+            assert not (int(t["anc_mask"][i, j // 64]) >> (j % 64)) & 1
+
+
+CASES = [(V, TT, d, k) for V in (4, 8) for d in (1, 2, 3) for k in (1, 2, 3)
+         for TT in (1, 2, 4, 7, 12, 40)]
+
+
+@pytest.mark.parametrize("V,TT,d,k", CASES)
+def test_tree_matches_brute_force_on_strings(V, TT, d, k):
+    for seed in range(3):
+        fn = lambda s: toy_logits(seed * 1000 + V, s, V)
+        rows = rows_from_fn(ref.build_tree, fn, V, d, k)
+        t = ref.build_tree(rows, TT, d, k, 5)
+        kept, score = brute_tree(fn, V, TT, d, k)
+        strs = node_strings(t)
+        assert strs[0] == () and t["tokens"][0] == 5
+        assert set(strs[1:]) == kept
+        assert len(strs) == len(set(strs))
+        for i in range(1, t["n_nodes"]):
+            assert abs(t["score"][i] - score[strs[i]]) < 1e-5
+            assert strs[t["parents"][i]] == strs[i][:-1]         # parent = string prefix
+            assert t["depth"][i] == len(strs[i])
+        check_invariants(t, TT, d, k)
+        assert t["min_margin"] > 1e-6                            # the brute force assumes no near-ties
+
+
+def test_k1_is_the_greedy_chain():
+    V, d = 16, 5
+    fn = lambda s: toy_logits(11, s, V)
+    rows = rows_from_fn(ref.build_tree, fn, V, d, 1)
+    for TT in (1, 3, 6, 10):
+        t = ref.build_tree(rows, TT, d, 1, 0)
+        n = min(d, TT - 1) + 1
+        assert t["n_nodes"] == n
+        s = ()
+        for i in range(1, n):
+            tok = int(np.argmax(fn(s)))
+            assert t["tokens"][i] == tok and t["parents"][i] == i - 1
+            s += (tok,)
+
+
+def test_d1_is_a_star_of_the_root_topk():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((1, 50)).astype(np.float32)
+    order = np.lexsort((np.arange(50), -x[0].astype(np.float64)))
+    for TT, k in [(4, 8), (20, 8), (9, 8)]:
+        t = ref.build_tree(x, TT, 1, k, 0)
+        n = min(k, TT - 1) + 1
+        assert t["n_nodes"] == n
+        assert (t["parents"][1:] == 0).all() and (t["depth"][1:] == 1).all()
+        assert sorted(t["tokens"][1:].tolist()) == sorted(order[:n - 1].tolist())
+        # node order is ascending pool index = descending logit
+        assert t["tokens"][1:].tolist() == order[:n - 1].tolist()
+
+
+def test_tt1_is_root_only_and_large_tt_keeps_whole_pool():
+    rows = dt_synth.draft_rows(dt_synth.config(1), 0)
+    t = ref.build_tree(rows, 1, 3, 2, 9)
+    assert t["n_nodes"] == 1 and t["tokens"][0] == 9 and t["anc_mask"][0, 0] == 1
+    t = ref.build_tree(rows, 100, 3, 2, 9)
+    assert t["n_nodes"] == 1 + 2 + 2 * 4                         # P = k + (d-1) k^2 = 10
+    check_invariants(t, 100, 3, 2)
+
+
+def test_src_row_is_the_row_layout_the_header_documents():
+    cfg = dt_synth.config(1)
+    rows = dt_synth.draft_rows(cfg, 0)
+    TT, d, k = 100, 3, 2
+    t = ref.build_tree(rows, TT, d, k, 0)
+    assert t["src_row"][0] == 0
+    for l in range(1, d):
+        owned = [t["src_row"][i] for i in range(t["n_nodes"]) if t["depth"][i] == l and t["src_row"][i] >= 0]
+        assert owned == list(range(1 + (l - 1) * k, 1 + (l - 1) * k + len(owned)))   # ascending pool index
+    assert all(t["src_row"][i] == -1 for i in range(t["n_nodes"]) if t["depth"][i] == d)
+
+
+def test_no_viable_candidates_stops_expansion():
+    V, d, k = 6, 3, 2
+    rows = np.full((1 + (d - 1) * k, V), -np.inf, np.float32)
+    rows[0, [1, 4]] = [0.5, 0.25]          # root has two viable children
+    rows[1, 2] = 1.0                        # first child has one viable child, second has none
+    t = ref.build_tree(rows, 16, d, k, 0)
+    strs = node_strings(t)
+    assert set(strs) == {(), (1,), (4,), (1, 2)}
+    rows[1, :] = -np.inf
+    t = ref.build_tree(rows, 16, d, k, 0)
+    assert set(node_strings(t)) == {(), (1,), (4,)}
+    rows[0, :] = -np.inf
+    t = ref.build_tree(rows, 16, d, k, 0)
+    assert t["n_nodes"] == 1
+
+
+@pytest.mark.parametrize("ci", [1, 2, 3])
+def test_invariants_on_benchmark_shaped_inputs(ci):
+    cfg = dt_synth.config(ci)
+    TT, d, k = cfg.params[0]
+    t = ref.build_tree(dt_synth.draft_rows(cfg, 0), TT, d, k, 1)
+    assert t["n_nodes"] == TT
+    check_invariants(t, TT, d, k)
+
+
+def test_invariants_random_sweep():
+    rng = np.random.default_rng(5)
+    for _ in range(40):
+        V = int(rng.integers(33, 400))
+        d, k = int(rng.integers(1, 9)), int(rng.integers(1, 13))
+        TT = int(rng.integers(1, 129))
+        rows = (rng.standard_normal((1 + (d - 1) * k, V)) * 3).astype(np.float32)
+        if rng.random() < 0.5:
+            rows = dt_synth.f32_to_bf16_bits(rows)
+        t = ref.build_tree(rows, TT, d, k, 0)
+        assert t["n_nodes"] == min(TT, 1 + k + (d - 1) * k * k)
+        check_invariants(t, TT, d, k)
+
+
+def test_bad_arguments_are_rejected():
+    rows = np.zeros((5, 64), np.float32)
+    for TT, d, k in [(0, 3, 2), (129, 3, 2), (8, 0, 2), (8, 9, 2), (8, 3, 0), (8, 3, 33), (8, 4, 2)]:
+        with pytest.raises(RuntimeError):
+            ref.build_tree(rows, TT, d, k, 0)
+
+
+def test_exact_score_ties_across_rows_go_to_the_lowest_pool_index():
+    """All-equal rows: every candidate of a level has the same score, so both the level cut and
+    the rerank are decided by the tie-break alone (lowest pool index = earlier parent, lower rank)."""
+    V, d, k = 8, 3, 2
+    rows = np.zeros((1 + (d - 1) * k, V), np.float32)
+    t = ref.build_tree(rows, 6, d, k, 0)
+    assert set(node_strings(t)) == {(), (0,), (1,), (0, 0), (0, 1), (1, 0)}
+    t = ref.build_tree(rows, 9, d, k, 0)
+    # level 2 is complete (4 nodes); its expanded set is the two lowest pool indices = children of
+    # the first level-1 node; the two level-3 nodes kept are the children of the first of those.
+    assert set(node_strings(t)) == {(), (0,), (1,), (0, 0), (0, 1), (1, 0), (1, 1), (0, 0, 0), (0, 0, 1)}
+    assert t["min_margin"] == 0.0          # such an input is exactly what the margin guard flags
