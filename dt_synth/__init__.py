@@ -157,3 +157,25 @@ def qkv(cfg, b):
 
 def root_token(cfg, b):
     return int(_rng(cfg, b, 4).integers(0, cfg.V))
+
+
+# ---- filling a device-side step object (anything with set_draft/set_root_token/set_qkv/set_target)
+
+def fill_draft_and_qkv(step, cfg, drafts=None):
+    """Upload draft rows, root tokens and Q/K/V of every sequence.  Returns the draft rows."""
+    drafts = drafts or [draft_rows(cfg, b) for b in range(cfg.B)]
+    for b in range(cfg.B):
+        step.set_draft(b, drafts[b])
+        step.set_root_token(b, root_token(cfg, b))
+        step.set_qkv(b, *qkv(cfg, b))
+    return drafts
+
+
+def fill_target(step, cfg, src_rows, drafts=None):
+    """Upload target rows built from each sequence's src_row array.  Returns them."""
+    targets = []
+    for b in range(cfg.B):
+        t = target_rows(cfg, b, src_rows[b], None if drafts is None else drafts[b])
+        step.set_target(b, t)
+        targets.append(t)
+    return targets

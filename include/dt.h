@@ -1,0 +1,186 @@
+/*
+ * dt.h -- C ABI of the draft-tree speculative step for AMD MI355X (gfx950).
+ *
+ * One speculative step of an EAGLE-style decoder whose tree limits (TT, d, k) are chosen
+ * anew on every call, as the RL policy of "Speculative Sampling with Reinforcement
+ * Learning" (Re-SpS) does:  dt_build_tree -> [target forward, whose attention is
+ * dt_tree_attention] -> dt_accept   (paper: Algorithm 1, "Construct draft tree DT using
+ * (TT, d, k)", "Verify DT with M_t"; Appendix B, Algorithm 2, drafting block).
+ *
+ * Conventions for every entry point
+ *   - Returns DT_OK or a negative dt_status.  Never throws, aborts, allocates, frees or
+ *     synchronises.  Arguments are validated on the host before anything is launched.
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  Scalars are host values.
+ *   - `stream` is the caller's hipStream_t (as void*; NULL = the default stream).  Work is
+ *     enqueued on it and the call returns immediately; outputs are valid once the stream
+ *     has reached that point.
+ *   - `ws` is caller-owned device scratch of at least dt_workspace_bytes() bytes, 256-byte
+ *     aligned.  Calls that share one workspace must be ordered on one stream.
+ *   - Per-sequence limits live in a DEVICE array of dt_params so that a policy running on
+ *     the GPU can set them without a host round trip.  Values are clamped on the device
+ *     to 1 <= TT <= TT_cap, 1 <= d <= DT_D_MAX, 1 <= k <= min(DT_K_MAX, V).
+ *   - Logits must not contain NaN or +inf; -inf marks a token that can never be proposed.
+ *   - Tie-breaks: inside a row larger logit first, then smaller token id; across rows
+ *     larger cumulative score first, then smaller pool index (see dt_build_tree).
+ */
+#ifndef DT_H
+#define DT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Limits: maxima of the action space in the paper's Appendix A
+ * (TT in {32..128}, d in {3..8}, k in {8..32}). */
+#define DT_TT_MAX 128
+#define DT_D_MAX 8
+#define DT_K_MAX 32
+#define DT_MASK_WORDS (DT_TT_MAX / 64) /* uint64 words per node in anc_mask */
+
+typedef struct {
+    int32_t TT; /* upper limit on tree tokens, root included  (paper Section 4, action space) */
+    int32_t d;  /* upper limit on tree depth = draft levels below the root */
+    int32_t k;  /* children proposed per expanded node and nodes expanded per level */
+} dt_params;
+
+typedef enum { DT_F32 = 0, DT_BF16 = 1 } dt_dtype;
+typedef enum { DT_ACCEPT_GREEDY = 0, DT_ACCEPT_STOCHASTIC = 1 } dt_accept_mode;
+
+typedef enum {
+    DT_OK = 0,
+    DT_ERR_INVALID_ARG = -1, /* null pointer, negative size, misaligned pointer, bad enum */
+    DT_ERR_LIMIT = -2,       /* a size exceeds a compiled limit (TT_cap, k, head dim, ...) */
+    DT_ERR_WORKSPACE = -3,   /* ws too small or NULL */
+    DT_ERR_DTYPE = -4,       /* dtype/shape combination without a kernel */
+    DT_ERR_HIP = -5          /* a HIP call failed; see dt_last_hip_error() */
+} dt_status;
+
+const char *dt_status_string(int status);
+/* hipError_t of the last failing HIP call made by this library on this thread (0 if none). */
+int dt_last_hip_error(void);
+
+/*
+ * Scratch size that suffices for any of the calls below with
+ *   batch sequences, total_rows draft rows (all sequences), vocabulary V,
+ *   node rows padded to TT_cap per sequence, Hq query heads of dimension D.
+ * Host-only computation.
+ */
+int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq, int D, size_t *bytes);
+
+/*
+ * Row top-k and row log-sum-exp (paper Algorithm 2: each expanded node proposes its k
+ * most confident children; Section 3.2: confidence = draft probability).
+ *   logits   [n_rows, row_stride] elements of type t, row r at logits + r*row_stride; V <= row_stride.
+ *   top_val  [n_rows, k] float : the k largest logits of the row, best first
+ *   top_id   [n_rows, k] int32 : their token ids; equal logits are ordered by ascending id
+ *   lse      [n_rows]   float  : log sum_v exp(logits[r, v])
+ * Slots beyond the number of finite entries of a row hold (-inf, -1).
+ * Errors: k < 1 or k > min(DT_K_MAX, V) -> DT_ERR_LIMIT.
+ */
+int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, int V, int64_t row_stride,
+                 int k, float *top_val, int32_t *top_id, float *lse, void *ws, size_t ws_bytes);
+
+/*
+ * Draft-tree construction for a batch (paper Section 3.2 "Draft Tree Expansion" and
+ * "Confidence-Based Candidate Reranking"; Algorithm 2, expansion loop and rerank).
+ *
+ * Input rows.  Sequence b owns draft rows row_off[b] .. row_off[b+1]-1 of draft_logits
+ * and uses the first 1 + (d-1)*k of them: local row 0 is the next-token row of the root;
+ * local row 1 + (l-1)*k + s is the next-token row of the s-th expanded node of level l
+ * (l = 1..d-1), expanded nodes of a level being numbered in ascending pool index.
+ * total_rows = row_off[batch] as a host value (sizes the launch).
+ *
+ * Method.  Level-l candidates are the top-k tokens of every expanded level-(l-1) node;
+ * score = score[parent] + (logit - lse of its row), one float add per level.  The k best
+ * candidates of a level (score desc, pool index asc) are expanded.  Pool index of the
+ * rank-r child of slot s at level l: r for l = 1, else k + (l-2)k^2 + s*k + r.  Finally the
+ * best min(TT-1, pool size) candidates of the whole pool are kept (same order).
+ *
+ * Outputs, per sequence b at offset b*TT_cap (b*TT_cap*DT_MASK_WORDS for anc_mask);
+ * node 0 is the root, nodes 1.. are the kept candidates in ascending pool index, so
+ * parents precede children and depth is non-decreasing:
+ *   n_nodes [batch]           number of nodes N <= TT
+ *   tokens  [batch, TT_cap]   token id (node 0: root_token[b])
+ *   parents [batch, TT_cap]   node index of the parent, -1 for the root
+ *   depth   [batch, TT_cap]   level, 0 for the root
+ *   score   [batch, TT_cap]   cumulative draft log-probability
+ *   logp    [batch, TT_cap]   the node's own draft log-probability (0 for the root)
+ *   src_row [batch, TT_cap]   local draft row the node was handed (root 0), -1 if not expanded
+ *   anc_mask[batch, TT_cap, DT_MASK_WORDS] bit j of node i set iff j == i or j is an ancestor of i
+ * Entries at index >= n_nodes[b] are left untouched.
+ * Errors: TT_cap < 1 or > DT_TT_MAX, V < 1 -> DT_ERR_LIMIT; ws too small -> DT_ERR_WORKSPACE.
+ */
+int dt_build_tree(void *stream, int batch, const dt_params *params, const void *draft_logits, dt_dtype t,
+                  int V, int64_t row_stride, const int64_t *row_off, int64_t total_rows,
+                  const int32_t *root_token, int TT_cap, int32_t *n_nodes, int32_t *tokens,
+                  int32_t *parents, int32_t *depth, float *score, float *logp, int32_t *src_row,
+                  uint64_t *anc_mask, void *ws, size_t ws_bytes);
+
+/*
+ * Tree-masked attention of the tree tokens for ONE layer (paper Section 3.2 "Verification
+ * Phase": the target evaluates all draft tokens in one pass; Section 2: tree attention).
+ * Node i of sequence b, query head h (kv head h / (Hq/Hkv)) attends to the prefix_len[b]
+ * prefix keys and to the tree keys j with bit j of anc_mask[b, i] set:
+ *   out[b,i,h,:] = softmax_j(scale * q[b,i,h,:] . K_j) V_j
+ *   q, out         [batch, TT_cap, Hq, D]  type t (rows >= n_nodes[b] are neither read nor written)
+ *   k_tree, v_tree [batch, TT_cap, Hkv, D] type t
+ *   k_prefix[b], v_prefix[b] : device arrays (length batch) of device pointers; element
+ *       (token, kv head, c) at token*kv_stride_tok + head*kv_stride_head + c (strides in elements)
+ *   max_prefix_len : host upper bound of prefix_len[] (sizes the launch)
+ * Arithmetic: bf16 inputs, fp32 accumulation (MFMA), fp32 softmax, output rounded to bf16;
+ * fp32 inputs are handled entirely in fp32.
+ * Errors: Hq % Hkv != 0, D not in {64, 128} for bf16 or D > 128 / D % 4 != 0 for fp32 -> DT_ERR_DTYPE/LIMIT.
+ */
+int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int D, float scale,
+                      const void *q, const void *k_tree, const void *v_tree, const int32_t *n_nodes,
+                      const void *const *k_prefix, const void *const *v_prefix, const int32_t *prefix_len,
+                      int max_prefix_len, int64_t kv_stride_tok, int64_t kv_stride_head,
+                      const uint64_t *anc_mask, int TT_cap, void *out, void *ws, size_t ws_bytes);
+
+/*
+ * Acceptance and longest accepted walk (paper Section 3.2 "Acceptance Criterion";
+ * Section 3.1 greedy decoding).  target_logits row (b, i) = the target's next-token
+ * logits after node i, at target_logits + (b*TT_cap + i)*row_stride.
+ *   greedy     : node i > 0 accepted iff tokens[i] == argmax(row of its parent), ties -> lowest id
+ *   stochastic : accepted iff u_i < min(1, P_T(tokens[i]) / P_d(tokens[i])), P_T = softmax(row of
+ *                parent / temperature), P_d = exp(logp[i]); u_i is the first word of
+ *                Philox4x32-10(counter = (i, b, step lo, step hi), key = (seed lo, seed hi)),
+ *                mapped to [0,1) as (word >> 8) * 2^-24.
+ * The walk ends at `best`, the deepest node all of whose ancestors (and itself) are accepted,
+ * ties -> lowest node index.  Outputs per sequence:
+ *   accept_len [batch]               depth of best = number of accepted draft tokens
+ *   best_node  [batch]
+ *   path_nodes [batch, DT_D_MAX+1]   root .. best, unused slots -1
+ *   out_tokens [batch, DT_D_MAX+1]   accepted draft tokens, then the bonus token (greedy: argmax of
+ *                                    row best; stochastic: inverse-CDF sample of softmax(row best /
+ *                                    temperature) at the uniform with node index 0xFFFFFFFF), then -1
+ *   node_argmax[batch, TT_cap]       argmax of every node row (may be NULL)
+ * Errors: stochastic with temperature <= 0 or logp NULL -> DT_ERR_INVALID_ARG.
+ */
+int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, const void *target_logits,
+              dt_dtype t, int V, int64_t row_stride, const int32_t *n_nodes, const int32_t *tokens,
+              const int32_t *parents, const int32_t *depth, const float *logp, const uint64_t *anc_mask,
+              int TT_cap, uint64_t philox_seed, uint64_t philox_step, int32_t *accept_len,
+              int32_t *best_node, int32_t *path_nodes, int32_t *out_tokens, int32_t *node_argmax,
+              void *ws, size_t ws_bytes);
+
+/*
+ * Optional per-kernel timing, for measurement only (off by default; not part of the step).
+ * dt_profile_enable(n > 0) pre-creates n HIP event pairs and switches timing on: every kernel
+ * launched by the calls above is then bracketed by an event pair on its stream.
+ * dt_profile_enable(0) switches it off.  dt_profile_read sums, for one kernel id
+ * (0 draft row chunks, 1 row merge, 2 tree, 3 attention, 4 attention combine, 5 target row
+ * chunks, 6 accept, 7 dt_topk_rows chunks), the elapsed milliseconds of the launches recorded
+ * since the last enable, waiting for them to finish.  Not thread-safe.
+ */
+int dt_profile_enable(int max_launches);
+int dt_profile_read(int kernel_id, double *total_ms, int *launches);
+const char *dt_profile_kernel_name(int kernel_id);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DT_H */

@@ -1,0 +1,136 @@
+"""ctypes binding of libdt.so.  Argument marshalling only."""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdt.so")
+
+DT_TT_MAX, DT_D_MAX, DT_K_MAX, DT_MASK_WORDS = 128, 8, 32, 2
+DT_F32, DT_BF16 = 0, 1
+DT_ACCEPT_GREEDY, DT_ACCEPT_STOCHASTIC = 0, 1
+
+_lib = None
+
+
+class DtError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__("%s failed: %s (%d)" % (fn, dt_status_string(status), status))
+
+
+def library_path():
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libdt.so (built by paper_2601_12212_amd/build.py).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError("libdt.so is not built: run `python paper_2601_12212_amd/build.py` "
+                              "(there is no fallback path)")
+        lib = C.CDLL(_LIB_PATH)
+        vp, i32, i64, u64, f32, sz = C.c_void_p, C.c_int, C.c_int64, C.c_uint64, C.c_float, C.c_size_t
+        lib.dt_status_string.restype = C.c_char_p
+        lib.dt_status_string.argtypes = [i32]
+        lib.dt_last_hip_error.restype = i32
+        lib.dt_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, i32, C.POINTER(sz)]
+        lib.dt_topk_rows.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, vp, vp, vp, sz]
+        lib.dt_build_tree.argtypes = [vp, i32, vp, vp, i32, i32, i64, vp, i64, vp, i32] + [vp] * 8 + [vp, sz]
+        lib.dt_tree_attention.argtypes = [vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64,
+                                          vp, i32, vp, vp, sz]
+        lib.dt_accept.argtypes = [vp, i32, i32, f32, vp, i32, i32, i64, vp, vp, vp, vp, vp, vp, i32, u64, u64,
+                                  vp, vp, vp, vp, vp, vp, sz]
+        lib.dt_profile_enable.argtypes = [i32]
+        lib.dt_profile_enable.restype = i32
+        lib.dt_profile_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i32)]
+        lib.dt_profile_read.restype = i32
+        lib.dt_profile_kernel_name.argtypes = [i32]
+        lib.dt_profile_kernel_name.restype = C.c_char_p
+        for fn in ("dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept"):
+            getattr(lib, fn).restype = i32
+        _lib = lib
+    return _lib
+
+
+def dt_status_string(status):
+    return load_library().dt_status_string(status).decode()
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _stream():
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype(t):
+    import torch
+    if t.dtype == torch.float32:
+        return DT_F32
+    if t.dtype == torch.bfloat16:
+        return DT_BF16
+    raise TypeError("dt: tensors are float32 or bfloat16, got %s" % t.dtype)
+
+
+def _check(fn, rc):
+    if rc != 0:
+        raise DtError(fn, rc)
+
+
+def dt_workspace_bytes(batch, total_rows, V, TT_cap, Hq, D):
+    out = C.c_size_t(0)
+    _check("dt_workspace_bytes", load_library().dt_workspace_bytes(batch, total_rows, V, TT_cap, Hq, D, C.byref(out)))
+    return out.value
+
+
+def dt_topk_rows(logits, k, top_val, top_id, lse, ws):
+    n_rows, V = logits.shape
+    _check("dt_topk_rows", load_library().dt_topk_rows(
+        _stream(), _ptr(logits), _dtype(logits), n_rows, V, logits.stride(0), k, _ptr(top_val), _ptr(top_id),
+        _ptr(lse), _ptr(ws), ws.numel() * ws.element_size()))
+
+
+def dt_build_tree(params, draft_logits, row_off, total_rows, root_token, TT_cap, n_nodes, tokens, parents, depth,
+                  score, logp, src_row, anc_mask, ws):
+    batch = params.shape[0]
+    V = draft_logits.shape[1]
+    _check("dt_build_tree", load_library().dt_build_tree(
+        _stream(), batch, _ptr(params), _ptr(draft_logits), _dtype(draft_logits), V, draft_logits.stride(0),
+        _ptr(row_off), total_rows, _ptr(root_token), TT_cap, _ptr(n_nodes), _ptr(tokens), _ptr(parents),
+        _ptr(depth), _ptr(score), _ptr(logp), _ptr(src_row), _ptr(anc_mask), _ptr(ws),
+        ws.numel() * ws.element_size()))
+
+
+def dt_tree_attention(q, k_tree, v_tree, n_nodes, k_prefix_ptrs, v_prefix_ptrs, prefix_len, max_prefix_len,
+                      kv_stride_tok, kv_stride_head, anc_mask, scale, out, ws):
+    batch, TT_cap, Hq, D = q.shape
+    Hkv = k_tree.shape[2]
+    _check("dt_tree_attention", load_library().dt_tree_attention(
+        _stream(), batch, _dtype(q), Hq, Hkv, D, scale, _ptr(q), _ptr(k_tree), _ptr(v_tree), _ptr(n_nodes),
+        _ptr(k_prefix_ptrs), _ptr(v_prefix_ptrs), _ptr(prefix_len), max_prefix_len, kv_stride_tok, kv_stride_head,
+        _ptr(anc_mask), TT_cap, _ptr(out), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size()))
+
+
+def dt_accept(mode, temperature, target_logits, n_nodes, tokens, parents, depth, logp, anc_mask, philox_seed,
+              philox_step, accept_len, best_node, path_nodes, out_tokens, node_argmax, ws):
+    batch, TT_cap, V = target_logits.shape
+    _check("dt_accept", load_library().dt_accept(
+        _stream(), batch, mode, temperature, _ptr(target_logits), _dtype(target_logits), V, target_logits.stride(1),
+        _ptr(n_nodes), _ptr(tokens), _ptr(parents), _ptr(depth), _ptr(logp), _ptr(anc_mask), TT_cap, philox_seed,
+        philox_step, _ptr(accept_len), _ptr(best_node), _ptr(path_nodes), _ptr(out_tokens), _ptr(node_argmax),
+        _ptr(ws), ws.numel() * ws.element_size()))
+
+
+def dt_profile_enable(max_launches):
+    _check("dt_profile_enable", load_library().dt_profile_enable(int(max_launches)))
+
+
+def dt_profile_read(kernel_id):
+    """-> (kernel name, total milliseconds, launches) recorded since the last dt_profile_enable."""
+    ms, n = C.c_double(0), C.c_int(0)
+    lib = load_library()
+    _check("dt_profile_read", lib.dt_profile_read(kernel_id, C.byref(ms), C.byref(n)))
+    return lib.dt_profile_kernel_name(kernel_id).decode(), ms.value, n.value

@@ -1,0 +1,216 @@
+// C ABI of the library: argument validation on host values, scratch layout, launches.
+// No allocation, no synchronisation, no exceptions.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "kernels.hpp"
+
+namespace {
+
+thread_local int g_last_hip = 0;
+
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+inline bool bad_dtype(int t) { return t != DT_F32 && t != DT_BF16; }
+
+// Smallest chunk multiplier that keeps a row within 64 chunks (the merge handles <= 64 lists).
+inline int min_nl(int V) {
+    for (int nl = 1; nl <= 4; nl <<= 1)
+        if (dt::rows_chunks_per_row(V, nl) <= 64) return nl;
+    return 0;
+}
+inline int pick_nl(int64_t n_rows, int V) {
+    int a = dt::rows_pick_nl(n_rows, V), b = min_nl(V);
+    return a > b ? a : b;
+}
+inline int max_chunks(int V) { return dt::rows_chunks_per_row(V, min_nl(V)); }
+
+struct RowScratch {
+    unsigned long long *keys;
+    float2 *ms;
+    size_t bytes;
+};
+// [rows, S, key_stride] keys followed by [rows, S] (max, sum) pairs
+inline RowScratch row_scratch(void *ws, int64_t rows, int S, int key_stride) {
+    RowScratch r;
+    size_t kb = align_up((size_t)rows * S * key_stride * 8);
+    size_t mb = align_up((size_t)rows * S * 8);
+    r.keys = (unsigned long long *)ws;
+    r.ms = (float2 *)((char *)ws + kb);
+    r.bytes = kb + mb;
+    return r;
+}
+
+inline int hip_fail(hipError_t e) {
+    g_last_hip = (int)e;
+    return DT_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dt_status_string(int s) {
+    switch (s) {
+        case DT_OK: return "ok";
+        case DT_ERR_INVALID_ARG: return "invalid argument";
+        case DT_ERR_LIMIT: return "size exceeds a compiled limit";
+        case DT_ERR_WORKSPACE: return "workspace missing or too small";
+        case DT_ERR_DTYPE: return "no kernel for this dtype/shape";
+        case DT_ERR_HIP: return "HIP call failed";
+        default: return "unknown status";
+    }
+}
+
+int dt_last_hip_error(void) { return g_last_hip; }
+
+int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq, int D, size_t *bytes) {
+    if (!bytes || batch < 0 || total_rows < 0 || Hq < 0 || D < 0) return DT_ERR_INVALID_ARG;
+    if (V < 1 || TT_cap < 1 || TT_cap > DT_TT_MAX || min_nl(V) == 0) return DT_ERR_LIMIT;
+    const int S = max_chunks(V);
+    // build: row partials (k slots each) + merged top-k (values, ids) + lse
+    size_t build = row_scratch(nullptr, total_rows, S, DT_K_MAX).bytes + 2 * align_up((size_t)total_rows * DT_K_MAX * 4) +
+                   align_up((size_t)total_rows * 4);
+    size_t accept = row_scratch(nullptr, (int64_t)batch * TT_cap, S, 1).bytes;
+    size_t attn = dt::attn_workspace_bytes(batch, TT_cap, Hq, D);
+    size_t m = build > accept ? build : accept;
+    m = m > attn ? m : attn;
+    *bytes = m + 256;
+    return DT_OK;
+}
+
+int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, int V, int64_t row_stride, int k,
+                 float *top_val, int32_t *top_id, float *lse, void *ws, size_t ws_bytes) {
+    if (!logits || !top_val || !top_id || !lse || n_rows < 0 || bad_dtype(t) || row_stride < V)
+        return DT_ERR_INVALID_ARG;
+    if (V < 1 || min_nl(V) == 0 || k < 1 || k > DT_K_MAX || k > V) return DT_ERR_LIMIT;
+    if (n_rows == 0) return DT_OK;
+    const int nl = pick_nl(n_rows, V), S = dt::rows_chunks_per_row(V, nl);
+    if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
+    RowScratch rs = row_scratch(ws, n_rows, S, k);
+    if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
+    dt::RowArgs a = {};
+    a.logits = logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
+    a.mode = dt::ROWS_UNIFORM; a.k_uniform = k;
+    a.want_lse = 1; a.inv_t = 1.0f;
+    a.part_keys = rs.keys; a.key_stride = k; a.part_ms = rs.ms;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = dt::rows_launch_chunks(a, n_rows, nl, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = dt::rows_launch_merge(a, n_rows, S, top_val, top_id, lse, k, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
+int dt_build_tree(void *stream, int batch, const dt_params *params, const void *draft_logits, dt_dtype t, int V,
+                  int64_t row_stride, const int64_t *row_off, int64_t total_rows, const int32_t *root_token,
+                  int TT_cap, int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth, float *score,
+                  float *logp, int32_t *src_row, uint64_t *anc_mask, void *ws, size_t ws_bytes) {
+    if (batch < 0 || total_rows < 0 || bad_dtype(t)) return DT_ERR_INVALID_ARG;
+    if (batch == 0) return DT_OK;
+    if (!params || !draft_logits || !row_off || !root_token || !n_nodes || !tokens || !parents || !depth ||
+        !score || !logp || !src_row || !anc_mask || row_stride < V)
+        return DT_ERR_INVALID_ARG;
+    if (V < 1 || min_nl(V) == 0 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
+    if (total_rows < batch) return DT_ERR_INVALID_ARG;  // every sequence owns at least its root row
+    const int nl = pick_nl(total_rows, V), S = dt::rows_chunks_per_row(V, nl);
+    if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
+    RowScratch rs = row_scratch(ws, total_rows, S, DT_K_MAX);
+    size_t off = rs.bytes;
+    float *top_val = (float *)((char *)ws + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
+    int32_t *top_id = (int32_t *)((char *)ws + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
+    float *lse = (float *)((char *)ws + off); off += align_up((size_t)total_rows * 4);
+    if (off > ws_bytes) return DT_ERR_WORKSPACE;
+
+    dt::RowArgs a = {};
+    a.logits = draft_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
+    a.mode = dt::ROWS_DRAFT; a.batch = batch; a.params = params; a.row_off = row_off; a.TT_cap = TT_cap;
+    a.want_lse = 1; a.inv_t = 1.0f;
+    a.part_keys = rs.keys; a.key_stride = DT_K_MAX; a.part_ms = rs.ms;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = dt::rows_launch_chunks(a, total_rows, nl, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = dt::rows_launch_merge(a, total_rows, S, top_val, top_id, lse, DT_K_MAX, st);
+    if (e != hipSuccess) return hip_fail(e);
+
+    dt::TreeArgs ta = {};
+    ta.batch = batch; ta.params = params; ta.V = V; ta.row_off = row_off; ta.root_token = root_token;
+    ta.TT_cap = TT_cap; ta.top_val = top_val; ta.top_id = top_id; ta.lse = lse;
+    ta.n_nodes = n_nodes; ta.tokens = tokens; ta.parents = parents; ta.depth = depth; ta.src_row = src_row;
+    ta.score = score; ta.logp = logp; ta.anc_mask = (unsigned long long *)anc_mask;
+    e = dt::tree_launch(ta, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
+int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int D, float scale, const void *q,
+                      const void *k_tree, const void *v_tree, const int32_t *n_nodes, const void *const *k_prefix,
+                      const void *const *v_prefix, const int32_t *prefix_len, int max_prefix_len,
+                      int64_t kv_stride_tok, int64_t kv_stride_head, const uint64_t *anc_mask, int TT_cap,
+                      void *out, void *ws, size_t ws_bytes) {
+    if (batch < 0 || bad_dtype(t)) return DT_ERR_INVALID_ARG;
+    if (batch == 0) return DT_OK;
+    if (!q || !k_tree || !v_tree || !n_nodes || !k_prefix || !v_prefix || !prefix_len || !anc_mask || !out)
+        return DT_ERR_INVALID_ARG;
+    if (Hq < 1 || Hkv < 1 || Hq % Hkv || D < 1 || max_prefix_len < 0 || !(scale > 0.0f) || kv_stride_tok < 0 ||
+        kv_stride_head < 0)
+        return DT_ERR_INVALID_ARG;
+    if (TT_cap < 1 || TT_cap > DT_TT_MAX || D > 128) return DT_ERR_LIMIT;
+    if ((uintptr_t)q % 16 || (uintptr_t)k_tree % 16 || (uintptr_t)v_tree % 16 || (uintptr_t)out % 16)
+        return DT_ERR_INVALID_ARG;
+    if (ws && (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
+    dt::AttnArgs a = {};
+    a.batch = batch; a.dtype = t; a.Hq = Hq; a.Hkv = Hkv; a.D = D; a.scale = scale;
+    a.q = q; a.k_tree = k_tree; a.v_tree = v_tree; a.n_nodes = n_nodes;
+    a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.prefix_len = prefix_len; a.max_prefix_len = max_prefix_len;
+    a.kv_stride_tok = kv_stride_tok; a.kv_stride_head = kv_stride_head;
+    a.anc_mask = (const unsigned long long *)anc_mask; a.TT_cap = TT_cap; a.out = out;
+    a.ws = ws; a.ws_bytes = ws ? ws_bytes : 0;
+    hipError_t e = hipSuccess;
+    int rc = dt::attn_launch(a, (hipStream_t)stream, &e);
+    if (rc == DT_ERR_HIP) return hip_fail(e);
+    return rc;
+}
+
+int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, const void *target_logits, dt_dtype t,
+              int V, int64_t row_stride, const int32_t *n_nodes, const int32_t *tokens, const int32_t *parents,
+              const int32_t *depth, const float *logp, const uint64_t *anc_mask, int TT_cap, uint64_t philox_seed,
+              uint64_t philox_step, int32_t *accept_len, int32_t *best_node, int32_t *path_nodes,
+              int32_t *out_tokens, int32_t *node_argmax, void *ws, size_t ws_bytes) {
+    if (batch < 0 || bad_dtype(t)) return DT_ERR_INVALID_ARG;
+    if (mode != DT_ACCEPT_GREEDY && mode != DT_ACCEPT_STOCHASTIC) return DT_ERR_INVALID_ARG;
+    if (batch == 0) return DT_OK;
+    if (!target_logits || !n_nodes || !tokens || !parents || !depth || !anc_mask || !accept_len || !best_node ||
+        !path_nodes || !out_tokens || row_stride < V)
+        return DT_ERR_INVALID_ARG;
+    if (mode == DT_ACCEPT_STOCHASTIC && (!logp || !(temperature > 0.0f))) return DT_ERR_INVALID_ARG;
+    if (V < 1 || min_nl(V) == 0 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
+    const int64_t rows = (int64_t)batch * TT_cap;
+    const int nl = pick_nl(rows, V), S = dt::rows_chunks_per_row(V, nl);
+    if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
+    RowScratch rs = row_scratch(ws, rows, S, 1);
+    if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
+
+    dt::RowArgs a = {};
+    a.logits = target_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
+    a.mode = dt::ROWS_TARGET; a.batch = batch; a.TT_cap = TT_cap; a.n_nodes = n_nodes;
+    a.want_lse = mode == DT_ACCEPT_STOCHASTIC; a.inv_t = mode == DT_ACCEPT_STOCHASTIC ? 1.0f / temperature : 1.0f;
+    a.part_keys = rs.keys; a.key_stride = 1; a.part_ms = rs.ms;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = dt::rows_launch_chunks(a, rows, nl, st);
+    if (e != hipSuccess) return hip_fail(e);
+
+    dt::AcceptArgs aa = {};
+    aa.batch = batch; aa.mode = mode; aa.temperature = temperature; aa.target = target_logits; aa.dtype = t;
+    aa.V = V; aa.row_stride = row_stride; aa.n_nodes = n_nodes; aa.tokens = tokens; aa.parents = parents;
+    aa.depth = depth; aa.logp = logp; aa.anc_mask = (const unsigned long long *)anc_mask; aa.TT_cap = TT_cap;
+    aa.seed = philox_seed; aa.step = philox_step; aa.accept_len = accept_len; aa.best_node = best_node;
+    aa.path_nodes = path_nodes; aa.out_tokens = out_tokens; aa.node_argmax = node_argmax;
+    aa.part_keys = rs.keys; aa.part_ms = rs.ms; aa.S = S;
+    e = dt::accept_launch(aa, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,108 @@
+// Internal interfaces between the C ABI (api.cpp) and the kernel files.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/dt.h"
+
+namespace dt {
+
+// ---------------------------------------------------------- per-kernel timing (profile.cpp)
+// Off by default.  When switched on (dt_profile_enable), every launch is bracketed by a pair
+// of pre-created HIP events on the launch stream; dt_profile_read sums the elapsed times.
+enum KernelId { KID_ROWS_DRAFT = 0, KID_ROWS_MERGE, KID_TREE, KID_ATTN, KID_ATTN_COMBINE, KID_ROWS_TARGET,
+                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COUNT };
+void prof_begin(int kid, hipStream_t st);
+void prof_end(int kid, hipStream_t st);
+struct ProfScope {
+    int kid;
+    hipStream_t st;
+    ProfScope(int k, hipStream_t s) : kid(k), st(s) { prof_begin(kid, st); }
+    ~ProfScope() { prof_end(kid, st); }
+};
+
+// ------------------------------------------------------------------ row kernels (rows.hip)
+enum RowMode { ROWS_UNIFORM = 0, ROWS_DRAFT = 1, ROWS_TARGET = 2 };
+
+struct RowArgs {
+    const void *logits;
+    int dtype;           // dt_dtype
+    int V;
+    int64_t row_stride;  // elements
+    int mode;            // RowMode: which rows of the launch are live and their k
+    int k_uniform;       // ROWS_UNIFORM
+    int batch;           // ROWS_DRAFT
+    const dt_params *params;
+    const int64_t *row_off;
+    int TT_cap;           // ROWS_DRAFT (clamp), ROWS_TARGET (rows per sequence)
+    const int32_t *n_nodes;  // ROWS_TARGET
+    int want_lse;
+    float inv_t;          // 1 / temperature applied inside the exponentials
+    unsigned long long *part_keys;  // [rows, S, key_stride]
+    int key_stride;
+    float2 *part_ms;      // [rows, S] (max, sum exp((x-max)*inv_t))
+};
+
+int rows_pick_nl(int64_t n_rows, int V);
+int rows_chunks_per_row(int V, int nl);
+hipError_t rows_launch_chunks(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st);
+hipError_t rows_launch_merge(const RowArgs &a, int64_t n_rows, int S, float *top_val, int32_t *top_id, float *lse,
+                             int out_stride, hipStream_t st);
+
+// ------------------------------------------------------------------ tree kernel (tree.hip)
+struct TreeArgs {
+    int batch;
+    const dt_params *params;
+    int V;
+    const int64_t *row_off;
+    const int32_t *root_token;
+    int TT_cap;
+    const float *top_val;  // [total_rows, DT_K_MAX]
+    const int32_t *top_id;
+    const float *lse;      // [total_rows]
+    int32_t *n_nodes, *tokens, *parents, *depth, *src_row;
+    float *score, *logp;
+    unsigned long long *anc_mask;
+};
+hipError_t tree_launch(const TreeArgs &a, hipStream_t st);
+
+// -------------------------------------------------------------- attention (attention.hip)
+struct AttnArgs {
+    int batch, dtype, Hq, Hkv, D;
+    float scale;
+    const void *q, *k_tree, *v_tree;
+    const int32_t *n_nodes;
+    const void *const *k_prefix;
+    const void *const *v_prefix;
+    const int32_t *prefix_len;
+    int max_prefix_len;
+    int64_t kv_stride_tok, kv_stride_head;
+    const unsigned long long *anc_mask;
+    int TT_cap;
+    void *out;
+    void *ws;
+    size_t ws_bytes;
+};
+size_t attn_workspace_bytes(int batch, int TT_cap, int Hq, int D);
+int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err);  // returns dt_status
+
+// ------------------------------------------------------------------- accept (accept.hip)
+struct AcceptArgs {
+    int batch, mode;
+    float temperature;
+    const void *target;
+    int dtype, V;
+    int64_t row_stride;
+    const int32_t *n_nodes, *tokens, *parents, *depth;
+    const float *logp;
+    const unsigned long long *anc_mask;
+    int TT_cap;
+    unsigned long long seed, step;
+    int32_t *accept_len, *best_node, *path_nodes, *out_tokens, *node_argmax;
+    const unsigned long long *part_keys;  // [batch*TT_cap, S]
+    const float2 *part_ms;
+    int S;
+};
+hipError_t accept_launch(const AcceptArgs &a, hipStream_t st);
+
+}  // namespace dt

@@ -1,0 +1,93 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, sizes its workspace, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2601_12212_amd as dt
+from paper_2601_12212_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dt_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = dt.load_library()
+    names = declared_symbols()
+    assert {"dt_build_tree", "dt_tree_attention", "dt_accept", "dt_topk_rows", "dt_workspace_bytes"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings_and_limits_match_header():
+    text = open(os.path.join(ROOT, "include", "dt.h")).read()
+    for name, val in [("DT_TT_MAX", binding.DT_TT_MAX), ("DT_D_MAX", binding.DT_D_MAX), ("DT_K_MAX", binding.DT_K_MAX)]:
+        assert int(re.search(r"#define %s (\d+)" % name, text).group(1)) == val
+    assert dt.dt_status_string(0) == "ok"
+    assert "workspace" in dt.dt_status_string(-3)
+    # the caps are the maxima of the action space printed in the paper's appendix
+    gold = dict(l.split(None, 1) for l in open(os.path.join(ROOT, "tests", "golden", "action_space.txt"))
+                if not l.startswith("#"))
+    assert max(map(int, gold["TT"].split())) == binding.DT_TT_MAX
+    assert max(map(int, gold["d"].split())) == binding.DT_D_MAX
+    assert max(map(int, gold["k"].split())) == binding.DT_K_MAX
+    assert len(gold["TT"].split()) * len(gold["d"].split()) * len(gold["k"].split()) == int(gold["combinations"])
+
+
+def test_workspace_bytes():
+    small = dt.dt_workspace_bytes(1, 5, 1024, 8, 4, 64)
+    big = dt.dt_workspace_bytes(16, 16 * 85, 128256, 96, 32, 128)
+    assert 0 < small < big < (1 << 31)
+    with pytest.raises(dt.DtError) as e:
+        dt.dt_workspace_bytes(1, 5, 1024, 129, 4, 64)
+    assert e.value.status == -2
+    with pytest.raises(dt.DtError):
+        dt.dt_workspace_bytes(1, 5, 600000, 8, 4, 64)          # vocabulary beyond the row-kernel limit
+
+
+def test_bad_arguments_are_rejected_before_any_launch():
+    lib = dt.load_library()
+    one = C.c_void_p(256)       # non-null, aligned, never dereferenced on the host
+    ws = C.c_void_p(4096)
+    # null pointers
+    assert lib.dt_topk_rows(None, None, 1, 4, 1024, 1024, 4, one, one, one, ws, 1 << 20) == -1
+    # k out of range / above V
+    assert lib.dt_topk_rows(None, one, 1, 4, 1024, 1024, 0, one, one, one, ws, 1 << 20) == -2
+    assert lib.dt_topk_rows(None, one, 1, 4, 1024, 1024, 33, one, one, one, ws, 1 << 20) == -2
+    assert lib.dt_topk_rows(None, one, 1, 4, 8, 8, 9, one, one, one, ws, 1 << 20) == -2
+    # row stride shorter than the row, bad dtype
+    assert lib.dt_topk_rows(None, one, 1, 4, 1024, 1000, 4, one, one, one, ws, 1 << 20) == -1
+    assert lib.dt_topk_rows(None, one, 7, 4, 1024, 1024, 4, one, one, one, ws, 1 << 20) == -1
+    # workspace missing / too small / misaligned
+    assert lib.dt_topk_rows(None, one, 1, 4, 1024, 1024, 4, one, one, one, None, 0) == -3
+    assert lib.dt_topk_rows(None, one, 1, 4, 1024, 1024, 4, one, one, one, ws, 16) == -3
+    assert lib.dt_topk_rows(None, one, 1, 4, 1024, 1024, 4, one, one, one, C.c_void_p(4100), 1 << 20) == -3
+    # build_tree: TT_cap over the limit, null params, too few rows, small workspace
+    args = lambda **kw: [kw.get("stream"), kw.get("batch", 1), kw.get("params", one), one, 1, 1024, 1024, one,
+                         kw.get("rows", 5), one, kw.get("TT_cap", 8)] + [one] * 8 + [ws, kw.get("wsb", 1 << 24)]
+    assert lib.dt_build_tree(*args(TT_cap=129)) == -2
+    assert lib.dt_build_tree(*args(TT_cap=0)) == -2
+    assert lib.dt_build_tree(*args(params=None)) == -1
+    assert lib.dt_build_tree(*args(batch=4, rows=3)) == -1
+    assert lib.dt_build_tree(*args(wsb=64)) == -3
+    assert lib.dt_build_tree(*args(batch=0)) == 0
+    # attention: Hq not a multiple of Hkv, head dim over the limit, non-positive scale
+    att = lambda **kw: [None, 1, 1, kw.get("Hq", 32), kw.get("Hkv", 8), kw.get("D", 128), kw.get("scale", 0.1),
+                        one, one, one, one, one, one, one, 1024, 1024, 128, one, 60, one, ws, 1 << 24]
+    assert lib.dt_tree_attention(*att(Hq=30)) == -1
+    assert lib.dt_tree_attention(*att(D=256)) == -2
+    assert lib.dt_tree_attention(*att(scale=0.0)) == -1
+    # accept: bad mode, stochastic without logp or with T <= 0
+    acc = lambda **kw: [None, 1, kw.get("mode", 0), kw.get("T", 1.0), one, 1, 1024, 1024, one, one, one, one,
+                        kw.get("logp", one), one, 8, 0, 0, one, one, one, one, None, ws, kw.get("wsb", 1 << 24)]
+    assert lib.dt_accept(*acc(mode=2)) == -1
+    assert lib.dt_accept(*acc(mode=1, logp=None)) == -1
+    assert lib.dt_accept(*acc(mode=1, T=0.0)) == -1
+    assert lib.dt_accept(*acc(wsb=8)) == -3

@@ -1,0 +1,248 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bars: token ids, parents, depth, src_row, ancestor masks, arg maxes, accepted paths and output tokens are
+bit-exact; scores/log-probs within a few fp32 ulp per level; attention within max-abs 2e-2 (bf16) or
+1e-5 (fp32).
+"""
+import numpy as np
+import pytest
+
+import dt_synth
+from oracle import ref
+from tests._cases import assert_accept_equal, assert_tree_equal, make_step, oracle_case
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def dev_logits(a):
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    return torch.from_numpy(a).cuda()
+
+
+def run_topk(x, k):
+    import paper_2601_12212_amd as dt
+    R, V = x.shape
+    xd = dev_logits(x)
+    val = torch.empty((R, k), dtype=torch.float32, device="cuda")
+    idx = torch.empty((R, k), dtype=torch.int32, device="cuda")
+    lse = torch.empty(R, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(dt.dt_workspace_bytes(1, R, V, 8, 1, 64), dtype=torch.uint8, device="cuda")
+    dt.dt_topk_rows(xd, k, val, idx, lse, ws)
+    torch.cuda.synchronize()
+    return val.cpu().numpy(), idx.cpu().numpy(), lse.cpu().numpy()
+
+
+def check_topk(x, k):
+    val, idx, lse = run_topk(x, k)
+    wval, widx, wlse = ref.topk_rows(x, k)
+    assert np.array_equal(idx, widx)
+    assert np.array_equal(val, wval)
+    fin = np.isfinite(wlse)
+    assert np.array_equal(np.isneginf(lse), np.isneginf(wlse))
+    assert (np.abs(lse[fin] - wlse[fin]) <= 4e-6 * np.maximum(1.0, np.abs(wlse[fin]))).all()
+
+
+# ------------------------------------------------------------------------------------ A1 row kernels
+
+@pytest.mark.parametrize("V,k,bf16", [(1024, 2, False), (1000, 10, True), (4097, 32, True), (32000, 8, True),
+                                       (128256, 10, True), (128256, 32, True), (50001, 12, False),
+                                       (33, 32, True), (8192 * 3 + 5, 1, True)])
+def test_topk_rows_random(V, k, bf16):
+    rng = np.random.default_rng(V + k)
+    x = (rng.standard_normal((7, V)) * 3).astype(np.float32)
+    check_topk(dt_synth.f32_to_bf16_bits(x) if bf16 else x, k)
+
+
+def test_topk_rows_ties_constant_rows_and_minus_inf():
+    V = 20000
+    rng = np.random.default_rng(1)
+    x = np.zeros((6, V), np.float32)                          # row 0: all equal -> ids 0..k-1
+    x[1] = rng.integers(-2, 3, V)                             # heavy ties
+    x[2] = -np.inf; x[2, [7, 19999, 4096]] = [1.0, 1.0, 2.0]  # three viable entries
+    x[3] = -np.inf                                            # nothing viable
+    x[4] = np.arange(V)                                       # ascending: the top sits in the last chunk
+    x[5] = -np.arange(V)                                      # descending: the top sits in the first chunk
+    for k in (1, 5, 32):
+        check_topk(x, k)
+        check_topk(dt_synth.f32_to_bf16_bits(x), k)           # bf16 rounding makes rows 4/5 tie in runs
+
+
+def test_topk_rows_unaligned_row_stride_takes_the_scalar_path():
+    import paper_2601_12212_amd as dt
+    rng = np.random.default_rng(2)
+    V, stride, R, k = 5003, 5005, 4, 6
+    buf = dt_synth.f32_to_bf16_bits((rng.standard_normal((R, stride)) * 3).astype(np.float32))
+    xd = dev_logits(buf)[:, :V]
+    val = torch.empty((R, k), dtype=torch.float32, device="cuda")
+    idx = torch.empty((R, k), dtype=torch.int32, device="cuda")
+    lse = torch.empty(R, dtype=torch.float32, device="cuda")
+    ws = torch.zeros(dt.dt_workspace_bytes(1, R, V, 8, 1, 64), dtype=torch.uint8, device="cuda")
+    dt.dt_topk_rows(xd, k, val, idx, lse, ws)
+    torch.cuda.synchronize()
+    wval, widx, wlse = ref.topk_rows(np.ascontiguousarray(buf[:, :V]), k)
+    assert np.array_equal(idx.cpu().numpy(), widx) and np.array_equal(val.cpu().numpy(), wval)
+
+
+# ------------------------------------------------------------------------- whole step on the configs
+
+def check_case(case, sample_attention=None, rng_seed=0):
+    c = case.cfg
+    st = make_step(case)
+    st.run(philox_step=0)
+    torch.cuda.synchronize()
+    tol = 1e-5 if c.dtype == "f32" else 2e-2
+    for b in range(c.B):
+        tag = "%s seq %d" % (c.name, b)
+        got = st.tree(b)
+        assert_tree_equal(got, case.trees[b], tag)
+        assert_accept_equal(st.accepted(b), case.accepts[b], tag)
+        q, kt, vt, kp, vp = dt_synth.qkv(c, b)
+        N = got["n_nodes"]
+        out = st.attention_out(b)
+        if sample_attention is None:
+            want = ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, case.trees[b]["anc_mask"], st.scale)
+            err = np.abs(out - want).max()
+        else:
+            rng = np.random.default_rng(rng_seed + b)
+            samples = np.stack([rng.integers(0, N, sample_attention), rng.integers(0, c.Hq, sample_attention)], 1)
+            samples[0] = (0, 0); samples[1] = (N - 1, c.Hq - 1)
+            want = ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, case.trees[b]["anc_mask"], st.scale,
+                                      samples=samples)
+            err = max(np.abs(out[i, h] - want[r]).max() for r, (i, h) in enumerate(samples))
+        assert err <= tol, (tag, "attention max-abs", err)
+    return st
+
+
+def test_config1_tiny_fp32():
+    check_case(oracle_case(1))
+
+
+def test_config2_llama3_8b_tt60():
+    case = oracle_case(2)
+    assert case.trees[0]["n_nodes"] == 60
+    assert 0 < sum(a["accept_len"] for a in case.accepts)          # acceptance is partial, not trivial
+    check_case(case)
+
+
+def test_config3_vicuna_13b_tt64():
+    check_case(oracle_case(3), sample_attention=400)
+
+
+def test_config4_batch16_ragged():
+    case = oracle_case(4)
+    assert len({p for p in case.cfg.params}) > 8                   # really ragged
+    check_case(case, sample_attention=40)
+
+
+def test_config5_llama3_70b_stochastic():
+    case = oracle_case(5)
+    lens = [a["accept_len"] for a in case.accepts]
+    assert max(lens) > 0
+    check_case(case, sample_attention=40)
+
+
+# ------------------------------------------------------------------------------------------ edge cases
+
+def small_cfg(params, prefix_len, V=4099, dtype="bf16", Hq=8, Hkv=2, D=128, seed=0, mode=dt_synth.GREEDY):
+    return dt_synth.StepConfig("edge", dtype, Hq, Hkv, D, V, params, prefix_len, seed=seed, mode=mode)
+
+
+@pytest.mark.parametrize("params", [[(1, 3, 4)], [(2, 1, 1)], [(128, 8, 3)], [(5, 1, 9), (128, 3, 32), (17, 8, 1)],
+                                    [(64, 2, 32)], [(100, 4, 4)]])
+def test_degenerate_tree_shapes(params):
+    # TT=1 (root only), d=1 (star), k=1 (chain), pool smaller than TT (clamp), the largest k
+    cfg = small_cfg(params, [70 + 13 * i for i in range(len(params))])
+    check_case(oracle_case(0, cfg=cfg))
+
+
+def test_large_pool_uses_the_workgroup_wide_cut():
+    cfg = small_cfg([(128, 8, 16)], [40], V=2000)                # pool 16 + 7*256 = 1808 > 1024
+    check_case(oracle_case(0, cfg=cfg))
+    cfg = small_cfg([(96, 8, 32)], [33], V=1500)                 # the largest pool: 7200
+    check_case(oracle_case(0, cfg=cfg))
+
+
+def test_empty_prefix_and_tt1_decode_and_fp32_heads():
+    check_case(oracle_case(0, cfg=small_cfg([(24, 4, 3)], [0])))                     # no prefix at all
+    check_case(oracle_case(0, cfg=small_cfg([(1, 1, 1)], [300])))                    # TT=1: ordinary decode
+    check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [65], dtype="f32", D=64, Hq=4, Hkv=4)))
+    check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [65], dtype="f32", D=128, Hq=6, Hkv=2)))
+    check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [65], dtype="bf16", D=64, Hq=4, Hkv=1)))  # simple path
+
+
+def test_stochastic_small_and_many_steps():
+    cfg = small_cfg([(40, 5, 4), (64, 6, 6)], [100, 31], V=3001, mode=dt_synth.STOCHASTIC)
+    case = oracle_case(0, cfg=cfg)
+    st = check_case(case)
+    # more Philox steps on the same tree: every step must agree (margin-guarded per step)
+    agree = 0
+    for step in range(1, 40):
+        st.accept(philox_step=step)
+        torch.cuda.synchronize()
+        for b in range(cfg.B):
+            t = case.trees[b]
+            want = ref.accept(cfg.mode, case.targets[b], t["tokens"], t["parents"], t["depth"], logp=t["logp"],
+                              temperature=cfg.temperature, seed=cfg.philox_seed, step=step, seq=b)
+            if want["min_margin"] < 1e-5:
+                continue
+            assert_accept_equal(st.accepted(b), want, "step %d seq %d" % (step, b))
+            agree += 1
+    assert agree > 60
+
+
+def test_masked_vocabulary_rows():
+    """-inf logits (tokens that may never be proposed) and rows with fewer than k viable tokens."""
+    cfg = small_cfg([(20, 3, 4)], [50], V=3000)
+    drafts = dt_synth.draft_rows(cfg, 0).copy()
+    ninf = dt_synth.f32_to_bf16_bits(np.array([-np.inf], np.float32))[0]
+    drafts[:, 100:] = ninf            # only 100 tokens viable
+    drafts[2, 2:] = ninf              # this row has 2 viable tokens (k = 4)
+    drafts[3, :] = ninf               # this row has none
+    case = oracle_case(0, cfg=cfg)
+    case.drafts = [drafts]
+    t = ref.build_tree(drafts, 20, 3, 4, dt_synth.root_token(cfg, 0))
+    assert t["min_margin"] >= 1e-4
+    case.trees = [t]
+    case.targets = [dt_synth.target_rows(cfg, 0, t["src_row"], drafts)]
+    case.accepts = [ref.accept(cfg.mode, case.targets[0], t["tokens"], t["parents"], t["depth"])]
+    check_case(case)
+
+
+def test_determinism_same_inputs_same_bits():
+    case = oracle_case(2)
+    st = make_step(case)
+    st.run()
+    torch.cuda.synchronize()
+    first = [st.tokens.clone(), st.anc_mask.clone(), st.out.clone(), st.out_tokens.clone(), st.score.clone()]
+    for _ in range(5):
+        st.run()
+    torch.cuda.synchronize()
+    for a, b in zip(first, [st.tokens, st.anc_mask, st.out, st.out_tokens, st.score]):
+        assert torch.equal(a, b)
+
+
+def test_driving_the_build_level_by_level_matches_the_oracle():
+    """The call pattern of a real draft model: rows become known one level at a time."""
+    from paper_2601_12212_amd.step import Step
+    from tests._brute import toy_logits
+    from tests._drive import rows_from_fn
+    V, d, k, TT = 64, 4, 3, 30
+
+    def gpu_build(rows, TT_, d_, k_, root):
+        st = Step([(TT_, d_, k_)], [1], 4, 4, 64, V, dtype=torch.float32, TT_cap=128)
+        full = np.zeros((1 + (d_ - 1) * k_, V), np.float32)
+        full[:] = rows[: full.shape[0]]
+        st.set_draft(0, full)
+        st.set_root_token(0, root)
+        st.build_tree()
+        torch.cuda.synchronize()
+        return st.tree(0)
+
+    fn = lambda s: toy_logits(3, s, V)
+    rows_gpu = rows_from_fn(gpu_build, fn, V, d, k)
+    rows_ref = rows_from_fn(ref.build_tree, fn, V, d, k)
+    assert np.array_equal(rows_gpu, rows_ref)
+    assert_tree_equal(gpu_build(rows_gpu, TT, d, k, 7), ref.build_tree(rows_ref, TT, d, k, 7))
