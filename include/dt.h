@@ -61,6 +61,7 @@ typedef enum {
 const char *dt_status_string(int status);
 /* hipError_t of the last failing HIP call made by this library on this thread (0 if none). */
 int dt_last_hip_error(void);
+const char *dt_hip_error_string(int hip_error); /* HIP's own text for that code */
 
 /*
  * Scratch size that suffices for any of the calls below with

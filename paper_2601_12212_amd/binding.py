@@ -15,7 +15,12 @@ _lib = None
 class DtError(RuntimeError):
     def __init__(self, fn, status):
         self.status = status
-        super().__init__("%s failed: %s (%d)" % (fn, dt_status_string(status), status))
+        msg = "%s failed: %s (%d)" % (fn, dt_status_string(status), status)
+        if status == -5:
+            lib = load_library()
+            code = lib.dt_last_hip_error()
+            msg += " [hip error %d: %s]" % (code, lib.dt_hip_error_string(code).decode())
+        super().__init__(msg)
 
 
 def library_path():
@@ -34,6 +39,8 @@ def load_library():
         lib.dt_status_string.restype = C.c_char_p
         lib.dt_status_string.argtypes = [i32]
         lib.dt_last_hip_error.restype = i32
+        lib.dt_hip_error_string.restype = C.c_char_p
+        lib.dt_hip_error_string.argtypes = [i32]
         lib.dt_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, i32, C.POINTER(sz)]
         lib.dt_topk_rows.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, vp, vp, vp, sz]
         lib.dt_build_tree.argtypes = [vp, i32, vp, vp, i32, i32, i64, vp, i64, vp, i32] + [vp] * 8 + [vp, sz]

@@ -64,6 +64,7 @@ const char *dt_status_string(int s) {
 }
 
 int dt_last_hip_error(void) { return g_last_hip; }
+const char *dt_hip_error_string(int code) { return hipGetErrorString((hipError_t)code); }
 
 int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq, int D, size_t *bytes) {
     if (!bytes || batch < 0 || total_rows < 0 || Hq < 0 || D < 0) return DT_ERR_INVALID_ARG;
@@ -96,6 +97,7 @@ int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, i
     a.want_lse = 1; a.inv_t = 1.0f;
     a.part_keys = rs.keys; a.key_stride = k; a.part_ms = rs.ms;
     hipStream_t st = (hipStream_t)stream;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
     hipError_t e = dt::rows_launch_chunks(a, n_rows, nl, st);
     if (e != hipSuccess) return hip_fail(e);
     e = dt::rows_launch_merge(a, n_rows, S, top_val, top_id, lse, k, st);
@@ -129,6 +131,7 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     a.want_lse = 1; a.inv_t = 1.0f;
     a.part_keys = rs.keys; a.key_stride = DT_K_MAX; a.part_ms = rs.ms;
     hipStream_t st = (hipStream_t)stream;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
     hipError_t e = dt::rows_launch_chunks(a, total_rows, nl, st);
     if (e != hipSuccess) return hip_fail(e);
     e = dt::rows_launch_merge(a, total_rows, S, top_val, top_id, lse, DT_K_MAX, st);
@@ -168,6 +171,7 @@ int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int 
     a.anc_mask = (const unsigned long long *)anc_mask; a.TT_cap = TT_cap; a.out = out;
     a.ws = ws; a.ws_bytes = ws ? ws_bytes : 0;
     hipError_t e = hipSuccess;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
     int rc = dt::attn_launch(a, (hipStream_t)stream, &e);
     if (rc == DT_ERR_HIP) return hip_fail(e);
     return rc;
@@ -198,6 +202,7 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     a.want_lse = mode == DT_ACCEPT_STOCHASTIC; a.inv_t = mode == DT_ACCEPT_STOCHASTIC ? 1.0f / temperature : 1.0f;
     a.part_keys = rs.keys; a.key_stride = 1; a.part_ms = rs.ms;
     hipStream_t st = (hipStream_t)stream;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
     hipError_t e = dt::rows_launch_chunks(a, rows, nl, st);
     if (e != hipSuccess) return hip_fail(e);
 
