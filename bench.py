@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of one draft-tree speculative step (dt_build_tree + dt_tree_attention + dt_accept).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--copies 16] [--eager]
+
+Prints ONE JSON line: tree-verify steps/s on the Llama-3-8B-shaped configuration (TT=60, d=6,
+k=10, batch 1, bf16), the HBM roofline of the dominant kernel measured with HIP events during a
+profiled pass, and the CPU oracle timed on the host cores on the same inputs.
+
+Inputs are synthetic and resident in HBM before the timed region.  The timed loop rotates over
+`copies` distinct input sets (16 x 36 MB > the 256 MB last-level cache) so that every step
+streams its logits and KV from HBM.  By default the rotation is captured once in a HIP graph and
+replayed (the step itself is three library calls = six kernels; launch overhead would otherwise
+be most of a 35 us step); --eager times plain stream launches instead.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def step_bytes(cfg, trees_n):
+    """Algorithmic HBM bytes of one step: every logit once, prefix+tree K/V once, Q in, O out."""
+    e = cfg.elem_bytes()
+    tot = 0
+    for b in range(cfg.B):
+        N, L = trees_n[b], cfg.prefix_len[b]
+        tot += e * cfg.V * (cfg.n_rows(b) + N)
+        tot += e * 2 * cfg.Hkv * cfg.D * (L + N)
+        tot += e * 2 * N * cfg.Hq * cfg.D
+    return tot
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--copies", type=int, default=16)
+    ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-steps", type=int, default=400)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
+            "in this path). Re-run with --gpus 1." % args.gpus)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import dt_synth
+    import paper_2601_12212_amd as dt
+    from paper_2601_12212_amd.step import Step
+
+    dt.load_library()                    # no fallback: raises if the HIP library is not built
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    cfg = dt_synth.config(args.config)
+    tdtype = torch.float32 if cfg.dtype == "f32" else torch.bfloat16
+    K, W, R = args.steps, args.warmup, max(1, args.copies)
+
+    # ---- inputs: generated once on the host, uploaded into R independent buffer sets ---------
+    t0 = time.time()
+    drafts = [dt_synth.draft_rows(cfg, b) for b in range(cfg.B)]
+    steps = []
+    for r in range(R):
+        st = Step(cfg.params, cfg.prefix_len, cfg.Hq, cfg.Hkv, cfg.D, cfg.V, dtype=tdtype, mode=cfg.mode,
+                  temperature=cfg.temperature, philox_seed=cfg.philox_seed)
+        dt_synth.fill_draft_and_qkv(st, cfg, drafts)
+        steps.append(st)
+    # the target rows follow the tree (row of node i = draft row the node owns + noise): build once
+    steps[0].build_tree()
+    torch.cuda.synchronize()
+    trees = [steps[0].tree(b) for b in range(cfg.B)]
+    targets = [dt_synth.target_rows(cfg, b, trees[b]["src_row"], drafts[b]) for b in range(cfg.B)]
+    for st in steps:
+        for b in range(cfg.B):
+            st.set_target(b, targets[b])
+        st.prepare()
+    torch.cuda.synchronize()
+    n_nodes = [t["n_nodes"] for t in trees]
+    bytes_step = step_bytes(cfg, n_nodes)
+    log("setup %.1fs: %s, n_nodes=%s, %.1f MB/step, %d input copies" % (time.time() - t0, cfg.name, n_nodes,
+                                                                         bytes_step / 1e6, R))
+
+    stream = torch.cuda.current_stream()
+    sptr = stream.cuda_stream
+
+    def run_range(i0, n):
+        for i in range(i0, i0 + n):
+            steps[i % R].run_prepared(sptr, i)
+
+    # ---- timed region -----------------------------------------------------------------------------
+    mode = "eager"
+    graph = None
+    if not args.eager:
+        try:
+            run_range(0, R)                      # first touches before capture
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                gs = torch.cuda.current_stream().cuda_stream
+                for i in range(R):
+                    steps[i].run_prepared(gs, i)
+            mode = "hipgraph"
+        except Exception as ex:                  # noqa: BLE001 -- report and fall back to eager launches
+            log("HIP graph capture failed (%s); timing eager launches" % ex)
+            graph = None
+    if graph is not None:
+        K = max(R, (K // R) * R)                 # whole replays
+        W = max(R, (W // R) * R)
+        for _ in range(W // R):
+            graph.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(K // R):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    else:
+        run_range(0, W)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        run_range(W, K)
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / K
+    dev_ms_per_step = e0.elapsed_time(e1) / K
+    steps_per_s = K / wall
+
+    # ---- eager reference number (always) and per-kernel durations with HIP events --------------
+    n_e = min(K, 500)
+    run_range(0, min(W, 50))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_range(0, n_e)
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) * 1e3 / n_e
+
+    P = max(R, args.profile_steps)
+    dt.dt_profile_enable(P * 8)
+    run_range(0, P)
+    torch.cuda.synchronize()
+    kern = {}
+    for kid in range(7):
+        name, ms, n = dt.dt_profile_read(kid)
+        if n:
+            kern[name] = dict(avg_us=ms * 1e3 / n, launches_per_step=n / P)
+    dt.dt_profile_enable(0)
+    e = cfg.elem_bytes()
+    kbytes = {"rows_target_chunk": e * cfg.V * sum(n_nodes),
+              "rows_draft_chunk": e * cfg.V * sum(cfg.n_rows(b) for b in range(cfg.B)),
+              "attention": sum(e * 2 * cfg.Hkv * cfg.D * (cfg.prefix_len[b] + n_nodes[b]) +
+                               e * 2 * n_nodes[b] * cfg.Hq * cfg.D for b in range(cfg.B))}
+    for name, v in kern.items():
+        if name in kbytes:
+            v["bytes"] = kbytes[name]
+            v["gbps"] = kbytes[name] / (v["avg_us"] * 1e-6) / 1e9
+        log("  kernel %-20s avg %8.2f us  x%.0f/step%s" % (name, v["avg_us"], v["launches_per_step"],
+                                                            "  %.0f GB/s" % v["gbps"] if "gbps" in v else ""))
+    dom = max((n for n in kern if n in kbytes), key=lambda n: kern[n]["avg_us"] * kern[n]["launches_per_step"])
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(kern[dom]["gbps"], 1), "peak": HBM_PEAK_GBPS,
+                "unit": "GB/s", "frac": round(kern[dom]["gbps"] / HBM_PEAK_GBPS, 4), "traffic": None,
+                "bytes_per_launch": kbytes[dom], "avg_us": round(kern[dom]["avg_us"], 3),
+                "timing": "HIP events around each launch, %d profiled steps, inputs rotated" % P}
+
+    # ---- the oracle on the host cores, same inputs -------------------------------------------------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ref
+        threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+        done, t_start = 0, time.perf_counter()
+        ok = True
+        while done < 8 and (time.perf_counter() - t_start) < 10.0:
+            for b in range(cfg.B):
+                TT, d, k = cfg.params[b]
+                t = ref.build_tree(drafts[b], TT, d, k, dt_synth.root_token(cfg, b))
+                ok = ok and np.array_equal(t["src_row"], trees[b]["src_row"])
+                q, kt, vt, kp, vp = dt_synth.qkv(cfg, b)
+                N = t["n_nodes"]
+                ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, t["anc_mask"], 1.0 / float(np.sqrt(cfg.D)))
+                tg = dt_synth.target_rows(cfg, b, t["src_row"], drafts[b]) if done == 0 else targets[b]
+                ref.accept(cfg.mode, tg, t["tokens"], t["parents"], t["depth"], logp=t["logp"],
+                           temperature=cfg.temperature, seed=cfg.philox_seed, step=done, seq=b)
+            done += 1
+        cpu_s = (time.perf_counter() - t_start) / done
+        cpu = {"value": round(1.0 / cpu_s, 4), "unit": "steps/s", "cores": threads, "kind": "oracle",
+               "sample": "%d whole steps of the same workload (tree build single-threaded, attention and "
+                         "row scans OpenMP over %d threads; includes regenerating inputs once)" % (done, threads),
+               "same_tree_as_gpu": bool(ok)}
+        log("cpu oracle: %.3f s/step on %d threads" % (cpu_s, threads))
+
+    out = {
+        "metric": "tree_verify_steps_per_sec", "value": round(steps_per_s, 1), "unit": "steps/s",
+        "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": "%s: Hq=%d Hkv=%d D=%d V=%d prefix=%s (TT,d,k)=%s batch=%d, one layer's attention"
+                               % (cfg.name, cfg.Hq, cfg.Hkv, cfg.D, cfg.V, cfg.prefix_len[:4], cfg.params[:4], cfg.B),
+                   "launch": mode, "input_copies": R, "n_nodes": n_nodes},
+        "device_ms_per_step": round(dev_ms_per_step, 5),
+        "eager_ms_per_step": round(eager_ms, 5),
+        "bytes_per_step": bytes_step,
+        "hbm_gbps_step": round(bytes_step / (ms_per_step * 1e-3) / 1e9, 1),
+        "pct_hbm_peak_step": round(100.0 * bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+        "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()}
+                    for k, v in kern.items()},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -50,28 +50,28 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     __shared__ double s_wtot[4];
     __shared__ int s_bonus;
 
-    // ---- merge the row partials ------------------------------------------------------------
-    if (tid < N) {
-        const int64_t g = o + tid;
-        u64 best = 0ull;
-        for (int c = 0; c < a.S; ++c) {
-            u64 key = a.part_keys[g * a.S + c];
-            best = key > best ? key : best;
-        }
-        s_amax[tid] = (int)key_idx(best);
-        s_rowmax[tid] = key_val(best);
-        if (a.node_argmax) a.node_argmax[g] = (int)key_idx(best);
-        if (stochastic) {
-            const float cexp = 1.4426950408889634f * inv_t;
-            float M = -INFINITY, S = 0.f;
-            for (int c = 0; c < a.S; ++c) {
-                float2 p = a.part_ms[g * a.S + c];
-                float M2 = fmaxf(M, p.x);
-                if (M2 != -INFINITY)
-                    S = S * __builtin_amdgcn_exp2f((M - M2) * cexp) + p.y * __builtin_amdgcn_exp2f((p.x - M2) * cexp);
-                M = M2;
+    // ---- merge the row partials: wave w takes rows w, w+4, ...; lane c holds chunk c (S <= 64) --
+    {
+        const float cexp = 1.4426950408889634f * inv_t;
+#pragma unroll 4
+        for (int i = w; i < N; i += 4) {
+            const int64_t g = o + i;
+            const u64 key = lane < a.S ? a.part_keys[g * a.S + lane] : 0ull;
+            const u64 best = wave_max_u64(key);
+            float lse_i = 0.f;
+            if (stochastic) {
+                float2 p = lane < a.S ? a.part_ms[g * a.S + lane] : make_float2(-INFINITY, 0.f);
+                const float M = wave_max(p.x);
+                const float Mu = M == -INFINITY ? 0.f : M;
+                const float term = p.y > 0.f ? p.y * __builtin_amdgcn_exp2f((p.x - Mu) * cexp) : 0.f;
+                lse_i = M * inv_t + __logf(wave_sum(term));
             }
-            s_lse[tid] = M * inv_t + __logf(S);
+            if (lane == 0) {
+                s_amax[i] = (int)key_idx(best);
+                s_rowmax[i] = key_val(best);
+                s_lse[i] = lse_i;
+                if (a.node_argmax) a.node_argmax[g] = (int)key_idx(best);
+            }
         }
     }
     if (tid < 2) s_acc[tid] = 0ull;

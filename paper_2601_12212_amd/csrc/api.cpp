@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <cstdlib>
 
 #include "kernels.hpp"
 
@@ -22,25 +23,40 @@ inline int min_nl(int V) {
 }
 inline int pick_nl(int64_t n_rows, int V) {
     int a = dt::rows_pick_nl(n_rows, V), b = min_nl(V);
+#ifdef DT_TIMESTAMPS
+    if (const char *e = getenv("DT_NL")) a = atoi(e);
+#endif
     return a > b ? a : b;
 }
 inline int max_chunks(int V) { return dt::rows_chunks_per_row(V, min_nl(V)); }
 
-struct RowScratch {
+struct ArgmaxScratch {  // arg max rows: [rows, S] keys, [rows, S] (max, sum) pairs
     unsigned long long *keys;
     float2 *ms;
     size_t bytes;
 };
-// [rows, S, key_stride] keys followed by [rows, S] (max, sum) pairs
-inline RowScratch row_scratch(void *ws, int64_t rows, int S, int key_stride) {
-    RowScratch r;
-    size_t kb = align_up((size_t)rows * S * key_stride * 8);
-    size_t mb = align_up((size_t)rows * S * 8);
+inline ArgmaxScratch argmax_scratch(void *ws, int64_t rows, int S) {
+    ArgmaxScratch r;
+    size_t kb = align_up((size_t)rows * S * 8);
     r.keys = (unsigned long long *)ws;
     r.ms = (float2 *)((char *)ws + kb);
-    r.bytes = kb + mb;
+    r.bytes = kb + align_up((size_t)rows * S * 8);
     return r;
 }
+struct TopkScratch {  // top-k rows: [rows, S*256] lane maxima, [rows, S*4] (max, sum) pairs
+    float *lane_max;
+    float2 *ms;
+    size_t bytes;
+};
+inline TopkScratch topk_scratch(void *ws, int64_t rows, int S) {
+    TopkScratch r;
+    size_t lb = align_up((size_t)rows * S * 256 * 4);
+    r.lane_max = (float *)ws;
+    r.ms = (float2 *)((char *)ws + lb);
+    r.bytes = lb + align_up((size_t)rows * S * 4 * 8);
+    return r;
+}
+inline bool topk_v_ok(int V) { return V >= 1 && dt::rows_chunks_per_row(V, dt::rows_topk_nl(V)) <= 64; }
 
 inline int hip_fail(hipError_t e) {
     g_last_hip = (int)e;
@@ -68,12 +84,13 @@ const char *dt_hip_error_string(int code) { return hipGetErrorString((hipError_t
 
 int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq, int D, size_t *bytes) {
     if (!bytes || batch < 0 || total_rows < 0 || Hq < 0 || D < 0) return DT_ERR_INVALID_ARG;
-    if (V < 1 || TT_cap < 1 || TT_cap > DT_TT_MAX || min_nl(V) == 0) return DT_ERR_LIMIT;
+    if (V < 1 || TT_cap < 1 || TT_cap > DT_TT_MAX || min_nl(V) == 0 || !topk_v_ok(V)) return DT_ERR_LIMIT;
     const int S = max_chunks(V);
-    // build: row partials (k slots each) + merged top-k (values, ids) + lse
-    size_t build = row_scratch(nullptr, total_rows, S, DT_K_MAX).bytes + 2 * align_up((size_t)total_rows * DT_K_MAX * 4) +
+    const int St = dt::rows_chunks_per_row(V, dt::rows_topk_nl(V));
+    // build: lane maxima + (max, sum) partials + merged top-k (values, ids) + lse
+    size_t build = topk_scratch(nullptr, total_rows, St).bytes + 2 * align_up((size_t)total_rows * DT_K_MAX * 4) +
                    align_up((size_t)total_rows * 4);
-    size_t accept = row_scratch(nullptr, (int64_t)batch * TT_cap, S, 1).bytes;
+    size_t accept = argmax_scratch(nullptr, (int64_t)batch * TT_cap, S).bytes;
     size_t attn = dt::attn_workspace_bytes(batch, TT_cap, Hq, D);
     size_t m = build > accept ? build : accept;
     m = m > attn ? m : attn;
@@ -85,22 +102,22 @@ int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, i
                  float *top_val, int32_t *top_id, float *lse, void *ws, size_t ws_bytes) {
     if (!logits || !top_val || !top_id || !lse || n_rows < 0 || bad_dtype(t) || row_stride < V)
         return DT_ERR_INVALID_ARG;
-    if (V < 1 || min_nl(V) == 0 || k < 1 || k > DT_K_MAX || k > V) return DT_ERR_LIMIT;
+    if (!topk_v_ok(V) || k < 1 || k > DT_K_MAX || k > V) return DT_ERR_LIMIT;
     if (n_rows == 0) return DT_OK;
-    const int nl = pick_nl(n_rows, V), S = dt::rows_chunks_per_row(V, nl);
+    const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
-    RowScratch rs = row_scratch(ws, n_rows, S, k);
+    TopkScratch rs = topk_scratch(ws, n_rows, S);
     if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
     dt::RowArgs a = {};
     a.logits = logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
     a.mode = dt::ROWS_UNIFORM; a.k_uniform = k;
     a.want_lse = 1; a.inv_t = 1.0f;
-    a.part_keys = rs.keys; a.key_stride = k; a.part_ms = rs.ms;
+    a.lane_max = rs.lane_max; a.part_ms = rs.ms;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
-    hipError_t e = dt::rows_launch_chunks(a, n_rows, nl, st);
+    hipError_t e = dt::rows_launch_stream(a, n_rows, nl, st);
     if (e != hipSuccess) return hip_fail(e);
-    e = dt::rows_launch_merge(a, n_rows, S, top_val, top_id, lse, k, st);
+    e = dt::rows_launch_select(a, n_rows, nl, top_val, top_id, lse, k, st);
     if (e != hipSuccess) return hip_fail(e);
     return DT_OK;
 }
@@ -114,11 +131,11 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     if (!params || !draft_logits || !row_off || !root_token || !n_nodes || !tokens || !parents || !depth ||
         !score || !logp || !src_row || !anc_mask || row_stride < V)
         return DT_ERR_INVALID_ARG;
-    if (V < 1 || min_nl(V) == 0 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
+    if (!topk_v_ok(V) || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
     if (total_rows < batch) return DT_ERR_INVALID_ARG;  // every sequence owns at least its root row
-    const int nl = pick_nl(total_rows, V), S = dt::rows_chunks_per_row(V, nl);
+    const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
-    RowScratch rs = row_scratch(ws, total_rows, S, DT_K_MAX);
+    TopkScratch rs = topk_scratch(ws, total_rows, S);
     size_t off = rs.bytes;
     float *top_val = (float *)((char *)ws + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
     int32_t *top_id = (int32_t *)((char *)ws + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
@@ -129,12 +146,12 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     a.logits = draft_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
     a.mode = dt::ROWS_DRAFT; a.batch = batch; a.params = params; a.row_off = row_off; a.TT_cap = TT_cap;
     a.want_lse = 1; a.inv_t = 1.0f;
-    a.part_keys = rs.keys; a.key_stride = DT_K_MAX; a.part_ms = rs.ms;
+    a.lane_max = rs.lane_max; a.part_ms = rs.ms;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
-    hipError_t e = dt::rows_launch_chunks(a, total_rows, nl, st);
+    hipError_t e = dt::rows_launch_stream(a, total_rows, nl, st);
     if (e != hipSuccess) return hip_fail(e);
-    e = dt::rows_launch_merge(a, total_rows, S, top_val, top_id, lse, DT_K_MAX, st);
+    e = dt::rows_launch_select(a, total_rows, nl, top_val, top_id, lse, DT_K_MAX, st);
     if (e != hipSuccess) return hip_fail(e);
 
     dt::TreeArgs ta = {};
@@ -193,17 +210,17 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     const int64_t rows = (int64_t)batch * TT_cap;
     const int nl = pick_nl(rows, V), S = dt::rows_chunks_per_row(V, nl);
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
-    RowScratch rs = row_scratch(ws, rows, S, 1);
+    ArgmaxScratch rs = argmax_scratch(ws, rows, S);
     if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
 
     dt::RowArgs a = {};
     a.logits = target_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
     a.mode = dt::ROWS_TARGET; a.batch = batch; a.TT_cap = TT_cap; a.n_nodes = n_nodes;
     a.want_lse = mode == DT_ACCEPT_STOCHASTIC; a.inv_t = mode == DT_ACCEPT_STOCHASTIC ? 1.0f / temperature : 1.0f;
-    a.part_keys = rs.keys; a.key_stride = 1; a.part_ms = rs.ms;
+    a.part_keys = rs.keys; a.part_ms = rs.ms;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
-    hipError_t e = dt::rows_launch_chunks(a, rows, nl, st);
+    hipError_t e = dt::rows_launch_argmax(a, rows, nl, st);
     if (e != hipSuccess) return hip_fail(e);
 
     dt::AcceptArgs aa = {};

@@ -39,27 +39,53 @@ __device__ __forceinline__ u32 lanes_below(u64 mask) {  // number of set bits of
     return __builtin_amdgcn_mbcnt_hi((u32)(mask >> 32), __builtin_amdgcn_mbcnt_lo((u32)mask, 0u));
 }
 
+// Wave-wide reductions with DPP row shifts and row broadcasts: six VALU steps, no LDS
+// traffic.  The total lands in lane 63 and is broadcast from there, so the result is uniform.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_mov(int ident, int v) {
+    return __builtin_amdgcn_update_dpp(ident, v, CTRL, ROW_MASK, 0xf, false);
+}
+#define DT_DPP_REDUCE(v, ident, OP, TO_I, FROM_I)                          \
+    v = OP(v, FROM_I(dpp_mov<0x111, 0xf>(TO_I(ident), TO_I(v))));          \
+    v = OP(v, FROM_I(dpp_mov<0x112, 0xf>(TO_I(ident), TO_I(v))));          \
+    v = OP(v, FROM_I(dpp_mov<0x114, 0xf>(TO_I(ident), TO_I(v))));          \
+    v = OP(v, FROM_I(dpp_mov<0x118, 0xf>(TO_I(ident), TO_I(v))));          \
+    v = OP(v, FROM_I(dpp_mov<0x142, 0xa>(TO_I(ident), TO_I(v))));          \
+    v = OP(v, FROM_I(dpp_mov<0x143, 0xc>(TO_I(ident), TO_I(v))));
+
+__device__ __forceinline__ float f_add(float a, float b) { return a + b; }
+__device__ __forceinline__ u32 u_max(u32 a, u32 b) { return a > b ? a : b; }
+__device__ __forceinline__ int i_max(int a, int b) { return a > b ? a : b; }
+__device__ __forceinline__ int i_add(int a, int b) { return a + b; }
+__device__ __forceinline__ int id_i(int x) { return x; }
+__device__ __forceinline__ int u2i(u32 x) { return (int)x; }
+__device__ __forceinline__ u32 i2u(int x) { return (u32)x; }
+
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
+    DT_DPP_REDUCE(v, -INFINITY, fmaxf, __float_as_int, __int_as_float)
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+    DT_DPP_REDUCE(v, 0.f, f_add, __float_as_int, __int_as_float)
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
 }
-__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int o) {
-    u32 lo = __shfl_xor((u32)v, o, 64), hi = __shfl_xor((u32)(v >> 32), o, 64);
-    return ((u64)hi << 32) | lo;
+__device__ __forceinline__ u32 wave_max_u32(u32 v) {
+    DT_DPP_REDUCE(v, 0u, u_max, u2i, i2u)
+    return (u32)__builtin_amdgcn_readlane((int)v, 63);
 }
+__device__ __forceinline__ int wave_max_i32(int v) {
+    DT_DPP_REDUCE(v, (int)0x80000000, i_max, id_i, id_i)
+    return __builtin_amdgcn_readlane(v, 63);
+}
+__device__ __forceinline__ int wave_sum_i32(int v) {
+    DT_DPP_REDUCE(v, 0, i_add, id_i, id_i)
+    return __builtin_amdgcn_readlane(v, 63);
+}
+// 64-bit maximum: the high words first, then the low words of the lanes that hold that high word.
 __device__ __forceinline__ u64 wave_max_u64(u64 v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        u64 w = shfl_xor_u64(v, o);
-        v = w > v ? w : v;
-    }
-    return v;
+    const u32 hi = wave_max_u32((u32)(v >> 32));
+    const u32 lo = wave_max_u32((u32)(v >> 32) == hi ? (u32)v : 0u);
+    return ((u64)hi << 32) | lo;
 }
 __device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
     u32 lo = __builtin_amdgcn_readlane((u32)v, lane), hi = __builtin_amdgcn_readlane((u32)(v >> 32), lane);

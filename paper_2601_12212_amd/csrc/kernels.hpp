@@ -38,16 +38,18 @@ struct RowArgs {
     const int32_t *n_nodes;  // ROWS_TARGET
     int want_lse;
     float inv_t;          // 1 / temperature applied inside the exponentials
-    unsigned long long *part_keys;  // [rows, S, key_stride]
-    int key_stride;
-    float2 *part_ms;      // [rows, S] (max, sum exp((x-max)*inv_t))
+    unsigned long long *part_keys;  // arg max rows: [rows, S] best key of every chunk
+    float *lane_max;      // top-k rows: [rows, S*256] one maximum per lane
+    float2 *part_ms;      // (max, sum exp((x-max)*inv_t)): [rows, S] (arg max rows), [rows, S*4] (top-k rows)
 };
 
-int rows_pick_nl(int64_t n_rows, int V);
 int rows_chunks_per_row(int V, int nl);
-hipError_t rows_launch_chunks(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st);
-hipError_t rows_launch_merge(const RowArgs &a, int64_t n_rows, int S, float *top_val, int32_t *top_id, float *lse,
-                             int out_stride, hipStream_t st);
+int rows_topk_nl(int V);                    // chunk multiplier of the top-k passes
+int rows_pick_nl(int64_t n_rows, int V);    // chunk multiplier of the arg max pass
+hipError_t rows_launch_stream(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st);
+hipError_t rows_launch_select(const RowArgs &a, int64_t n_rows, int nl, float *top_val, int32_t *top_id, float *lse,
+                              int out_stride, hipStream_t st);
+hipError_t rows_launch_argmax(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st);
 
 // ------------------------------------------------------------------ tree kernel (tree.hip)
 struct TreeArgs {

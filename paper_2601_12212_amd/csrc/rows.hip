@@ -1,13 +1,13 @@
 // Row kernels: top-k and log-sum-exp over vocabulary rows (draft rows: k best + lse;
 // target rows: arg max, and lse of row/T for stochastic acceptance).
 //
-// A row is cut into chunks of 256*8*NL elements; one workgroup reduces one chunk held
-// entirely in registers (one coalesced 16-byte load per lane per 8 bf16 elements), and a
-// second small kernel merges the per-chunk partials of a row.  Selection is exact under
-// the total order (value desc, id asc): the k-th largest lane maximum bounds the k-th
-// largest element from below, elements at or above that bound are ranked by their 64-bit
-// (value, id) keys; a slow exact path covers rows with so many ties that the candidate
-// list overflows.
+// Top-k rows take two passes.  The first is a pure stream: a row is cut into chunks of
+// 256*8*NL elements, each lane reads 8*NL of them with coalesced 16-byte loads and leaves
+// only its maximum (plus one (max, sum-exp) pair per wave).  The second works on those lane
+// maxima, 8*NL times fewer than the logits: the k-th largest lane maximum bounds the k-th
+// largest element from below, so only the ~k lanes that reach it are read again and their
+// elements ranked by 64-bit (value, id) keys -- exact under (value desc, id asc).  Rows
+// dominated by ties fall back to a slow exact loop.
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -44,27 +44,15 @@ __device__ __forceinline__ RowMeta row_meta(const RowArgs &a, int64_t g) {
     return m;
 }
 
-// ---------------------------------------------- rank a short LDS list, keep the k best --
-// list[0..n) distinct keys, n <= 64*IPL.  The key of rank r < k is handed to emit(r, key).
-template <int IPL, typename Emit>
-__device__ __forceinline__ void rank_emit(const u64 *list, int n, int k, Emit emit) {
-    const int lane = lane_id();
-    u64 mine[IPL];
-    int rank[IPL];
-#pragma unroll
-    for (int q = 0; q < IPL; ++q) {
-        int i = lane + 64 * q;
-        mine[q] = i < n ? list[i] : 0ull;
-        rank[q] = 0;
-    }
-    for (int i = 0; i < n; ++i) {
-        u64 o = list[i];  // same address in every lane: LDS broadcast
-#pragma unroll
-        for (int q = 0; q < IPL; ++q) rank[q] += (o > mine[q]) ? 1 : 0;
-    }
-#pragma unroll
-    for (int q = 0; q < IPL; ++q)
-        if (lane + 64 * q < n && rank[q] < k) emit(rank[q], mine[q]);
+// ------------------------------------------------- rank at most 64 keys, keep the k best --
+// Keys are held one per lane (lanes >= n hold 0) and are distinct.  Each lane ranks its key by
+// comparing against every lane's key through readlane: no LDS traffic, no wait inside the loop.
+// The key of rank r < k is handed to emit(r, key).
+template <typename Emit>
+__device__ __forceinline__ void rank_emit_lanes(u64 mine, int n, int k, Emit emit) {
+    int rank = 0;
+    for (int i = 0; i < n; ++i) rank += (readlane_u64(mine, i) > mine) ? 1 : 0;
+    if (lane_id() < n && rank < k) emit(rank, mine);
 }
 
 // k-th largest of one 32-bit key per lane (k <= 64), by bitwise bisection over ballots.
@@ -81,28 +69,12 @@ __device__ __forceinline__ u32 wave_kth_largest(u32 key, int k) {
     return t;
 }
 
-// ------------------------------------------------------------------- chunk kernel -----
-// LDS per workgroup: candidate lists (4 waves x 64), wave results (4 x 32), merge list (128).
+// -------------------------------------------------------------------- chunk loading -----
+// Element (n, e) of a lane, n < NL, e < 8, has id = base + n*512 + e with
+// base = chunk*256*8*NL + wave*64*8*NL + lane*8: one coalesced 16-byte load per (lane, n).
 template <int NL, bool BF16, bool VEC>
-__global__ __launch_bounds__(256) void row_chunk_kernel(RowArgs a) {
-    constexpr int E = 8 * NL;
-    constexpr int CH = 256 * E;
-    const int64_t g = blockIdx.y;
-    const int c = blockIdx.x;
-    const RowMeta meta = row_meta(a, g);
-    if (!meta.valid) return;
-    const int k = meta.k;
-    const int lane = lane_id(), w = threadIdx.x >> 6;
+__device__ __forceinline__ void load_chunk(const RowArgs &a, int64_t g, int base, float (&x)[8 * NL]) {
     const int V = a.V;
-
-    __shared__ u64 s_cand[4][64];
-    __shared__ u64 s_wout[4][DT_K_MAX];
-    __shared__ u64 s_merge[128];
-    __shared__ float s_m[4], s_s[4];
-
-    // ---- load the chunk: element (n, e) of this lane has id = base + n*512 + e ----------
-    const int base = c * CH + w * (64 * E) + lane * 8;
-    float x[E];
     if (BF16) {
         const uint16_t *row = (const uint16_t *)a.logits + g * a.row_stride;
 #pragma unroll
@@ -137,139 +109,90 @@ __global__ __launch_bounds__(256) void row_chunk_kernel(RowArgs a) {
             }
         }
     }
+}
 
-    // ---- lane maximum -----------------------------------------------------------------------
+// (max, sum of exp((x - max) * inv_t)) of a wave's elements, from the lane maxima.
+template <int E>
+__device__ __forceinline__ float2 wave_lse_partial(const float (&x)[E], float mx, float inv_t) {
+    const float cexp = 1.4426950408889634f * inv_t;
+    const float mref = mx == -INFINITY ? 0.f : mx;
+    const float nm = -mref * cexp;
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < E; ++j) s += __builtin_amdgcn_exp2f(fmaf(x[j], cexp, nm));
+    const float M = wave_max(mx);
+    const float Mref = M == -INFINITY ? 0.f : M;
+    float term = s > 0.f ? s * __builtin_amdgcn_exp2f((mref - Mref) * cexp) : 0.f;
+    return make_float2(M, wave_sum(term));
+}
+
+// ------------------------------------------------------------ streaming kernel (top-k rows) --
+// Pure stream: every wave reads its 64*8*NL elements once and leaves behind one maximum per
+// lane and one (max, sum) pair per wave.  No LDS, no barrier.  All selection happens later on
+// the lane maxima, which are 8*NL times fewer than the logits.
+template <int NL, bool BF16, bool VEC>
+__global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
+    constexpr int E = 8 * NL;
+    const int64_t g = blockIdx.y;
+    const int c = blockIdx.x;
+    const RowMeta meta = row_meta(a, g);
+    if (!meta.valid) return;
+    const int lane = lane_id(), w = threadIdx.x >> 6;
+    const int base = c * (256 * E) + w * (64 * E) + lane * 8;
+    float x[E];
+    load_chunk<NL, BF16, VEC>(a, g, base, x);
     float mx = x[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
-
-    // ---- partial log-sum-exp of x * inv_t, relative to the lane maximum -------------------
+    const int64_t wslot = (g * gridDim.x + c) * 4 + w;
+    a.lane_max[wslot * 64 + lane] = mx;
     if (a.want_lse) {
-        const float cexp = 1.4426950408889634f * a.inv_t;
-        const float mref = mx == -INFINITY ? 0.f : mx;
-        const float nm = -mref * cexp;
-        float s = 0.f;
-#pragma unroll
-        for (int j = 0; j < E; ++j) s += __builtin_amdgcn_exp2f(fmaf(x[j], cexp, nm));
-        const float M = wave_max(mx);
-        const float Mref = M == -INFINITY ? 0.f : M;
-        float term = s > 0.f ? s * __builtin_amdgcn_exp2f((mref - Mref) * cexp) : 0.f;
-        term = wave_sum(term);
-        if (lane == 0) { s_m[w] = M; s_s[w] = term; }
-    }
-
-    // ---- wave-level exact top-k ---------------------------------------------------------------
-    float T;
-    if (k == 1) {
-        T = wave_max(mx);
-    } else {
-        T = unord32(wave_kth_largest<BF16 ? 16 : 0>(ord32(mx), k));
-    }
-    int n_c = 0;
-#pragma unroll
-    for (int j = 0; j < E; ++j) {
-        const bool hit = x[j] >= T;
-        const u64 m = __ballot(hit);
-        if (m) {
-            if (hit) {
-                int slot = n_c + (int)lanes_below(m);
-                if (slot < 64) s_cand[w][slot] = make_key(x[j], (u32)(base + (j >> 3) * 512 + (j & 7)));
-            }
-            n_c += __popcll(m);
-        }
-    }
-    if (n_c <= 64) {
-        u64 *wout = s_wout[w];
-        rank_emit<1>(s_cand[w], n_c, k, [&](int r, u64 key) { wout[r] = key; });
-    } else {
-        // too many elements tie with the bound: k rounds of exact extract-max
-        u64 prev = ~0ull;
-        for (int r = 0; r < k; ++r) {
-            u64 best = 0ull;
-#pragma unroll
-            for (int j = 0; j < E; ++j) {
-                u64 key = make_key(x[j], (u32)(base + (j >> 3) * 512 + (j & 7)));
-                if (key < prev && key > best) best = key;
-            }
-            best = wave_max_u64(best);
-            if (lane == 0) s_wout[w][r] = best;
-            prev = best;
-        }
-    }
-    __syncthreads();
-
-    // ---- workgroup merge by wave 0, partial results to scratch ----------------------------
-    if (w == 0) {
-        const int64_t slot = g * gridDim.x + c;
-        u64 *out = a.part_keys + slot * a.key_stride;
-        if (k == 1) {
-            u64 best = lane < 4 ? s_wout[lane][0] : 0ull;
-            best = wave_max_u64(best);
-            if (lane == 0) out[0] = best;
-        } else {
-            u64 bound = lane < 4 ? s_wout[lane][k - 1] : 0ull;
-            bound = wave_max_u64(bound);  // the best wave's k-th key: at least k keys are >= it
-            int n = 0;
-#pragma unroll
-            for (int q = 0; q < 2; ++q) {
-                int i = lane + 64 * q;
-                u64 key = i < 4 * k ? s_wout[i / k][i % k] : 0ull;
-                bool hit = i < 4 * k && key >= bound;
-                u64 m = __ballot(hit);
-                if (hit) s_merge[n + (int)lanes_below(m)] = key;
-                n += __popcll(m);
-            }
-            rank_emit<2>(s_merge, n, k, [&](int r, u64 key) { out[r] = key; });
-        }
-        if (a.want_lse && lane == 0) {
-            float M = s_m[0], S = s_s[0];
-#pragma unroll
-            for (int q = 1; q < 4; ++q) {
-                float M2 = fmaxf(M, s_m[q]);
-                if (M2 != -INFINITY) {
-                    const float cexp = 1.4426950408889634f * a.inv_t;
-                    S = S * __builtin_amdgcn_exp2f((M - M2) * cexp) + s_s[q] * __builtin_amdgcn_exp2f((s_m[q] - M2) * cexp);
-                }
-                M = M2;
-            }
-            a.part_ms[slot] = make_float2(M, S);
-        }
+        const float2 p = wave_lse_partial<E>(x, mx, a.inv_t);
+        if (lane == 0) a.part_ms[wslot] = p;
     }
 }
 
-// -------------------------------------------------------------------- merge kernel ------
-// One wave per row: merge the S per-chunk lists (each k keys, best first) into the row's
-// top-k, and the S (max, sum) pairs into the row's log-sum-exp.  S <= 64.
-__global__ __launch_bounds__(64) void row_merge_kernel(RowArgs a, int S, float *top_val, int32_t *top_id,
-                                                       float *lse, int out_stride) {
+// ------------------------------------------------------------- selection kernel (top-k rows) --
+// One workgroup per row, working on the row's S*256 lane maxima:
+//   1. every thread takes the maximum of its S lane maxima; each wave finds the k-th largest of
+//      its 64 thread maxima (ballot bisection); the largest of the four is a lower bound T0 of
+//      the row's k-th largest lane maximum;
+//   2. lane maxima >= T0 (a few dozen) are compacted; their k-th largest, T, is a lower bound
+//      of the row's k-th largest ELEMENT, and only lanes whose maximum reaches T ("hot" lanes,
+//      about k of them) can hold a winner;
+//   3. the hot lanes' 8*NL elements are read again (they sit in L2), elements >= T are keyed
+//      by (value, id) and ranked.
+// Any overflow of the small lists (rows dominated by ties, fewer than k finite entries)
+// switches to an exact but slow extract-max loop over the whole row.
+__device__ __forceinline__ float load_elem(const RowArgs &a, int64_t g, int id) {
+    if (a.dtype == DT_BF16) return bf16_bits_to_float(((const uint16_t *)a.logits)[g * a.row_stride + id]);
+    return ((const float *)a.logits)[g * a.row_stride + id];
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int S, float *top_val, int32_t *top_id,
+                                                         float *lse, int out_stride) {
     const int64_t g = blockIdx.x;
     const RowMeta meta = row_meta(a, g);
     if (!meta.valid) return;
-    const int k = meta.k, lane = lane_id();
-    const u64 *lists = a.part_keys + g * S * a.key_stride;
-    __shared__ u64 s_all[64 * DT_K_MAX];  // list c at [c*k, c*k+k)
-    __shared__ u64 s_list[256];
+    const int k = meta.k, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+    const int V = a.V, E = 8 * nl;
+    const int n_lanes = S * 256;
+    const float *lm = a.lane_max + g * n_lanes;
 
-    const int n_items = S * k;
-    for (int i = lane; i < n_items; i += 64) s_all[i] = lists[(i / k) * a.key_stride + (i % k)];
-
-    if (a.want_lse && lse) {
-        const float cexp = 1.4426950408889634f * a.inv_t;
-        float M = -INFINITY, Ssum = 0.f;
-        if (lane < S) {
-            float2 p = a.part_ms[g * S + lane];
-            M = p.x;
-            Ssum = p.y;
-        }
-        const float Mw = wave_max(M);
-        float term = (Ssum > 0.f) ? Ssum * __builtin_amdgcn_exp2f((M - Mw) * cexp) : 0.f;
-        term = wave_sum(term);
-        if (lane == 0) lse[g] = (Mw == -INFINITY) ? -INFINITY : Mw * a.inv_t + __logf(term);
-    }
+    __shared__ float s_T[4];
+    __shared__ float s_c1v[4][64];
+    __shared__ int s_c1l[4][64];
+    __shared__ int s_c1n[4];
+    __shared__ int s_hot[64];
+    __shared__ int s_h;
+    __shared__ float s_Trow;
+    __shared__ u64 s_fin[64];
+    __shared__ int s_n2;
+    __shared__ u64 s_best[4];
 
     float *tv = top_val + g * out_stride;
     int32_t *ti = top_id ? top_id + g * out_stride : nullptr;
-    const int V = a.V;
     auto emit = [&](int r, u64 key) {
         float v = key_val(key);
         u32 id = key_idx(key);
@@ -278,91 +201,260 @@ __global__ __launch_bounds__(64) void row_merge_kernel(RowArgs a, int S, float *
         if (ti) ti[r] = viable ? (int32_t)id : -1;
     };
 
-    // Lower bound of the k-th best key: (a) the best list's k-th key, (b) the k-th largest of
-    // the first q keys of every list (S*q >= k keys).  At least k keys are >= either.
-    const int q = (k + S - 1) / S;
-    const int nh = S * q;  // < k + S <= 96
-    u64 bound = lane < S ? s_all[lane * k + k - 1] : 0ull;
-    {
-        u64 kth = 0ull;
+    // ---- 1. thread maxima, per-wave k-th largest, T0 ------------------------------------------
+    float it[16];
+    float tmax = -INFINITY;
+    if (S <= 16) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            int i = lane + 64 * h;
-            u64 mine = i < nh ? s_all[(i / q) * k + (i % q)] : 0ull;
-            int rank = 0;
-            for (int j = 0; j < nh; ++j) rank += (s_all[(j / q) * k + (j % q)] > mine) ? 1 : 0;
-            if (i < nh && rank == k - 1) kth = mine;
+        for (int j = 0; j < 16; ++j) {
+            it[j] = j < S ? lm[j * 256 + tid] : -INFINITY;
+            tmax = fmaxf(tmax, it[j]);
         }
-        bound = kth > bound ? kth : bound;
-    }
-    bound = wave_max_u64(bound);
-
-    int n = 0;
-    for (int base = 0; base < n_items; base += 64) {
-        int i = base + lane;
-        u64 key = i < n_items ? s_all[i] : 0ull;
-        bool hit = i < n_items && key >= bound;
-        u64 m = __ballot(hit);
-        int slot = n + (int)lanes_below(m);
-        if (hit && slot < 256) s_list[slot] = key;
-        n += __popcll(m);
-    }
-    if (n <= 256) {
-        rank_emit<4>(s_list, n, k, emit);
     } else {
-        // adversarial spread of the top keys over the lists: rank every key against all
-        for (int base = 0; base < n_items; base += 64) {
-            int i = base + lane;
-            u64 mine = i < n_items ? s_all[i] : 0ull;
-            int rank = 0;
-            for (int j = 0; j < n_items; ++j) rank += (s_all[j] > mine) ? 1 : 0;
-            if (i < n_items && rank < k) emit(rank, mine);
+        for (int j = 0; j < S; ++j) tmax = fmaxf(tmax, lm[j * 256 + tid]);
+    }
+    const float Tw = unord32(wave_kth_largest<BF16 ? 16 : 0>(ord32(tmax), k));
+    if (lane == 0) s_T[w] = Tw;
+    if (tid == 0) s_n2 = 0;
+    __syncthreads();
+    const float T0 = fmaxf(fmaxf(s_T[0], s_T[1]), fmaxf(s_T[2], s_T[3]));
+
+    // ---- 2. lane maxima >= T0, compacted per wave ---------------------------------------------
+    int cnt = 0;
+    auto push = [&](float v, int j) {
+        const bool hit = v >= T0;
+        const u64 m = __ballot(hit);
+        if (m) {
+            const int slot = cnt + (int)lanes_below(m);
+            if (hit && slot < 64) { s_c1v[w][slot] = v; s_c1l[w][slot] = j * 256 + tid; }
+            cnt += __popcll(m);
+        }
+    };
+    if (S <= 16) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (j < S) push(it[j], j);
+    } else {
+        for (int j = 0; j < S; ++j) push(lm[j * 256 + tid], j);
+    }
+    if (lane == 0) s_c1n[w] = cnt;
+    __syncthreads();
+    const int c0 = s_c1n[0], c1 = s_c1n[1], c2 = s_c1n[2], c3 = s_c1n[3];
+    const int n1 = c0 + c1 + c2 + c3;
+    bool slow = n1 > 64;  // uniform over the workgroup
+
+    // ---- the row's log-sum-exp, by wave 1 while wave 0 selects -----------------------------
+    if (w == 1 && a.want_lse && lse) {
+        const float cexp = 1.4426950408889634f * a.inv_t;
+        float M = -INFINITY, Ssum = 0.f;
+        for (int i = lane; i < S * 4; i += 64) {
+            const float2 p = a.part_ms[g * S * 4 + i];
+            const float M2 = fmaxf(M, p.x);
+            if (M2 != -INFINITY)
+                Ssum = Ssum * __builtin_amdgcn_exp2f((M - M2) * cexp) + p.y * __builtin_amdgcn_exp2f((p.x - M2) * cexp);
+            M = M2;
+        }
+        const float Mw = wave_max(M);
+        float term = (Ssum > 0.f) ? Ssum * __builtin_amdgcn_exp2f((M - Mw) * cexp) : 0.f;
+        term = wave_sum(term);
+        if (lane == 0) lse[g] = (Mw == -INFINITY) ? -INFINITY : Mw * a.inv_t + __logf(term);
+    }
+
+    if (!slow) {
+        if (w == 0) {
+            // candidate i of the concatenated per-wave lists
+            float v = -INFINITY;
+            int gl = -1;
+            if (lane < n1) {
+                int q = lane, ww = 0;
+                if (q >= c0) { q -= c0; ww = 1; if (q >= c1) { q -= c1; ww = 2; if (q >= c2) { q -= c2; ww = 3; } } }
+                v = s_c1v[ww][q];
+                gl = s_c1l[ww][q];
+            }
+            const float T = unord32(wave_kth_largest<BF16 ? 16 : 0>(ord32(v), k));
+            const bool hot = lane < n1 && v >= T;
+            const u64 m = __ballot(hot);
+            if (hot) s_hot[lanes_below(m)] = gl;
+            if (lane == 0) { s_h = __popcll(m); s_Trow = T; }
+        }
+        __syncthreads();
+        const int h = s_h;
+        const float T = s_Trow;
+        // ---- 3. re-read the hot lanes: (hot lane, load n) pairs spread over the threads ----
+        for (int q = tid; q < h * nl; q += 256) {
+            const int gl = s_hot[q / nl], n = q % nl;
+            const int c = gl >> 8, ww = (gl >> 6) & 3, l = gl & 63;
+            const int id0 = c * (256 * E) + ww * (64 * E) + l * 8 + n * 512;
+            for (int e = 0; e < 8; ++e) {
+                const int id = id0 + e;
+                const float xv = id < V ? load_elem(a, g, id) : -INFINITY;
+                if (xv >= T) {
+                    const int slot = atomicAdd(&s_n2, 1);
+                    if (slot < 64) s_fin[slot] = make_key(xv, (u32)id);
+                }
+            }
+        }
+        __syncthreads();
+        const int n2 = s_n2;
+        if (n2 <= 64) {
+            if (w == 0) rank_emit_lanes(lane < n2 ? s_fin[lane] : 0ull, n2, k, emit);
+            return;
+        }
+        slow = true;
+    }
+
+    // ---- exact fallback: k rounds of "largest key below the previous winner" ----------------
+    u64 prev = ~0ull;
+    for (int r = 0; r < k; ++r) {
+        u64 best = 0ull;
+        for (int id = tid; id < V; id += 256) {
+            const u64 key = make_key(load_elem(a, g, id), (u32)id);
+            if (key < prev && key > best) best = key;
+        }
+        best = wave_max_u64(best);
+        __syncthreads();
+        if (lane == 0) s_best[w] = best;
+        __syncthreads();
+        u64 b01 = s_best[0] > s_best[1] ? s_best[0] : s_best[1];
+        u64 b23 = s_best[2] > s_best[3] ? s_best[2] : s_best[3];
+        best = b01 > b23 ? b01 : b23;
+        if (tid == 0) {
+            if (best != 0ull) emit(r, best);
+            else { tv[r] = -INFINITY; if (ti) ti[r] = -1; }
+        }
+        prev = best;  // 0 once the row is exhausted: nothing is below it, later slots stay empty
+    }
+}
+
+// ------------------------------------------------------------- arg max kernel (target rows) --
+// k = 1: every workgroup leaves the best (value, id) key of its chunk, and optionally the
+// (max, sum) pair of row/T; the acceptance kernel merges the chunks of a row.
+template <int NL, bool BF16, bool VEC>
+__global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
+    constexpr int E = 8 * NL;
+    const int64_t g = blockIdx.y;
+    const int c = blockIdx.x;
+    const RowMeta meta = row_meta(a, g);
+    if (!meta.valid) return;
+    const int lane = lane_id(), w = threadIdx.x >> 6;
+    __shared__ u64 s_wout[4];
+    __shared__ float s_m[4], s_s[4];
+
+    const int base = c * (256 * E) + w * (64 * E) + lane * 8;
+    float x[E];
+    load_chunk<NL, BF16, VEC>(a, g, base, x);
+    float mx = x[0];
+#pragma unroll
+    for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
+    if (a.want_lse) {
+        const float2 p = wave_lse_partial<E>(x, mx, a.inv_t);
+        if (lane == 0) { s_m[w] = p.x; s_s[w] = p.y; }
+    }
+    // the wave's best key: lanes holding the wave maximum find their first such element
+    const float T = wave_max(mx);
+    u64 key = 0ull;
+    if (mx == T) {
+        int jbest = 0;
+#pragma unroll
+        for (int j = E - 1; j >= 0; --j) jbest = x[j] == T ? j : jbest;
+        key = make_key(T, (u32)(base + (jbest >> 3) * 512 + (jbest & 7)));
+    }
+    key = wave_max_u64(key);
+    if (lane == 0) s_wout[w] = key;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int64_t slot = g * gridDim.x + c;
+        u64 b01 = s_wout[0] > s_wout[1] ? s_wout[0] : s_wout[1];
+        u64 b23 = s_wout[2] > s_wout[3] ? s_wout[2] : s_wout[3];
+        a.part_keys[slot] = b01 > b23 ? b01 : b23;
+        if (a.want_lse) {
+            const float cexp = 1.4426950408889634f * a.inv_t;
+            float M = s_m[0], S = s_s[0];
+#pragma unroll
+            for (int q = 1; q < 4; ++q) {
+                float M2 = fmaxf(M, s_m[q]);
+                if (M2 != -INFINITY)
+                    S = S * __builtin_amdgcn_exp2f((M - M2) * cexp) + s_s[q] * __builtin_amdgcn_exp2f((s_m[q] - M2) * cexp);
+                M = M2;
+            }
+            a.part_ms[slot] = make_float2(M, S);
         }
     }
 }
 
 // ------------------------------------------------------------------------ launchers ------
-template <int NL>
-static hipError_t launch_chunk(const RowArgs &a, int64_t n_rows, bool vec, hipStream_t st) {
-    const int CH = 256 * 8 * NL;
-    dim3 grid((a.V + CH - 1) / CH, (unsigned)n_rows);
-    if (a.dtype == DT_BF16) {
-        if (vec) hipLaunchKernelGGL((row_chunk_kernel<NL, true, true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((row_chunk_kernel<NL, true, false>), grid, dim3(256), 0, st, a);
-    } else {
-        if (vec) hipLaunchKernelGGL((row_chunk_kernel<NL, false, true>), grid, dim3(256), 0, st, a);
-        else hipLaunchKernelGGL((row_chunk_kernel<NL, false, false>), grid, dim3(256), 0, st, a);
-    }
-    return hipGetLastError();
-}
-
 int rows_chunks_per_row(int V, int nl) { return (V + 256 * 8 * nl - 1) / (256 * 8 * nl); }
 
+// Chunk multiplier for the top-k rows: the smallest that keeps a row within 16 chunks (so that
+// the selection kernel holds its lane maxima in registers); 4 beyond that.
+int rows_topk_nl(int V) {
+    for (int nl = 1; nl <= 4; nl <<= 1)
+        if (rows_chunks_per_row(V, nl) <= 16) return nl;
+    return 4;
+}
+
+// Chunk multiplier for the arg max rows: enough workgroups to cover the chip, else smaller chunks.
 int rows_pick_nl(int64_t n_rows, int V) {
-    // enough workgroups to cover the chip several times over, else smaller chunks
     for (int nl = 4; nl > 1; nl >>= 1)
         if (n_rows * rows_chunks_per_row(V, nl) >= 2048) return nl;
     return 1;
 }
 
-hipError_t rows_launch_chunks(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st) {
-    if (n_rows <= 0) return hipSuccess;
+static bool rows_vec_ok(const RowArgs &a) {
     const int esz = a.dtype == DT_BF16 ? 2 : 4;
-    const bool vec = ((uintptr_t)a.logits % 16 == 0) && ((a.row_stride * esz) % 16 == 0);
-    ProfScope prof(a.mode == ROWS_DRAFT ? KID_ROWS_DRAFT : a.mode == ROWS_TARGET ? KID_ROWS_TARGET : KID_ROWS_UNIFORM, st);
-    switch (nl) {
-        case 4: return launch_chunk<4>(a, n_rows, vec, st);
-        case 2: return launch_chunk<2>(a, n_rows, vec, st);
-        default: return launch_chunk<1>(a, n_rows, vec, st);
-    }
+    return ((uintptr_t)a.logits % 16 == 0) && ((a.row_stride * esz) % 16 == 0);
 }
 
-hipError_t rows_launch_merge(const RowArgs &a, int64_t n_rows, int S, float *top_val, int32_t *top_id,
-                             float *lse, int out_stride, hipStream_t st) {
+#define DT_ROWS_DISPATCH(KERNEL, NLV)                                                                     \
+    do {                                                                                                  \
+        dim3 grid(rows_chunks_per_row(a.V, NLV), (unsigned)n_rows);                                       \
+        if (a.dtype == DT_BF16) {                                                                         \
+            if (vec) hipLaunchKernelGGL((KERNEL<NLV, true, true>), grid, dim3(256), 0, st, a);            \
+            else hipLaunchKernelGGL((KERNEL<NLV, true, false>), grid, dim3(256), 0, st, a);               \
+        } else {                                                                                          \
+            if (vec) hipLaunchKernelGGL((KERNEL<NLV, false, true>), grid, dim3(256), 0, st, a);           \
+            else hipLaunchKernelGGL((KERNEL<NLV, false, false>), grid, dim3(256), 0, st, a);              \
+        }                                                                                                 \
+    } while (0)
+
+// top-k rows, pass 1: lane maxima and (max, sum) partials
+hipError_t rows_launch_stream(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
+    const bool vec = rows_vec_ok(a);
+    ProfScope prof(a.mode == ROWS_DRAFT ? KID_ROWS_DRAFT : KID_ROWS_UNIFORM, st);
+    switch (nl) {
+        case 4: DT_ROWS_DISPATCH(row_stream_kernel, 4); break;
+        case 2: DT_ROWS_DISPATCH(row_stream_kernel, 2); break;
+        default: DT_ROWS_DISPATCH(row_stream_kernel, 1); break;
+    }
+    return hipGetLastError();
+}
+
+// top-k rows, pass 2: selection on the lane maxima
+hipError_t rows_launch_select(const RowArgs &a, int64_t n_rows, int nl, float *top_val, int32_t *top_id, float *lse,
+                              int out_stride, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    const int S = rows_chunks_per_row(a.V, nl);
     ProfScope prof(KID_ROWS_MERGE, st);
-    hipLaunchKernelGGL(row_merge_kernel, dim3((unsigned)n_rows), dim3(64), 0, st, a, S, top_val, top_id, lse,
-                       out_stride);
+    if (a.dtype == DT_BF16)
+        hipLaunchKernelGGL(row_select_kernel<true>, dim3((unsigned)n_rows), dim3(256), 0, st, a, nl, S, top_val, top_id,
+                           lse, out_stride);
+    else
+        hipLaunchKernelGGL(row_select_kernel<false>, dim3((unsigned)n_rows), dim3(256), 0, st, a, nl, S, top_val,
+                           top_id, lse, out_stride);
+    return hipGetLastError();
+}
+
+// arg max rows (target logits)
+hipError_t rows_launch_argmax(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st) {
+    if (n_rows <= 0) return hipSuccess;
+    const bool vec = rows_vec_ok(a);
+    ProfScope prof(KID_ROWS_TARGET, st);
+    switch (nl) {
+        case 4: DT_ROWS_DISPATCH(row_argmax_kernel, 4); break;
+        case 2: DT_ROWS_DISPATCH(row_argmax_kernel, 2); break;
+        default: DT_ROWS_DISPATCH(row_argmax_kernel, 1); break;
+    }
     return hipGetLastError();
 }
 

@@ -12,6 +12,13 @@
 
 namespace dt {
 
+#ifdef DT_TIMESTAMPS
+__device__ unsigned long long dt_dbg_stamps[64];
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) dt_dbg_stamps[i] = __builtin_amdgcn_s_memtime(); } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#endif
+
 #define DT_P_MAX (DT_K_MAX + (DT_D_MAX - 1) * DT_K_MAX * DT_K_MAX)
 
 struct Cut {
@@ -22,32 +29,69 @@ struct Cut {
 __device__ __forceinline__ u32 score_key(float s) { return ord32(s); }
 #define KEY_NEG_INF 0x007FFFFFu
 
-// keep-th largest key among score[0..n), n <= 1024; executed by one full wave.
-__device__ __forceinline__ Cut wave_cut(const float *score, int n, int keep) {
+// Selection of the `keep_max` best of score[0..n) (n <= 64*ITEMS) by one full wave, entirely from
+// registers: count the viable ones, find the keep-th largest key by bisection two bits at a time
+// (three independent probe counts per step, all on ballots), then visit the winners in ascending
+// index: f(index, position).  Absent items hold key 0, which no probe (>= 1) ever counts.
+template <int ITEMS, typename F>
+__device__ __forceinline__ int wave_select_t(const float *score, int n, int keep_max, Cut *cut_out, F f) {
     const int lane = lane_id();
-    u32 it[16];
+    u32 it[ITEMS];
+    int viable = 0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        int i = j * 64 + lane;
+    for (int j = 0; j < ITEMS; ++j) {
+        const int i = j * 64 + lane;
         it[j] = i < n ? score_key(score[i]) : 0u;
+        viable += __popcll(__ballot(it[j] > KEY_NEG_INF));
     }
-    u32 t = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const u32 cand = t | (1u << bit);
-        int cnt = 0;
-#pragma unroll
-        for (int j = 0; j < 16; ++j)
-            if (j * 64 < n) cnt += __popcll(__ballot(it[j] >= cand));
-        if (cnt >= keep) t = cand;
-    }
-    int gt = 0;
-#pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (j * 64 < n) gt += __popcll(__ballot(it[j] > t));
+    const int keep = min(keep_max, viable);
     Cut c;
-    c.thr = t;
-    c.need_eq = keep - gt;
-    return c;
+    c.thr = 0xFFFFFFFFu;
+    c.need_eq = 0;
+    if (keep > 0) {
+        u32 t = 0;
+#pragma unroll 1
+        for (int bit = 30; bit >= 0; bit -= 2) {
+            const u32 c1 = t | (1u << bit), c2 = t | (2u << bit), c3 = t | (3u << bit);
+            int n1 = 0, n2 = 0, n3 = 0;
+#pragma unroll
+            for (int j = 0; j < ITEMS; ++j) {
+                n1 += __popcll(__ballot(it[j] >= c1));
+                n2 += __popcll(__ballot(it[j] >= c2));
+                n3 += __popcll(__ballot(it[j] >= c3));
+            }
+            t = n3 >= keep ? c3 : n2 >= keep ? c2 : n1 >= keep ? c1 : t;
+        }
+        int gt = 0;
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) gt += __popcll(__ballot(it[j] > t));
+        c.thr = t;
+        c.need_eq = keep - gt;
+    }
+    if (cut_out) *cut_out = c;
+    int pos = 0, eq_seen = 0;
+    if (keep > 0) {
+#pragma unroll
+        for (int j = 0; j < ITEMS; ++j) {
+            const int i = j * 64 + lane;
+            const bool eq = it[j] == c.thr;
+            const u64 meq = __ballot(eq);
+            const bool take = it[j] > c.thr || (eq && eq_seen + (int)lanes_below(meq) < c.need_eq);
+            const u64 m = __ballot(take);
+            if (take) f(i, pos + (int)lanes_below(m));
+            pos += __popcll(m);
+            eq_seen += __popcll(meq);
+        }
+    }
+    return pos;
+}
+template <typename F>
+__device__ __forceinline__ int wave_select(const float *score, int n, int keep_max, Cut *cut_out, F f) {
+    if (n <= 64) return wave_select_t<1>(score, n, keep_max, cut_out, f);
+    if (n <= 128) return wave_select_t<2>(score, n, keep_max, cut_out, f);
+    if (n <= 256) return wave_select_t<4>(score, n, keep_max, cut_out, f);
+    if (n <= 512) return wave_select_t<8>(score, n, keep_max, cut_out, f);
+    return wave_select_t<16>(score, n, keep_max, cut_out, f);
 }
 
 __device__ __forceinline__ int block_sum_256(int v, int *s_red) {
@@ -139,6 +183,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     __shared__ int s_red[4];
     __shared__ Cut s_cut;
 
+    STAMP(0);
     if (tid == 0) {
         a.tokens[o] = a.root_token[b];
         a.parents[o] = -1;
@@ -154,47 +199,45 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
         return;
     }
     const int P = k + (d - 1) * k * k;
+    // Every candidate's own log-probability is known up front: the draft row that would
+    // produce pool index p is fixed by p alone (only its parent is decided later).  Park
+    // lp in s_score; the level loop turns it into the cumulative score in place.
     for (int p = tid; p < P; p += 256) {
-        s_score[p] = -INFINITY;
+        const Decoded dc = decode(p, k);
+        const float v = tv[dc.row * DT_K_MAX + dc.rank];
+        s_score[p] = v > -INFINITY ? v - lse[dc.row] : -INFINITY;
         s_node[p] = -1;
         s_slot[p] = -1;
     }
     __syncthreads();
-    if (tid < k) {
-        float v = tv[tid];
-        s_score[tid] = v > -INFINITY ? v - lse[0] : -INFINITY;
-    }
-    __syncthreads();
+    STAMP(1);
 
     // ---- expansion, level by level -----------------------------------------------------------
+    int p_end = k;  // pool indices below p_end hold real scores (levels computed so far)
     for (int l = 1; l < d; ++l) {
         const int lo = l == 1 ? 0 : k + (l - 2) * k * k;
         const int n = l == 1 ? k : k * k;
         if (w == 0) {
-            const float *sc = s_score + lo;
-            int keep = min(k, count_viable_wave(sc, n));
-            int n_exp = 0;
-            if (keep > 0) {
-                Cut c = wave_cut(sc, n, keep);
-                int *exp_l = s_exp[l];
-                n_exp = wave_enumerate(sc, n, c, [&](int i, int pos) {
-                    exp_l[pos] = lo + i;
-                    s_slot[lo + i] = (int8_t)pos;
-                });
-            }
+            int *exp_l = s_exp[l];
+            const int n_exp = wave_select(s_score + lo, n, k, nullptr, [&](int i, int pos) {
+                exp_l[pos] = lo + i;
+                s_slot[lo + i] = (int8_t)pos;
+            });
             if (lane_id() == 0) s_nexp = n_exp;
         }
+        STAMP(2 + 2 * l);
         __syncthreads();
         const int n_exp = s_nexp;
         if (n_exp == 0) break;
         const int nlo = k + (l - 1) * k * k;
-        for (int t = tid; t < n_exp * k; t += 256) {
-            int s = t / k, r = t - s * k;
-            int row = 1 + (l - 1) * k + s;
-            float v = tv[row * DT_K_MAX + r];
-            if (v > -INFINITY) s_score[nlo + s * k + r] = s_score[s_exp[l][s]] + (v - lse[row]);
+        for (int t = tid; t < k * k; t += 256) {
+            const int s = t / k;
+            // slots beyond the expanded set own no node: their candidates do not exist
+            s_score[nlo + t] = s < n_exp ? s_score[s_exp[l][s]] + s_score[nlo + t] : -INFINITY;
         }
+        p_end = nlo + k * k;
         __syncthreads();
+        STAMP(3 + 2 * l);
     }
 
     __syncthreads();  // every wave has read s_nexp before it is reused below
@@ -202,33 +245,33 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     // ---- rerank: the TT-1 best of the whole pool ----------------------------------------------
     Cut cut;
     int keep;
-    if (P <= 1024) {
+    if (p_end <= 1024) {
         if (w == 0) {
-            int kp = min(TT - 1, count_viable_wave(s_score, P));
-            Cut c;
-            c.thr = 0xFFFFFFFFu;
-            c.need_eq = 0;
-            if (kp > 0) c = wave_cut(s_score, P, kp);
-            if (lane_id() == 0) { s_cut = c; s_nexp = kp; }
+            const int kp = wave_select(s_score, p_end, TT - 1, nullptr,
+                                       [&](int i, int pos) { s_node[i] = (int16_t)(pos + 1); });
+            if (lane_id() == 0) s_nexp = kp;
         }
         __syncthreads();
-        cut = s_cut;
         keep = s_nexp;
     } else {
         int v = 0;
-        for (int i = tid; i < P; i += 256) v += s_score[i] > -INFINITY ? 1 : 0;
+        for (int i = tid; i < p_end; i += 256) v += s_score[i] > -INFINITY ? 1 : 0;
         keep = min(TT - 1, block_sum_256(v, s_red));
         cut.thr = 0xFFFFFFFFu;
         cut.need_eq = 0;
-        if (keep > 0) cut = block_cut(s_score, P, keep, s_red);
+        if (keep > 0) cut = block_cut(s_score, p_end, keep, s_red);
     }
-    if (w == 0 && keep > 0)
-        wave_enumerate(s_score, P, cut, [&](int i, int pos) { s_node[i] = (int16_t)(pos + 1); });
-    __syncthreads();
+    STAMP(20);
+    if (p_end > 1024) {
+        if (w == 0 && keep > 0)
+            wave_enumerate(s_score, p_end, cut, [&](int i, int pos) { s_node[i] = (int16_t)(pos + 1); });
+        __syncthreads();
+    }
     if (tid == 0) a.n_nodes[b] = keep + 1;
+    STAMP(21);
 
     // ---- emission -------------------------------------------------------------------------------
-    for (int p = tid; p < P; p += 256) {
+    for (int p = tid; p < p_end; p += 256) {
         const int n = s_node[p];
         if (n < 0) continue;
         const Decoded dc = decode(p, k);
@@ -252,7 +295,14 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
         a.anc_mask[(o + n) * DT_MASK_WORDS] = m0;
         a.anc_mask[(o + n) * DT_MASK_WORDS + 1] = m1;
     }
+    STAMP(22);
 }
+
+#ifdef DT_TIMESTAMPS
+extern "C" int dt_debug_stamps(unsigned long long *out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_stamps), sizeof(unsigned long long) * 64);
+}
+#endif
 
 hipError_t tree_launch(const TreeArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;

@@ -105,6 +105,36 @@ class Step:
         self.tree_attention()
         self.accept(philox_step)
 
+    # ---- the same three calls with the argument lists marshalled once ---------------------------
+    def prepare(self):
+        """Marshal the (fixed) pointer arguments once; run_prepared() then costs three foreign calls."""
+        p = lambda t: None if t is None else t.data_ptr()
+        dtc = B._dtype(self.draft_logits)
+        wsb = self.ws.numel()
+        self._lib = B.load_library()
+        self._a_build = (self.Bsz, p(self.params), p(self.draft_logits), dtc, self.V, self.draft_logits.stride(0),
+                         p(self.row_off), self.total_rows, p(self.root_token), self.TT_cap, p(self.n_nodes),
+                         p(self.tokens), p(self.parents), p(self.depth), p(self.score), p(self.logp),
+                         p(self.src_row), p(self.anc_mask), p(self.ws), wsb)
+        self._a_attn = (self.Bsz, dtc, self.Hq, self.Hkv, self.D, self.scale, p(self.q), p(self.k_tree),
+                        p(self.v_tree), p(self.n_nodes), p(self.k_prefix_ptrs), p(self.v_prefix_ptrs),
+                        p(self.prefix_len), max(self.host_prefix_len), self.Hkv * self.D, self.D, p(self.anc_mask),
+                        self.TT_cap, p(self.out), p(self.ws), wsb)
+        self._a_acc_head = (self.Bsz, self.mode, self.temperature, p(self.target_logits), dtc, self.V,
+                            self.target_logits.stride(1), p(self.n_nodes), p(self.tokens), p(self.parents),
+                            p(self.depth), p(self.logp), p(self.anc_mask), self.TT_cap, self.philox_seed)
+        self._a_acc_tail = (p(self.accept_len), p(self.best_node), p(self.path_nodes), p(self.out_tokens),
+                            p(self.node_argmax), p(self.ws), wsb)
+        return self
+
+    def run_prepared(self, stream, philox_step=0):
+        lib = self._lib
+        rc = lib.dt_build_tree(stream, *self._a_build)
+        rc = rc or lib.dt_tree_attention(stream, *self._a_attn)
+        rc = rc or lib.dt_accept(stream, *self._a_acc_head, philox_step, *self._a_acc_tail)
+        if rc:
+            raise B.DtError("step", rc)
+
     # ---- downloads ----------------------------------------------------------------------------------
     def tree(self, b):
         n = int(self.n_nodes[b].item())
