@@ -41,6 +41,7 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     const int64_t o = (int64_t)b * a.TT_cap;
     const bool stochastic = a.mode == DT_ACCEPT_STOCHASTIC;
     const float inv_t = stochastic ? 1.0f / a.temperature : 1.0f;
+    const int S = a.S;
 
     __shared__ int s_amax[DT_TT_MAX];
     __shared__ float s_rowmax[DT_TT_MAX];
@@ -50,31 +51,59 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     __shared__ double s_wtot[4];
     __shared__ int s_bonus;
 
-    // ---- merge the row partials: wave w takes rows w, w+4, ...; lane c holds chunk c (S <= 64) --
+    // ---- everything a node needs later is requested now, so the loads overlap the merge -------
+    int my_tok = 0, my_par = 0, my_dep = 0;
+    u64 my_m0 = 0ull, my_m1 = 0ull;
+    float my_logp = 0.f;
+    if (tid < N) {
+        my_tok = a.tokens[o + tid];
+        my_par = a.parents[o + tid];
+        my_dep = a.depth[o + tid];
+        my_m0 = a.anc_mask[(o + tid) * DT_MASK_WORDS];
+        my_m1 = a.anc_mask[(o + tid) * DT_MASK_WORDS + 1];
+        if (stochastic) my_logp = a.logp[o + tid];
+    }
+
+    // ---- merge the row partials: four adjacent lanes share a row, each takes every fourth chunk --
     {
         const float cexp = 1.4426950408889634f * inv_t;
-#pragma unroll 4
-        for (int i = w; i < N; i += 4) {
-            const int64_t g = o + i;
-            const u64 key = lane < a.S ? a.part_keys[g * a.S + lane] : 0ull;
-            const u64 best = wave_max_u64(key);
-            float lse_i = 0.f;
-            if (stochastic) {
-                float2 p = lane < a.S ? a.part_ms[g * a.S + lane] : make_float2(-INFINITY, 0.f);
-                const float M = wave_max(p.x);
-                const float Mu = M == -INFINITY ? 0.f : M;
-                const float term = p.y > 0.f ? p.y * __builtin_amdgcn_exp2f((p.x - Mu) * cexp) : 0.f;
-                lse_i = M * inv_t + __logf(wave_sum(term));
+        const int part = tid & 3;
+        for (int i0 = 0; i0 < N; i0 += 64) {
+            const int i = i0 + (tid >> 2);
+            const int64_t g = o + min(i, N - 1);
+            u64 best = 0ull;
+            float M = -INFINITY, Ssum = 0.f;
+            for (int c = part; c < S; c += 4) {
+                const u64 key = a.part_keys[g * S + c];
+                best = key > best ? key : best;
+                if (stochastic) {
+                    const float2 p = a.part_ms[g * S + c];
+                    const float M2 = fmaxf(M, p.x);
+                    if (M2 != -INFINITY)
+                        Ssum = Ssum * __builtin_amdgcn_exp2f((M - M2) * cexp) + p.y * __builtin_amdgcn_exp2f((p.x - M2) * cexp);
+                    M = M2;
+                }
             }
-            if (lane == 0) {
+#pragma unroll
+            for (int off = 1; off <= 2; off <<= 1) {  // the four lanes of the row
+                const u64 ob = shfl_xor_u64(best, off);
+                best = ob > best ? ob : best;
+                if (stochastic) {
+                    const float M2 = __shfl_xor(M, off, 64), S2 = __shfl_xor(Ssum, off, 64);
+                    const float Mn = fmaxf(M, M2);
+                    if (Mn != -INFINITY)
+                        Ssum = Ssum * __builtin_amdgcn_exp2f((M - Mn) * cexp) + S2 * __builtin_amdgcn_exp2f((M2 - Mn) * cexp);
+                    M = Mn;
+                }
+            }
+            if (part == 0 && i < N) {
                 s_amax[i] = (int)key_idx(best);
                 s_rowmax[i] = key_val(best);
-                s_lse[i] = lse_i;
-                if (a.node_argmax) a.node_argmax[g] = (int)key_idx(best);
+                s_lse[i] = stochastic ? M * inv_t + __logf(Ssum) : 0.f;
+                if (a.node_argmax) a.node_argmax[o + i] = (int)key_idx(best);
             }
         }
     }
-    if (tid < 2) s_acc[tid] = 0ull;
     __syncthreads();
 
     // ---- per-node accept bit ----------------------------------------------------------------
@@ -84,14 +113,13 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
             if (tid == 0) {
                 acc = true;
             } else {
-                const int p = min(max(a.parents[o + tid], 0), N - 1);
-                const int tok = a.tokens[o + tid];
+                const int p = min(max(my_par, 0), N - 1);
                 if (!stochastic) {
-                    acc = tok == s_amax[p];
-                } else if (tok >= 0 && tok < a.V) {
-                    const float x = load_logit(a.target, a.dtype, (o + p) * a.row_stride + tok);
+                    acc = my_tok == s_amax[p];
+                } else if (my_tok >= 0 && my_tok < a.V) {
+                    const float x = load_logit(a.target, a.dtype, (o + p) * a.row_stride + my_tok);
                     const float lpT = x * inv_t - s_lse[p];
-                    const float alpha = fminf(1.0f, __expf(lpT - a.logp[o + tid]));
+                    const float alpha = fminf(1.0f, __expf(lpT - my_logp));
                     const float u = philox_uniform(a.seed, a.step, (u32)b, (u32)tid);
                     acc = u < alpha;
                 }
@@ -106,18 +134,33 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     if (tid < DT_TT_MAX) {
         int key = -1;
         if (tid < N) {
-            const u64 m0 = a.anc_mask[(o + tid) * DT_MASK_WORDS], m1 = a.anc_mask[(o + tid) * DT_MASK_WORDS + 1];
-            const bool ok = ((m0 & ~s_acc[0]) | (m1 & ~s_acc[1])) == 0ull;
-            if (ok) key = (a.depth[o + tid] << 8) | (255 - tid);
+            const bool ok = ((my_m0 & ~s_acc[0]) | (my_m1 & ~s_acc[1])) == 0ull;
+            if (ok) key = (my_dep << 8) | (255 - tid);
         }
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) key = max(key, __shfl_xor(key, off, 64));
+        key = wave_max_i32(key);
         if (lane == 0) s_best[w] = key;
     }
     __syncthreads();
     const int bkey = max(s_best[0], s_best[1]);
     const int best = 255 - (bkey & 255);
     const int len = bkey >> 8;
+
+    // ---- the accepted path: exactly the nodes in the ancestor set of `best`, which its owner
+    //      thread publishes (the accept bits in s_acc are no longer needed) -----------------------
+    if (tid == best) { s_acc[0] = my_m0; s_acc[1] = my_m1; }
+    if (tid <= DT_D_MAX && tid > len) {  // unused slots; slot len of out_tokens is the bonus token
+        a.path_nodes[(int64_t)b * (DT_D_MAX + 1) + tid] = -1;
+        a.out_tokens[(int64_t)b * (DT_D_MAX + 1) + tid] = -1;
+    }
+    __syncthreads();
+    if (tid < N) {
+        const bool on_path = ((tid < 64 ? s_acc[0] : s_acc[1]) >> (tid & 63)) & 1ull;
+        if (on_path && my_dep <= DT_D_MAX) {
+            a.path_nodes[(int64_t)b * (DT_D_MAX + 1) + my_dep] = tid;
+            if (tid > 0) a.out_tokens[(int64_t)b * (DT_D_MAX + 1) + my_dep - 1] = my_tok;
+        }
+    }
+    if (tid == 0) { a.accept_len[b] = len; a.best_node[b] = best; }
 
     // ---- bonus token --------------------------------------------------------------------------
     if (!stochastic) {
@@ -186,22 +229,7 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     }
     __syncthreads();
 
-    // ---- walk and outputs ---------------------------------------------------------------------
-    if (tid == 0) {
-        a.accept_len[b] = len;
-        a.best_node[b] = best;
-        int32_t *path = a.path_nodes + (int64_t)b * (DT_D_MAX + 1);
-        int32_t *outt = a.out_tokens + (int64_t)b * (DT_D_MAX + 1);
-        for (int s = 0; s <= DT_D_MAX; ++s) { path[s] = -1; outt[s] = -1; }
-        int i = best;
-        for (int guard = 0; guard <= DT_D_MAX && i >= 0; ++guard) {
-            const int dpt = min(max(a.depth[o + i], 0), DT_D_MAX);
-            path[dpt] = i;
-            if (i > 0) outt[dpt - 1] = a.tokens[o + i];
-            i = i > 0 ? a.parents[o + i] : -1;
-        }
-        if (len <= DT_D_MAX) outt[len] = s_bonus;
-    }
+    if (tid == 0 && len <= DT_D_MAX) a.out_tokens[(int64_t)b * (DT_D_MAX + 1) + len] = s_bonus;
 }
 
 hipError_t accept_launch(const AcceptArgs &a, hipStream_t st) {

@@ -17,9 +17,36 @@
 
 namespace dt {
 
+#ifdef DT_TIMESTAMPS
+__device__ unsigned long long dt_dbg_attn[64];
+#define ASTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (i) < 64) dt_dbg_attn[i] = __builtin_amdgcn_s_memtime(); } while (0)
+extern "C" int dt_debug_attn_stamps(unsigned long long *out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_attn), sizeof(unsigned long long) * 64);
+}
+#else
+#define ASTAMP(i) do {} while (0)
+#endif
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// Global-address-space views: pointers fetched from memory (the per-sequence prefix pointers)
+// would otherwise be generic, and generic loads also count against the LDS wait counter.
+typedef const __bf16 __attribute__((address_space(1))) *gbf16p;
+typedef const bf16x8 __attribute__((address_space(1))) *gbf16x8p;
+__device__ __forceinline__ bf16x8 gload8(gbf16p p) { return *(gbf16x8p)p; }
+
+// LDS transpose read of gfx950 (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane p
+// supplies the address of 4 consecutive 16-bit values; with X the concatenation of the 16
+// quadruples in lane order, lane i receives X[i], X[16+i], X[32+i], X[48+i].  Pointing lane
+// p = 4j+q at row j, columns 4q..4q+3 of a row-major tile therefore hands lane i the column
+// i of rows 0..3: a 4x16 -> 16x4 transpose, which is what a K-contiguous MFMA operand needs
+// from a matrix stored with the other index contiguous.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x4 lds_read_tr4(const __bf16 *p) {
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3))) *)p);
+    return __builtin_bit_cast(bf16x4, v);
+}
 
 #define ATT_KB 32           // keys per block
 #define ATT_ROWS_PER_WAVE 32
@@ -73,12 +100,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
     {
         const __bf16 *qp = (const __bf16 *)a.q + (((int64_t)b * a.TT_cap + node) * a.Hq + hq) * D;
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            if (qvalid) qreg[s] = *(const bf16x8 *)(qp + 16 * s + 8 * half);
-            else
-#pragma unroll
-                for (int e = 0; e < 8; ++e) qreg[s][e] = (__bf16)0.f;
-        }
+        for (int s = 0; s < KSTEPS; ++s) qreg[s] = *(const bf16x8 *)(qp + 16 * s + 8 * half);  // rows past M read node 0: unused
     }
     const u64 mask0 = a.anc_mask[((int64_t)b * a.TT_cap + node) * DT_MASK_WORDS];
     const u64 mask1 = a.anc_mask[((int64_t)b * a.TT_cap + node) * DT_MASK_WORDS + 1];
@@ -102,22 +124,13 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
         // ---- stage K (row-major) and V (transposed) of this key block ---------------------
         {
             const int t = kb * ATT_KB + skey;
-            bf16x8 k0, k1, v0, v1;
-            if (t < Tk) {
-                const __bf16 *kp, *vp;
-                if (t < L) {
-                    const int64_t off = (int64_t)t * a.kv_stride_tok + (int64_t)h * a.kv_stride_head + sd0;
-                    kp = kpre + off; vp = vpre + off;
-                } else {
-                    const int64_t off = ((int64_t)(t - L) * a.Hkv + h) * D + sd0;
-                    kp = ktree + off; vp = vtree + off;
-                }
-                k0 = *(const bf16x8 *)kp; k1 = *(const bf16x8 *)(kp + 8);
-                v0 = *(const bf16x8 *)vp; v1 = *(const bf16x8 *)(vp + 8);
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) { k0[e] = k1[e] = v0[e] = v1[e] = (__bf16)0.f; }
-            }
+            // keys past the end re-read the last valid row: masked to probability 0 below
+            const int tc = min(t, Tk - 1);
+            const int64_t off = tc < L ? (int64_t)tc * a.kv_stride_tok + (int64_t)h * a.kv_stride_head + sd0
+                                       : ((int64_t)(tc - L) * a.Hkv + h) * D + sd0;
+            const __bf16 *kp = (tc < L ? kpre : ktree) + off, *vp = (tc < L ? vpre : vtree) + off;
+            const bf16x8 k0 = *(const bf16x8 *)kp, k1 = *(const bf16x8 *)(kp + 8);
+            const bf16x8 v0 = *(const bf16x8 *)vp, v1 = *(const bf16x8 *)(vp + 8);
             *(bf16x8 *)(s_k + skey * K_PITCH + sd0) = k0;
             *(bf16x8 *)(s_k + skey * K_PITCH + sd0 + 8) = k1;
             const int pos = vt_pos(skey);
@@ -211,6 +224,274 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
             }
         if (half == 0) part.ml[prow] = make_float2(m_run, l_tot);
     }
+}
+
+// ------------------------------------------------------------------- small-batch kernel -----
+// When a batch offers only a few (sequence, kv head) pairs, latency matters more than reuse:
+// one workgroup owns 32 query rows, its NW waves take the key blocks round-robin and stream
+// them PRIVATELY (coalesced 16-byte loads, a wave-private LDS tile to bring K into operand
+// layout and V into transposed operand layout, next block prefetched into registers), so the
+// main loop has no barrier at all.  The partial results meet in LDS once at the end; nothing
+// goes through global scratch.  Two waves per SIMD hide each other's instruction latency.
+#define KT_ELEMS (ATT_KB * K_PITCH)    // per-wave K tile and V tile: 32 rows of 272 B each
+#define WT_ELEMS (2 * KT_ELEMS)        // both tiles of a wave: 17 KB
+typedef const char __attribute__((address_space(1))) *gbytep;
+
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a) {
+    static_assert(D == 128 && (NW == 4 || NW == 8), "shape");
+    constexpr int KSTEPS = D / 16, DBLK = D / 32;
+    const int G = a.Hq / a.Hkv;
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
+    const int M = N * G;
+    const int m0 = blockIdx.x * 32;
+    if (m0 >= M) return;
+    const int L = max(a.prefix_len[b], 0);
+    const int Tk = L + N;
+    const int nb = (Tk + ATT_KB - 1) / ATT_KB;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave index, known uniform
+    const int half = lane >> 5, col = lane & 31;
+    const int mq = m0 + col;
+    const bool qvalid = mq < M;
+    const int node = qvalid ? mq / G : 0;
+    const int hq = h * G + (qvalid ? mq % G : 0);
+
+    // LDS: NW private tiles during the loop, then the exchange area of the partial results
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
+    __shared__ float s_m[NW][32], s_l[NW][32];
+    float *s_buf = (float *)s_dyn;
+    __bf16 *kt = (__bf16 *)s_dyn + w * WT_ELEMS;
+    __bf16 *vt = kt + KT_ELEMS;
+
+    bf16x8 qreg[KSTEPS];
+    {
+        const __bf16 *qp = (const __bf16 *)a.q + (((int64_t)b * a.TT_cap + node) * a.Hq + hq) * D;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) qreg[s] = *(const bf16x8 *)(qp + 16 * s + 8 * half);  // rows past M read node 0: unused
+    }
+    const u64 mask0 = a.anc_mask[((int64_t)b * a.TT_cap + node) * DT_MASK_WORDS];
+    const u64 mask1 = a.anc_mask[((int64_t)b * a.TT_cap + node) * DT_MASK_WORDS + 1];
+
+    f32x16 oacc[DBLK];
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+    const float c = a.scale * 1.4426950408889634f;
+
+    const gbf16p kpre = (gbf16p)a.k_prefix[b] + (int64_t)h * a.kv_stride_head;
+    const gbf16p vpre = (gbf16p)a.v_prefix[b] + (int64_t)h * a.kv_stride_head;
+    const gbf16p ktree = (gbf16p)a.k_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
+    const gbf16p vtree = (gbf16p)a.v_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
+    const int64_t stok = a.kv_stride_tok, stree = (int64_t)a.Hkv * D;
+    const int kq = lane >> 4, dc = lane & 15;
+    // Loading role of a lane, the same for K and V: load i takes key (i>>2)*16 + 4*kq + (i&3) of
+    // the block, columns 8dc..8dc+7, so 16 lanes cover one 256-byte row (fully coalesced).
+    // Inside the prefix the address is a uniform block base plus a fixed 32-bit lane offset.
+    u32 loff[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) loff[i] = (u32)(((i >> 2) * 16 + 4 * kq + (i & 3)) * stok + 8 * dc) * 2u;
+    const bool small_stride = (int64_t)ATT_KB * stok * 2 < ((int64_t)1 << 31);
+
+    // Every load is unconditional, so the sixteen loads of a block are in flight together.  Keys
+    // past the end are read from the last valid row; their scores are masked to -inf below, so
+    // their probabilities are exactly 0 and the duplicated V rows contribute nothing.
+    bf16x8 kn[8], vn[8];
+    auto fetch = [&](int kb) {
+        if (small_stride && kb * ATT_KB + ATT_KB <= L) {  // block inside the prefix (uniform test)
+            const gbytep kbase = (gbytep)(kpre + (int64_t)kb * ATT_KB * stok);
+            const gbytep vbase = (gbytep)(vpre + (int64_t)kb * ATT_KB * stok);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                kn[i] = *(gbf16x8p)(kbase + loff[i]);
+                vn[i] = *(gbf16x8p)(vbase + loff[i]);
+            }
+        } else {                                           // block touching the tree keys or the end
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int t = min(kb * ATT_KB + (i >> 2) * 16 + 4 * kq + (i & 3), Tk - 1);
+                const int64_t o = (t < L ? (int64_t)t * stok : (int64_t)(t - L) * stree) + 8 * dc;
+                kn[i] = gload8((t < L ? kpre : ktree) + o);
+                vn[i] = gload8((t < L ? vpre : vtree) + o);
+            }
+        }
+    };
+
+    ASTAMP(0);
+    int kb = w;
+    if (kb < nb) fetch(kb);
+    int it_no = 0;
+    for (; kb < nb; kb += NW, ++it_no) {
+        ASTAMP(1 + it_no * 5);
+        // The prefetched block goes straight into the wave's two LDS tiles, both row-major, which
+        // frees its registers for the next prefetch, issued before any arithmetic on this block.
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = ((i >> 2) * 16 + 4 * kq + (i & 3)) * K_PITCH + 8 * dc;
+            *(bf16x8 *)(kt + r) = kn[i];
+            *(bf16x8 *)(vt + r) = vn[i];
+        }
+        if (kb + NW < nb) fetch(kb + NW);
+        ASTAMP(2 + it_no * 5);
+
+        f32x16 sacc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            const bf16x8 ka = *(const bf16x8 *)(kt + col * K_PITCH + 16 * s + 8 * half);
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc, 0, 0, 0);
+        }
+        ASTAMP(3 + it_no * 5);
+
+        const int tbase = kb * ATT_KB;
+        if (tbase + ATT_KB > L) {  // only blocks that contain tree keys (or the end) need the mask
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int j = tbase + 8 * (i >> 2) + 4 * half + (i & 3) - L;
+                const bool vis = j < 0 || (j < N && (((j < 64 ? mask0 : mask1) >> (j & 63)) & 1ull));
+                sacc[i] = vis ? sacc[i] : -INFINITY;
+            }
+        }
+        float mloc = sacc[0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, sacc[i]);
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        const float m_new = fmaxf(m_run, mloc);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c);
+        const float nmc = -m_use * c;
+        float psum = 0.f;
+        bf16x8 pb[2];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, nmc));
+            psum += p;
+            pb[i >> 3][i & 7] = (__bf16)p;
+        }
+        l_run = l_run * alpha + psum;
+        m_run = m_new;
+        if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some query of this wave
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        }
+        ASTAMP(4 + it_no * 5);
+
+        // O^T += V^T P^T.  The A operand of lane (column d = 32db + col, half) holds, for e = 0..7,
+        // V[key 16st + 8(e/4) + 4half + e%4][d]: two transposing LDS reads of 4 keys each.  In a
+        // 16-lane group lane p = 4j+q points at key j of the quadruple, columns d0 + 4q..4q+3.
+        {
+            const int p16 = lane & 15;
+            const __bf16 *vbase = vt + (4 * half + (p16 >> 2)) * K_PITCH + 16 * ((lane >> 4) & 1) + 4 * (p16 & 3);
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int st = 0; st < 2; ++st) {
+                    const bf16x4 lo = lds_read_tr4(vbase + (16 * st) * K_PITCH + 32 * db);
+                    const bf16x4 hi = lds_read_tr4(vbase + (16 * st + 8) * K_PITCH + 32 * db);
+                    const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[db], 0, 0, 0);
+                }
+        }
+        ASTAMP(5 + it_no * 5);
+    }
+
+    ASTAMP(60);
+    // ---- the partial results meet ----------------------------------------------------------------
+    float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    __syncthreads();  // all private tiles are dead
+    // exchange layout: float4 slot (slice, q, lane) at ((slice*16 + q)*64 + lane), q = 4 db + i/4
+    float4 *xb = (float4 *)s_dyn;
+    if (NW == 8) {
+        // stage A: wave w+4 hands its whole partial to wave w
+        if (w >= 4) {
+            if (half == 0) { s_m[w][col] = m_run; s_l[w][col] = l_tot; }
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    xb[((w - 4) * 16 + db * 4 + q) * 64 + lane] =
+                        make_float4(oacc[db][4 * q], oacc[db][4 * q + 1], oacc[db][4 * q + 2], oacc[db][4 * q + 3]);
+        }
+        __syncthreads();
+        if (w < 4) {
+            const float m2 = s_m[w + 4][col], l2 = s_l[w + 4][col];
+            const float Mn = fmaxf(m_run, m2), Mu = Mn == -INFINITY ? 0.f : Mn;
+            const float f1 = __builtin_amdgcn_exp2f((m_run - Mu) * c), f2 = __builtin_amdgcn_exp2f((m2 - Mu) * c);
+#pragma unroll
+            for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const float4 o = xb[(w * 16 + db * 4 + q) * 64 + lane];
+                    oacc[db][4 * q] = oacc[db][4 * q] * f1 + o.x * f2;
+                    oacc[db][4 * q + 1] = oacc[db][4 * q + 1] * f1 + o.y * f2;
+                    oacc[db][4 * q + 2] = oacc[db][4 * q + 2] * f1 + o.z * f2;
+                    oacc[db][4 * q + 3] = oacc[db][4 * q + 3] * f1 + o.w * f2;
+                }
+            l_tot = l_tot * f1 + l2 * f2;
+            m_run = Mn;
+        }
+        __syncthreads();
+    }
+    // stage B: waves 0..3; wave w finishes output columns [32w, 32w+32)
+    if (w < 4) {
+        if (half == 0) { s_m[w][col] = m_run; s_l[w][col] = l_tot; }
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db) {
+            if (db == w) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                xb[(w * 16 + db * 4 + q) * 64 + lane] =
+                    make_float4(oacc[db][4 * q], oacc[db][4 * q + 1], oacc[db][4 * q + 2], oacc[db][4 * q + 3]);
+        }
+    }
+    __syncthreads();
+    if (w >= 4) return;
+    float Mx = fmaxf(fmaxf(s_m[0][col], s_m[1][col]), fmaxf(s_m[2][col], s_m[3][col]));
+    const float Mu = Mx == -INFINITY ? 0.f : Mx;
+    float f[4], Lsum = 0.f;
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+        f[ww] = __builtin_amdgcn_exp2f((s_m[ww][col] - Mu) * c);
+        Lsum += f[ww] * s_l[ww][col];
+    }
+    float res[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) res[i] = 0.f;
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)  // own block (db == w) from registers; static indexing only
+        if (db == w)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) res[i] = oacc[db][i] * f[db];
+#pragma unroll
+    for (int ww = 0; ww < 4; ++ww) {
+        if (ww == w) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 o = xb[(ww * 16 + w * 4 + q) * 64 + lane];
+            res[4 * q] += o.x * f[ww];
+            res[4 * q + 1] += o.y * f[ww];
+            res[4 * q + 2] += o.z * f[ww];
+            res[4 * q + 3] += o.w * f[ww];
+        }
+    }
+    if (!qvalid) return;
+    const float inv = Lsum > 0.f ? 1.0f / Lsum : 0.f;
+    __bf16 *op = (__bf16 *)a.out + (((int64_t)b * a.TT_cap + node) * a.Hq + hq) * D + 32 * w;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(res[q4 * 4 + e] * inv);
+        *(bf16x4 *)(op + 8 * q4 + 4 * half) = o4;
+    }
+    ASTAMP(61);
 }
 
 // Merge the per-split partials: one thread per (row, 4 output columns).
@@ -348,6 +629,23 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
     const int G = a.Hq / a.Hkv;
     const int mtiles = (a.TT_cap * G + ATT_MTILE - 1) / ATT_MTILE;
     const int base_wgs = a.batch * a.Hkv * mtiles;
+    if (base_wgs < 128) {
+        // few (sequence, kv head, row tile) items: the barrier-free small-batch kernel
+        constexpr int NW = 8;
+        constexpr size_t lds = (size_t)NW * WT_ELEMS * 2;  // 152 KB: above the default 64 KB limit
+        static bool lds_opt_in = false;
+        if (!lds_opt_in) {
+            *err = hipFuncSetAttribute((const void *)attn_wave_kernel<128, NW>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (*err != hipSuccess) return DT_ERR_HIP;
+            lds_opt_in = true;
+        }
+        dim3 grid((a.TT_cap * G + 31) / 32, a.Hkv, a.batch);
+        ProfScope prof(KID_ATTN, st);
+        hipLaunchKernelGGL((attn_wave_kernel<128, NW>), grid, dim3(64 * NW), lds, st, a);
+        *err = hipGetLastError();
+        return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
+    }
     const int nb_max = (a.max_prefix_len + a.TT_cap + ATT_KB - 1) / ATT_KB;
     int splits = 1;
     if (base_wgs < 512) splits = (512 + base_wgs - 1) / base_wgs;

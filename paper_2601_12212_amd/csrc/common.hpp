@@ -87,6 +87,10 @@ __device__ __forceinline__ u64 wave_max_u64(u64 v) {
     const u32 lo = wave_max_u32((u32)(v >> 32) == hi ? (u32)v : 0u);
     return ((u64)hi << 32) | lo;
 }
+__device__ __forceinline__ u64 shfl_xor_u64(u64 v, int o) {
+    u32 lo = __shfl_xor((u32)v, o, 64), hi = __shfl_xor((u32)(v >> 32), o, 64);
+    return ((u64)hi << 32) | lo;
+}
 __device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
     u32 lo = __builtin_amdgcn_readlane((u32)v, lane), hi = __builtin_amdgcn_readlane((u32)(v >> 32), lane);
     return ((u64)hi << 32) | lo;

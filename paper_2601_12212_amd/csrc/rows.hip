@@ -393,10 +393,12 @@ int rows_topk_nl(int V) {
     return 4;
 }
 
-// Chunk multiplier for the arg max rows: enough workgroups to cover the chip, else smaller chunks.
+// Chunk multiplier for the arg max rows: few, fat chunks (the acceptance kernel merges the
+// chunks of a row, and measured kernel time does not depend on the chunk size), but at least
+// about one workgroup per compute unit.
 int rows_pick_nl(int64_t n_rows, int V) {
     for (int nl = 4; nl > 1; nl >>= 1)
-        if (n_rows * rows_chunks_per_row(V, nl) >= 2048) return nl;
+        if (n_rows * rows_chunks_per_row(V, nl) >= 256) return nl;
     return 1;
 }
 
