@@ -15,7 +15,8 @@
  *     enqueued on it and the call returns immediately; outputs are valid once the stream
  *     has reached that point.
  *   - `ws` is caller-owned device scratch of at least dt_workspace_bytes() bytes, 256-byte
- *     aligned.  Calls that share one workspace must be ordered on one stream.
+ *     aligned; its contents need not survive between calls.  Calls that share one workspace
+ *     must be ordered on one stream.
  *   - Per-sequence limits live in a DEVICE array of dt_params so that a policy running on
  *     the GPU can set them without a host round trip.  Values are clamped on the device
  *     to 1 <= TT <= TT_cap, 1 <= d <= DT_D_MAX, 1 <= k <= min(DT_K_MAX, V).

@@ -135,11 +135,12 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     if (total_rows < batch) return DT_ERR_INVALID_ARG;  // every sequence owns at least its root row
     const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
-    TopkScratch rs = topk_scratch(ws, total_rows, S);
+    char *wsd = (char *)ws;
+    TopkScratch rs = topk_scratch(wsd, total_rows, S);
     size_t off = rs.bytes;
-    float *top_val = (float *)((char *)ws + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
-    int32_t *top_id = (int32_t *)((char *)ws + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
-    float *lse = (float *)((char *)ws + off); off += align_up((size_t)total_rows * 4);
+    float *top_val = (float *)(wsd + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
+    int32_t *top_id = (int32_t *)(wsd + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
+    float *lse = (float *)(wsd + off); off += align_up((size_t)total_rows * 4);
     if (off > ws_bytes) return DT_ERR_WORKSPACE;
 
     dt::RowArgs a = {};

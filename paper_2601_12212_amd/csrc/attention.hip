@@ -12,6 +12,8 @@
 //
 // fp32 path: plain ALU kernel, one wave per (node, head); a correctness path for small
 // problems and for head sizes the MFMA path does not cover.
+#include <cstdlib>
+
 #include "common.hpp"
 #include "kernels.hpp"
 
@@ -237,12 +239,21 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
 #define WT_ELEMS (2 * KT_ELEMS)        // both tiles of a wave: 17 KB
 typedef const char __attribute__((address_space(1))) *gbytep;
 
+// With KS > 1 the key blocks are additionally dealt over KS workgroups per (sequence, kv head,
+// row block); each leaves its partial (max, sum, O) in global scratch for a small merge kernel.
+// (Merging in the last workgroup to arrive was tried: the device-scope release/acquire it needs
+// writes back and invalidates the whole L2 of the XCD and cost far more than a second launch.)
+struct SplitBuf {
+    float4 *o;    // [unit, KS, 4 waves, 4, 64 lanes]: the owner waves' output registers
+    float2 *ml;   // [unit, KS, 32]: (max, sum) per query row
+};
+
 template <int D, int NW>
-__global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, SplitBuf sb) {
     static_assert(D == 128 && (NW == 4 || NW == 8), "shape");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     const int G = a.Hq / a.Hkv;
-    const int b = blockIdx.z, h = blockIdx.y;
+    const int b = blockIdx.z / KS, ks = blockIdx.z % KS, h = blockIdx.y;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
     const int M = N * G;
     const int m0 = blockIdx.x * 32;
@@ -322,10 +333,11 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a) {
     };
 
     ASTAMP(0);
-    int kb = w;
+    const int kstep = KS * NW;  // the blocks are dealt round-robin over all waves of all splits
+    int kb = ks * NW + w;
     if (kb < nb) fetch(kb);
     int it_no = 0;
-    for (; kb < nb; kb += NW, ++it_no) {
+    for (; kb < nb; kb += kstep, ++it_no) {
         ASTAMP(1 + it_no * 5);
         // The prefetched block goes straight into the wave's two LDS tiles, both row-major, which
         // frees its registers for the next prefetch, issued before any arithmetic on this block.
@@ -335,7 +347,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a) {
             *(bf16x8 *)(kt + r) = kn[i];
             *(bf16x8 *)(vt + r) = vn[i];
         }
-        if (kb + NW < nb) fetch(kb + NW);
+        if (kb + kstep < nb) fetch(kb + kstep);
         ASTAMP(2 + it_no * 5);
 
         f32x16 sacc;
@@ -350,12 +362,20 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a) {
 
         const int tbase = kb * ATT_KB;
         if (tbase + ATT_KB > L) {  // only blocks that contain tree keys (or the end) need the mask
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int j = tbase + 8 * (i >> 2) + 4 * half + (i & 3) - L;
-                const bool vis = j < 0 || (j < N && (((j < 64 ? mask0 : mask1) >> (j & 63)) & 1ull));
-                sacc[i] = vis ? sacc[i] : -INFINITY;
+            // 32-bit visibility window of this lane's query over keys tbase .. tbase+31: prefix keys
+            // are visible, tree key j is visible iff bit j of the node's ancestor set (bits >= N are 0)
+            const int off = tbase - L;  // uniform
+            u32 vis;
+            if (off >= 0) {
+                const u64 lo = off < 64 ? mask0 : mask1, hi = off < 64 ? mask1 : 0ull;
+                const int sh = off & 63;
+                vis = (u32)((lo >> sh) | (sh ? hi << (64 - sh) : 0ull));
+            } else {
+                vis = ((u32)mask0 << (-off)) | ((1u << (-off)) - 1u);
             }
+            vis >>= 4 * half;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[i] = ((vis >> (8 * (i >> 2) + (i & 3))) & 1u) ? sacc[i] : -INFINITY;
         }
         float mloc = sacc[0];
 #pragma unroll
@@ -481,6 +501,15 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a) {
             res[4 * q + 3] += o.w * f[ww];
         }
     }
+    if (KS > 1) {
+        // ---- leave this workgroup's partial for the merge kernel ---------------------------------
+        const int64_t unit = ((int64_t)b * a.Hkv + h) * gridDim.x + blockIdx.x;
+        float4 *pw = sb.o + ((unit * KS + ks) * 4 + w) * 4 * 64;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) pw[q * 64 + lane] = make_float4(res[4 * q], res[4 * q + 1], res[4 * q + 2], res[4 * q + 3]);
+        if (w == 0 && half == 0) sb.ml[(unit * KS + ks) * 32 + col] = make_float2(Mx, Lsum);
+        return;
+    }
     if (!qvalid) return;
     const float inv = Lsum > 0.f ? 1.0f / Lsum : 0.f;
     __bf16 *op = (__bf16 *)a.out + (((int64_t)b * a.TT_cap + node) * a.Hq + hq) * D + 32 * w;
@@ -492,6 +521,55 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a) {
         *(bf16x4 *)(op + 8 * q4 + 4 * half) = o4;
     }
     ASTAMP(61);
+}
+
+// Merge of the KS partials of every (sequence, kv head, 32-row block): thread (w, lane) owns the
+// same 16 output values it would own in the single-split epilogue, so the partials are read
+// back in exactly the layout they were written in.
+template <int D>
+__global__ __launch_bounds__(256) void attn_wave_merge_kernel(AttnArgs a, int KS, SplitBuf sb) {
+    const int G = a.Hq / a.Hkv;
+    const int b = blockIdx.z, h = blockIdx.y;
+    const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
+    const int M = N * G;
+    const int m0 = blockIdx.x * 32;
+    if (m0 >= M) return;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int half = lane >> 5, col = lane & 31;
+    const int mq = m0 + col;
+    if (mq >= M) return;
+    const int node = mq / G, hq = h * G + mq % G;
+    const float c = a.scale * 1.4426950408889634f;
+    const int64_t unit = ((int64_t)b * a.Hkv + h) * gridDim.x + blockIdx.x;
+    float Mall = -INFINITY;
+    for (int s2 = 0; s2 < KS; ++s2) Mall = fmaxf(Mall, sb.ml[(unit * KS + s2) * 32 + col].x);
+    const float Ma = Mall == -INFINITY ? 0.f : Mall;
+    float res[16], Lsum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) res[i] = 0.f;
+    for (int s2 = 0; s2 < KS; ++s2) {
+        const float2 ml = sb.ml[(unit * KS + s2) * 32 + col];
+        const float fs = __builtin_amdgcn_exp2f((ml.x - Ma) * c);
+        Lsum += ml.y * fs;
+        const float4 *pr = sb.o + ((unit * KS + s2) * 4 + w) * 4 * 64;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 o = pr[q * 64 + lane];
+            res[4 * q] += o.x * fs;
+            res[4 * q + 1] += o.y * fs;
+            res[4 * q + 2] += o.z * fs;
+            res[4 * q + 3] += o.w * fs;
+        }
+    }
+    const float inv = Lsum > 0.f ? 1.0f / Lsum : 0.f;
+    __bf16 *op = (__bf16 *)a.out + (((int64_t)b * a.TT_cap + node) * a.Hq + hq) * D + 32 * w;
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+        bf16x4 o4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(res[q4 * 4 + e] * inv);
+        *(bf16x4 *)(op + 8 * q4 + 4 * half) = o4;
+    }
 }
 
 // Merge the per-split partials: one thread per (row, 4 output columns).
@@ -631,18 +709,50 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
     const int base_wgs = a.batch * a.Hkv * mtiles;
     if (base_wgs < 128) {
         // few (sequence, kv head, row tile) items: the barrier-free small-batch kernel
-        constexpr int NW = 8;
-        constexpr size_t lds = (size_t)NW * WT_ELEMS * 2;  // 152 KB: above the default 64 KB limit
+        // Key splits: towards one workgroup per compute unit, but only while a split still owns
+        // about 20 key blocks -- below that the fixed cost of a workgroup (query load, first
+        // fetch, LDS exchange) plus the merge launch outweighs the shorter loop (measured).
+        const int mblocks = (a.TT_cap * G + 31) / 32;
+        const int units = a.batch * a.Hkv * mblocks;
+        const int nb_max = (a.max_prefix_len + a.TT_cap + ATT_KB - 1) / ATT_KB;
+        int KS = 256 / units;
+        if (KS > 8) KS = 8;
+        if (KS > nb_max / 20) KS = nb_max / 20;
+        const size_t per_split = (size_t)units * (4 * 4 * 64 * 16 + 32 * 8);
+        if (KS > 1 && (!a.ws || (size_t)KS * per_split > a.ws_bytes)) KS = a.ws ? (int)(a.ws_bytes / per_split) : 1;
+        if (KS < 1) KS = 1;
+        int nw_sel = KS > 1 ? 4 : 8;
+#ifdef DT_TIMESTAMPS
+        if (const char *e = getenv("DT_KS")) { KS = atoi(e); }
+        if (const char *e = getenv("DT_NW")) { nw_sel = atoi(e); }
+#endif
+        SplitBuf sb;
+        sb.o = (float4 *)a.ws;
+        sb.ml = (float2 *)((char *)a.ws + (size_t)units * KS * 4 * 4 * 64 * 16);
+        dim3 grid(mblocks, a.Hkv, a.batch * KS);
         static bool lds_opt_in = false;
         if (!lds_opt_in) {
-            *err = hipFuncSetAttribute((const void *)attn_wave_kernel<128, NW>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            *err = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 8>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 8 * WT_ELEMS * 2);
+            if (*err == hipSuccess)
+                *err = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 4>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 4 * WT_ELEMS * 2);
             if (*err != hipSuccess) return DT_ERR_HIP;
             lds_opt_in = true;
         }
-        dim3 grid((a.TT_cap * G + 31) / 32, a.Hkv, a.batch);
-        ProfScope prof(KID_ATTN, st);
-        hipLaunchKernelGGL((attn_wave_kernel<128, NW>), grid, dim3(64 * NW), lds, st, a);
+        {
+            ProfScope prof(KID_ATTN, st);
+            if (nw_sel == 4)  // several workgroups per unit: four waves each (two workgroups fit a compute unit)
+                hipLaunchKernelGGL((attn_wave_kernel<128, 4>), grid, dim3(256), 4 * WT_ELEMS * 2, st, a, KS, sb);
+            else         // one workgroup per unit: eight waves (two per SIMD), 136 KB of LDS
+                hipLaunchKernelGGL((attn_wave_kernel<128, 8>), grid, dim3(512), 8 * WT_ELEMS * 2, st, a, KS, sb);
+        }
+        if (KS > 1) {
+            *err = hipGetLastError();
+            if (*err != hipSuccess) return DT_ERR_HIP;
+            ProfScope prof(KID_ATTN_COMBINE, st);
+            hipLaunchKernelGGL(attn_wave_merge_kernel<128>, dim3(mblocks, a.Hkv, a.batch), dim3(256), 0, st, a, KS, sb);
+        }
         *err = hipGetLastError();
         return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
     }

@@ -173,6 +173,13 @@ def test_empty_prefix_and_tt1_decode_and_fp32_heads():
     check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [65], dtype="bf16", D=64, Hq=4, Hkv=1)))  # simple path
 
 
+def test_attention_key_splits_and_long_prefix():
+    # few (sequence, kv head) pairs and a long prefix: the small-batch kernel splits the keys over
+    # several workgroups and a merge kernel joins the partials
+    check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [2000], Hq=8, Hkv=2)))
+    check_case(oracle_case(0, cfg=small_cfg([(128, 6, 6), (7, 2, 3)], [4097, 640], Hq=4, Hkv=4)), sample_attention=300)
+
+
 def test_stochastic_small_and_many_steps():
     cfg = small_cfg([(40, 5, 4), (64, 6, 6)], [100, 31], V=3001, mode=dt_synth.STOCHASTIC)
     case = oracle_case(0, cfg=cfg)
