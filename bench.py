@@ -51,6 +51,9 @@ def main():
     ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=400)
+    ap.add_argument("--calibration-copy-mb", type=int, default=0,
+                    help="also run a plain device copy of this many MB (a kernel of known traffic, for scaling "
+                         "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding "
@@ -176,11 +179,41 @@ def main():
             v["gbps"] = kbytes[name] / (v["avg_us"] * 1e-6) / 1e9
         log("  kernel %-20s avg %8.2f us  x%.0f/step%s" % (name, v["avg_us"], v["launches_per_step"],
                                                             "  %.0f GB/s" % v["gbps"] if "gbps" in v else ""))
-    dom = max((n for n in kern if n in kbytes), key=lambda n: kern[n]["avg_us"] * kern[n]["launches_per_step"])
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(kern[dom]["gbps"], 1), "peak": HBM_PEAK_GBPS,
-                "unit": "GB/s", "frac": round(kern[dom]["gbps"] / HBM_PEAK_GBPS, 4), "traffic": None,
-                "bytes_per_launch": kbytes[dom], "avg_us": round(kern[dom]["avg_us"], 3),
-                "timing": "HIP events around each launch, %d profiled steps, inputs rotated" % P}
+    # HBM traffic per launch from the committed rocprofv3 --pmc summary of this workload, if present
+    traffic = {}
+    pmc_path = os.path.join(ROOT, "profiles", "pmc_%s.json" % cfg.name)
+    if os.path.exists(pmc_path):
+        pk = json.load(open(pmc_path))["kernels"]
+        for ours, prefix in (("rows_target_chunk", "dt::row_argmax_kernel"), ("rows_draft_chunk", "dt::row_stream_kernel"),
+                             ("attention", "dt::attn_")):
+            hit = [v for k, v in pk.items() if k.startswith(prefix)]
+            if hit:
+                traffic[ours] = sum(v["hbm_bytes"] for v in hit)
+
+    def roof(name):
+        v = kern[name]
+        return {"bound": "hbm", "kernel": name, "achieved": round(v["gbps"], 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(v["gbps"] / HBM_PEAK_GBPS, 4), "traffic": traffic.get(name),
+                "bytes_per_launch": kbytes[name], "avg_us": round(v["avg_us"], 3)}
+
+    with_bytes = [n for n in kern if n in kbytes]
+    # the dominant kernel: the one that takes the most time among those that move the step's data
+    dom = max(with_bytes, key=lambda n: kern[n]["avg_us"] * kern[n]["launches_per_step"])
+    roofline = roof(dom)
+    roofline["timing"] = ("HIP events attached to each dispatch, %d profiled steps, %d rotating input sets"
+                          % (P, R))
+    roofline["traffic_source"] = os.path.relpath(pmc_path, ROOT) if traffic else None
+    roofline_all = [roof(n) for n in sorted(with_bytes, key=lambda n: -kbytes[n])]
+
+    if args.calibration_copy_mb > 0:
+        n = args.calibration_copy_mb * 1000 * 1000 // 4
+        src = torch.arange(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(4):
+            dst.copy_(src)          # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        log("calibration copy: 4 launches of %d bytes read + %d bytes written" % (n * 4, n * 4))
 
     # ---- the oracle on the host cores, same inputs -------------------------------------------------
     cpu = None
@@ -224,6 +257,7 @@ def main():
         "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                     for k, v in kern.items()},
         "roofline": roofline,
+        "roofline_all_streams": roofline_all,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

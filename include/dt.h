@@ -172,7 +172,8 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
 /*
  * Optional per-kernel timing, for measurement only (off by default; not part of the step).
  * dt_profile_enable(n > 0) pre-creates n HIP event pairs and switches timing on: every kernel
- * launched by the calls above is then bracketed by an event pair on its stream.
+ * launched by the calls above then carries an event pair on its dispatch that records the
+ * kernel's own begin and end (not usable while the stream is being captured into a graph).
  * dt_profile_enable(0) switches it off.  dt_profile_read sums, for one kernel id
  * (0 draft row chunks, 1 row merge, 2 tree, 3 attention, 4 attention combine, 5 target row
  * chunks, 6 accept, 7 dt_topk_rows chunks), the elapsed milliseconds of the launches recorded

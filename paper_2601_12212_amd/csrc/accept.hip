@@ -234,8 +234,7 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
 
 hipError_t accept_launch(const AcceptArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;
-    ProfScope prof(KID_ACCEPT, st);
-    hipLaunchKernelGGL(accept_kernel, dim3(a.batch), dim3(256), 0, st, a);
+    launch_kernel(KID_ACCEPT, st, accept_kernel, dim3(a.batch), dim3(256), 0, a);
     return hipGetLastError();
 }
 

@@ -76,10 +76,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
     static_assert(D == 128, "head dim");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     const int G = a.Hq / a.Hkv;
-    const int b = blockIdx.z / splits, sp = blockIdx.z % splits, h = blockIdx.y;
+    // blockIdx.x = kv head: workgroups are dealt to the 8 XCDs round-robin by linear id, so all
+    // row tiles and splits of one kv head land on one XCD and share its L2 copy of that head's K/V
+    const int b = blockIdx.z / splits, sp = blockIdx.z % splits, h = blockIdx.x;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
     const int M = N * G;
-    const int m0 = blockIdx.x * ATT_MTILE;
+    const int m0 = blockIdx.y * ATT_MTILE;
     if (m0 >= M) return;
     const int L = max(a.prefix_len[b], 0);
     const int Tk = L + N;
@@ -253,10 +255,12 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
     static_assert(D == 128 && (NW == 4 || NW == 8), "shape");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     const int G = a.Hq / a.Hkv;
-    const int b = blockIdx.z / KS, ks = blockIdx.z % KS, h = blockIdx.y;
+    // blockIdx.x = kv head: workgroups are dealt to the 8 XCDs round-robin by linear id, so every
+    // row block and split of one kv head lands on one XCD and shares its L2 copy of that head's K/V
+    const int b = blockIdx.z / KS, ks = blockIdx.z % KS, h = blockIdx.x;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
     const int M = N * G;
-    const int m0 = blockIdx.x * 32;
+    const int m0 = blockIdx.y * 32;
     if (m0 >= M) return;
     const int L = max(a.prefix_len[b], 0);
     const int Tk = L + N;
@@ -503,7 +507,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
     }
     if (KS > 1) {
         // ---- leave this workgroup's partial for the merge kernel ---------------------------------
-        const int64_t unit = ((int64_t)b * a.Hkv + h) * gridDim.x + blockIdx.x;
+        const int64_t unit = ((int64_t)b * a.Hkv + h) * gridDim.y + blockIdx.y;
         float4 *pw = sb.o + ((unit * KS + ks) * 4 + w) * 4 * 64;
 #pragma unroll
         for (int q = 0; q < 4; ++q) pw[q * 64 + lane] = make_float4(res[4 * q], res[4 * q + 1], res[4 * q + 2], res[4 * q + 3]);
@@ -529,10 +533,10 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
 template <int D>
 __global__ __launch_bounds__(256) void attn_wave_merge_kernel(AttnArgs a, int KS, SplitBuf sb) {
     const int G = a.Hq / a.Hkv;
-    const int b = blockIdx.z, h = blockIdx.y;
+    const int b = blockIdx.z, h = blockIdx.x;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
     const int M = N * G;
-    const int m0 = blockIdx.x * 32;
+    const int m0 = blockIdx.y * 32;
     if (m0 >= M) return;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int half = lane >> 5, col = lane & 31;
@@ -540,7 +544,7 @@ __global__ __launch_bounds__(256) void attn_wave_merge_kernel(AttnArgs a, int KS
     if (mq >= M) return;
     const int node = mq / G, hq = h * G + mq % G;
     const float c = a.scale * 1.4426950408889634f;
-    const int64_t unit = ((int64_t)b * a.Hkv + h) * gridDim.x + blockIdx.x;
+    const int64_t unit = ((int64_t)b * a.Hkv + h) * gridDim.y + blockIdx.y;
     float Mall = -INFINITY;
     for (int s2 = 0; s2 < KS; ++s2) Mall = fmaxf(Mall, sb.ml[(unit * KS + s2) * 32 + col].x);
     const float Ma = Mall == -INFINITY ? 0.f : Mall;
@@ -698,9 +702,8 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
     if (!mfma) {
         if (a.D > 128) return DT_ERR_LIMIT;
         dim3 grid(a.TT_cap, a.Hq, a.batch);
-        ProfScope prof(KID_ATTN, st);
-        if (a.dtype == DT_BF16) hipLaunchKernelGGL(attn_simple_kernel<uint16_t>, grid, dim3(64), 0, st, a);
-        else hipLaunchKernelGGL(attn_simple_kernel<float>, grid, dim3(64), 0, st, a);
+        if (a.dtype == DT_BF16) launch_kernel(KID_ATTN, st, attn_simple_kernel<uint16_t>, grid, dim3(64), 0, a);
+        else launch_kernel(KID_ATTN, st, attn_simple_kernel<float>, grid, dim3(64), 0, a);
         *err = hipGetLastError();
         return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
     }
@@ -729,7 +732,7 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
         SplitBuf sb;
         sb.o = (float4 *)a.ws;
         sb.ml = (float2 *)((char *)a.ws + (size_t)units * KS * 4 * 4 * 64 * 16);
-        dim3 grid(mblocks, a.Hkv, a.batch * KS);
+        dim3 grid(a.Hkv, mblocks, a.batch * KS);
         static bool lds_opt_in = false;
         if (!lds_opt_in) {
             *err = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 8>,
@@ -740,18 +743,15 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
             if (*err != hipSuccess) return DT_ERR_HIP;
             lds_opt_in = true;
         }
-        {
-            ProfScope prof(KID_ATTN, st);
-            if (nw_sel == 4)  // several workgroups per unit: four waves each (two workgroups fit a compute unit)
-                hipLaunchKernelGGL((attn_wave_kernel<128, 4>), grid, dim3(256), 4 * WT_ELEMS * 2, st, a, KS, sb);
-            else         // one workgroup per unit: eight waves (two per SIMD), 136 KB of LDS
-                hipLaunchKernelGGL((attn_wave_kernel<128, 8>), grid, dim3(512), 8 * WT_ELEMS * 2, st, a, KS, sb);
-        }
+        if (nw_sel == 4)  // several workgroups per unit: four waves each (two workgroups fit a compute unit)
+            launch_kernel(KID_ATTN, st, attn_wave_kernel<128, 4>, grid, dim3(256), 4 * WT_ELEMS * 2, a, KS, sb);
+        else              // one workgroup per unit: eight waves (two per SIMD), 136 KB of LDS
+            launch_kernel(KID_ATTN, st, attn_wave_kernel<128, 8>, grid, dim3(512), 8 * WT_ELEMS * 2, a, KS, sb);
         if (KS > 1) {
             *err = hipGetLastError();
             if (*err != hipSuccess) return DT_ERR_HIP;
-            ProfScope prof(KID_ATTN_COMBINE, st);
-            hipLaunchKernelGGL(attn_wave_merge_kernel<128>, dim3(mblocks, a.Hkv, a.batch), dim3(256), 0, st, a, KS, sb);
+            launch_kernel(KID_ATTN_COMBINE, st, attn_wave_merge_kernel<128>, dim3(a.Hkv, mblocks, a.batch), dim3(256), 0,
+                          a, KS, sb);
         }
         *err = hipGetLastError();
         return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
@@ -767,20 +767,14 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
     Partial part;
     part.o = (float *)a.ws;
     part.ml = (float2 *)((char *)a.ws + (size_t)a.batch * splits * a.TT_cap * a.Hq * a.D * 4);
-    dim3 grid(mtiles, a.Hkv, a.batch * splits);
-    {
-        ProfScope prof(KID_ATTN, st);
-        hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, dim3(256), 0, st, a, splits, part);
-    }
+    dim3 grid(a.Hkv, mtiles, a.batch * splits);
+    launch_kernel(KID_ATTN, st, attn_mfma_kernel<128>, grid, dim3(256), 0, a, splits, part);
     *err = hipGetLastError();
     if (*err != hipSuccess) return DT_ERR_HIP;
     if (splits > 1) {
         const int64_t items = (int64_t)a.TT_cap * a.Hq * (a.D / 4);
         dim3 cgrid((unsigned)((items + 255) / 256), a.batch);
-        {
-            ProfScope prof(KID_ATTN_COMBINE, st);
-            hipLaunchKernelGGL(attn_combine_kernel<128>, cgrid, dim3(256), 0, st, a, splits, part);
-        }
+        launch_kernel(KID_ATTN_COMBINE, st, attn_combine_kernel<128>, cgrid, dim3(256), 0, a, splits, part);
         *err = hipGetLastError();
         if (*err != hipSuccess) return DT_ERR_HIP;
     }

@@ -1,5 +1,6 @@
 // Internal interfaces between the C ABI (api.cpp) and the kernel files.
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -8,18 +9,19 @@
 namespace dt {
 
 // ---------------------------------------------------------- per-kernel timing (profile.cpp)
-// Off by default.  When switched on (dt_profile_enable), every launch is bracketed by a pair
-// of pre-created HIP events on the launch stream; dt_profile_read sums the elapsed times.
+// Off by default.  When switched on (dt_profile_enable), every kernel is launched with a pair
+// of pre-created HIP events attached to its dispatch (hipExtLaunchKernelGGL), which record the
+// kernel's own begin and end; dt_profile_read sums the elapsed times per kernel id.
 enum KernelId { KID_ROWS_DRAFT = 0, KID_ROWS_MERGE, KID_TREE, KID_ATTN, KID_ATTN_COMBINE, KID_ROWS_TARGET,
                 KID_ACCEPT, KID_ROWS_UNIFORM, KID_COUNT };
-void prof_begin(int kid, hipStream_t st);
-void prof_end(int kid, hipStream_t st);
-struct ProfScope {
-    int kid;
-    hipStream_t st;
-    ProfScope(int k, hipStream_t s) : kid(k), st(s) { prof_begin(kid, st); }
-    ~ProfScope() { prof_end(kid, st); }
-};
+bool prof_next(int kid, hipEvent_t *start, hipEvent_t *stop);  // false when timing is off
+
+template <typename F, typename... Args>
+inline void launch_kernel(int kid, hipStream_t st, F kernel, dim3 grid, dim3 block, size_t lds, Args... args) {
+    hipEvent_t e0, e1;
+    if (prof_next(kid, &e0, &e1)) hipExtLaunchKernelGGL(kernel, grid, block, (unsigned)lds, st, e0, e1, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, (unsigned)lds, st, args...);
+}
 
 // ------------------------------------------------------------------ row kernels (rows.hip)
 enum RowMode { ROWS_UNIFORM = 0, ROWS_DRAFT = 1, ROWS_TARGET = 2 };

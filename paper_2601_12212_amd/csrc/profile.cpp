@@ -1,6 +1,6 @@
-// Optional per-kernel timing with HIP events on the launch stream (used by the benchmark to
-// report the achieved bandwidth of individual kernels).  Events are created when profiling
-// is switched on, never on the launch path.
+// Optional per-kernel timing (used by the benchmark to report the achieved bandwidth of
+// individual kernels): HIP events attached to each kernel dispatch record its begin and end.
+// Events are created when profiling is switched on, never on the launch path.
 #include <hip/hip_runtime.h>
 
 #include <vector>
@@ -15,27 +15,23 @@ bool g_on = false;
 std::vector<Pair> g_pool;            // pre-created pairs
 std::vector<int> g_used[dt::KID_COUNT];  // indices into g_pool, per kernel id
 size_t g_next = 0;
-int g_open[dt::KID_COUNT];
 }  // namespace
 
 namespace dt {
-void prof_begin(int kid, hipStream_t st) {
-    if (!g_on || g_next >= g_pool.size()) { if (g_on) g_open[kid] = -1; return; }
-    g_open[kid] = (int)g_next++;
-    (void)hipEventRecord(g_pool[g_open[kid]].a, st);
-}
-void prof_end(int kid, hipStream_t st) {
-    if (!g_on || g_open[kid] < 0) return;
-    (void)hipEventRecord(g_pool[g_open[kid]].b, st);
-    g_used[kid].push_back(g_open[kid]);
-    g_open[kid] = -1;
+bool prof_next(int kid, hipEvent_t *start, hipEvent_t *stop) {
+    if (!g_on || g_next >= g_pool.size()) return false;
+    const int idx = (int)g_next++;
+    *start = g_pool[idx].a;
+    *stop = g_pool[idx].b;
+    g_used[kid].push_back(idx);
+    return true;
 }
 }  // namespace dt
 
 extern "C" {
 
 int dt_profile_enable(int max_launches) {
-    for (int k = 0; k < dt::KID_COUNT; ++k) { g_used[k].clear(); g_open[k] = -1; }
+    for (int k = 0; k < dt::KID_COUNT; ++k) g_used[k].clear();
     g_next = 0;
     if (max_launches <= 0) { g_on = false; return DT_OK; }
     while ((int)g_pool.size() < max_launches) {

@@ -407,15 +407,15 @@ static bool rows_vec_ok(const RowArgs &a) {
     return ((uintptr_t)a.logits % 16 == 0) && ((a.row_stride * esz) % 16 == 0);
 }
 
-#define DT_ROWS_DISPATCH(KERNEL, NLV)                                                                     \
+#define DT_ROWS_DISPATCH(KID, KERNEL, NLV)                                                                \
     do {                                                                                                  \
         dim3 grid(rows_chunks_per_row(a.V, NLV), (unsigned)n_rows);                                       \
         if (a.dtype == DT_BF16) {                                                                         \
-            if (vec) hipLaunchKernelGGL((KERNEL<NLV, true, true>), grid, dim3(256), 0, st, a);            \
-            else hipLaunchKernelGGL((KERNEL<NLV, true, false>), grid, dim3(256), 0, st, a);               \
+            if (vec) launch_kernel(KID, st, KERNEL<NLV, true, true>, grid, dim3(256), 0, a);              \
+            else launch_kernel(KID, st, KERNEL<NLV, true, false>, grid, dim3(256), 0, a);                 \
         } else {                                                                                          \
-            if (vec) hipLaunchKernelGGL((KERNEL<NLV, false, true>), grid, dim3(256), 0, st, a);           \
-            else hipLaunchKernelGGL((KERNEL<NLV, false, false>), grid, dim3(256), 0, st, a);              \
+            if (vec) launch_kernel(KID, st, KERNEL<NLV, false, true>, grid, dim3(256), 0, a);             \
+            else launch_kernel(KID, st, KERNEL<NLV, false, false>, grid, dim3(256), 0, a);                \
         }                                                                                                 \
     } while (0)
 
@@ -423,11 +423,11 @@ static bool rows_vec_ok(const RowArgs &a) {
 hipError_t rows_launch_stream(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
     const bool vec = rows_vec_ok(a);
-    ProfScope prof(a.mode == ROWS_DRAFT ? KID_ROWS_DRAFT : KID_ROWS_UNIFORM, st);
+    const int kid = a.mode == ROWS_DRAFT ? KID_ROWS_DRAFT : KID_ROWS_UNIFORM;
     switch (nl) {
-        case 4: DT_ROWS_DISPATCH(row_stream_kernel, 4); break;
-        case 2: DT_ROWS_DISPATCH(row_stream_kernel, 2); break;
-        default: DT_ROWS_DISPATCH(row_stream_kernel, 1); break;
+        case 4: DT_ROWS_DISPATCH(kid, row_stream_kernel, 4); break;
+        case 2: DT_ROWS_DISPATCH(kid, row_stream_kernel, 2); break;
+        default: DT_ROWS_DISPATCH(kid, row_stream_kernel, 1); break;
     }
     return hipGetLastError();
 }
@@ -437,13 +437,12 @@ hipError_t rows_launch_select(const RowArgs &a, int64_t n_rows, int nl, float *t
                               int out_stride, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
     const int S = rows_chunks_per_row(a.V, nl);
-    ProfScope prof(KID_ROWS_MERGE, st);
     if (a.dtype == DT_BF16)
-        hipLaunchKernelGGL(row_select_kernel<true>, dim3((unsigned)n_rows), dim3(256), 0, st, a, nl, S, top_val, top_id,
-                           lse, out_stride);
+        launch_kernel(KID_ROWS_MERGE, st, row_select_kernel<true>, dim3((unsigned)n_rows), dim3(256), 0, a, nl, S,
+                      top_val, top_id, lse, out_stride);
     else
-        hipLaunchKernelGGL(row_select_kernel<false>, dim3((unsigned)n_rows), dim3(256), 0, st, a, nl, S, top_val,
-                           top_id, lse, out_stride);
+        launch_kernel(KID_ROWS_MERGE, st, row_select_kernel<false>, dim3((unsigned)n_rows), dim3(256), 0, a, nl, S,
+                      top_val, top_id, lse, out_stride);
     return hipGetLastError();
 }
 
@@ -451,11 +450,10 @@ hipError_t rows_launch_select(const RowArgs &a, int64_t n_rows, int nl, float *t
 hipError_t rows_launch_argmax(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
     const bool vec = rows_vec_ok(a);
-    ProfScope prof(KID_ROWS_TARGET, st);
     switch (nl) {
-        case 4: DT_ROWS_DISPATCH(row_argmax_kernel, 4); break;
-        case 2: DT_ROWS_DISPATCH(row_argmax_kernel, 2); break;
-        default: DT_ROWS_DISPATCH(row_argmax_kernel, 1); break;
+        case 4: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 4); break;
+        case 2: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 2); break;
+        default: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 1); break;
     }
     return hipGetLastError();
 }

@@ -306,8 +306,7 @@ extern "C" int dt_debug_stamps(unsigned long long *out) {
 
 hipError_t tree_launch(const TreeArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;
-    ProfScope prof(KID_TREE, st);
-    hipLaunchKernelGGL(tree_kernel, dim3(a.batch), dim3(256), 0, st, a);
+    launch_kernel(KID_TREE, st, tree_kernel, dim3(a.batch), dim3(256), 0, a);
     return hipGetLastError();
 }
 
