@@ -34,7 +34,7 @@ __device__ __forceinline__ u32 score_key(float s) { return ord32(s); }
 // (three independent probe counts per step, all on ballots), then visit the winners in ascending
 // index: f(index, position).  Absent items hold key 0, which no probe (>= 1) ever counts.
 template <int ITEMS, typename F>
-__device__ __forceinline__ int wave_select_t(const float *score, int n, int keep_max, Cut *cut_out, F f) {
+__device__ __forceinline__ int wave_select_t(const float *score, int n, int keep_max, Cut *cut_out, u32 *scratch, F f) {
     const int lane = lane_id();
     u32 it[ITEMS];
     int viable = 0;
@@ -50,17 +50,66 @@ __device__ __forceinline__ int wave_select_t(const float *score, int n, int keep
     c.need_eq = 0;
     if (keep > 0) {
         u32 t = 0;
+        if (ITEMS <= 2) {
+            // few registers per lane: two bits per step (three independent probe counts)
 #pragma unroll 1
-        for (int bit = 30; bit >= 0; bit -= 2) {
-            const u32 c1 = t | (1u << bit), c2 = t | (2u << bit), c3 = t | (3u << bit);
-            int n1 = 0, n2 = 0, n3 = 0;
+            for (int bit = 30; bit >= 0; bit -= 2) {
+                const u32 c1 = t | (1u << bit), c2 = t | (2u << bit), c3 = t | (3u << bit);
+                int n1 = 0, n2 = 0, n3 = 0;
+#pragma unroll
+                for (int j = 0; j < ITEMS; ++j) {
+                    n1 += __popcll(__ballot(it[j] >= c1));
+                    n2 += __popcll(__ballot(it[j] >= c2));
+                    n3 += __popcll(__ballot(it[j] >= c3));
+                }
+                t = n3 >= keep ? c3 : n2 >= keep ? c2 : n1 >= keep ? c1 : t;
+            }
+        } else {
+            // many registers per lane: settle the upper 16 key bits on all of them, then only the
+            // handful of keys that share that prefix (compacted to one per lane) decide the rest
+#pragma unroll 1
+            for (int bit = 31; bit >= 16; --bit) {
+                const u32 c1 = t | (1u << bit);
+                int n1 = 0;
+#pragma unroll
+                for (int j = 0; j < ITEMS; ++j) n1 += __popcll(__ballot(it[j] >= c1));
+                t = n1 >= keep ? c1 : t;
+            }
+            int above = 0, nb = 0;
+            u32 bk = 0u;  // boundary key of this lane
+            bool one_per_lane = true;
 #pragma unroll
             for (int j = 0; j < ITEMS; ++j) {
-                n1 += __popcll(__ballot(it[j] >= c1));
-                n2 += __popcll(__ballot(it[j] >= c2));
-                n3 += __popcll(__ballot(it[j] >= c3));
+                above += __popcll(__ballot((it[j] >> 16) > (t >> 16)));
+                const bool bnd = (it[j] >> 16) == (t >> 16);
+                const u64 m = __ballot(bnd);
+                // lane q takes the q-th boundary key: hand it over through LDS-free readlane
+                // is not possible for a variable source, so stage through the scratch list
+                if (bnd) {
+                    const int slot = nb + (int)lanes_below(m);
+                    if (slot < 64) scratch[slot] = it[j];
+                }
+                nb += __popcll(m);
             }
-            t = n3 >= keep ? c3 : n2 >= keep ? c2 : n1 >= keep ? c1 : t;
+            one_per_lane = nb <= 64;
+            const int need = keep - above;
+            if (one_per_lane) {
+                bk = lane < nb ? scratch[lane] : 0u;
+#pragma unroll 1
+                for (int bit = 15; bit >= 0; --bit) {
+                    const u32 c1 = t | (1u << bit);
+                    t = __popcll(__ballot(bk >= c1)) >= need ? c1 : t;
+                }
+            } else {
+#pragma unroll 1
+                for (int bit = 15; bit >= 0; --bit) {
+                    const u32 c1 = t | (1u << bit);
+                    int n1 = 0;
+#pragma unroll
+                    for (int j = 0; j < ITEMS; ++j) n1 += __popcll(__ballot(it[j] >= c1));
+                    t = n1 >= keep ? c1 : t;
+                }
+            }
         }
         int gt = 0;
 #pragma unroll
@@ -85,13 +134,14 @@ __device__ __forceinline__ int wave_select_t(const float *score, int n, int keep
     }
     return pos;
 }
+// scratch: 64 LDS words private to the calling wave
 template <typename F>
-__device__ __forceinline__ int wave_select(const float *score, int n, int keep_max, Cut *cut_out, F f) {
-    if (n <= 64) return wave_select_t<1>(score, n, keep_max, cut_out, f);
-    if (n <= 128) return wave_select_t<2>(score, n, keep_max, cut_out, f);
-    if (n <= 256) return wave_select_t<4>(score, n, keep_max, cut_out, f);
-    if (n <= 512) return wave_select_t<8>(score, n, keep_max, cut_out, f);
-    return wave_select_t<16>(score, n, keep_max, cut_out, f);
+__device__ __forceinline__ int wave_select(const float *score, int n, int keep_max, Cut *cut_out, u32 *scratch, F f) {
+    if (n <= 64) return wave_select_t<1>(score, n, keep_max, cut_out, scratch, f);
+    if (n <= 128) return wave_select_t<2>(score, n, keep_max, cut_out, scratch, f);
+    if (n <= 256) return wave_select_t<4>(score, n, keep_max, cut_out, scratch, f);
+    if (n <= 512) return wave_select_t<8>(score, n, keep_max, cut_out, scratch, f);
+    return wave_select_t<16>(score, n, keep_max, cut_out, scratch, f);
 }
 
 __device__ __forceinline__ int block_sum_256(int v, int *s_red) {
@@ -182,6 +232,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     __shared__ int s_nexp;
     __shared__ int s_red[4];
     __shared__ Cut s_cut;
+    __shared__ u32 s_scratch[64];
 
     STAMP(0);
     if (tid == 0) {
@@ -219,7 +270,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
         const int n = l == 1 ? k : k * k;
         if (w == 0) {
             int *exp_l = s_exp[l];
-            const int n_exp = wave_select(s_score + lo, n, k, nullptr, [&](int i, int pos) {
+            const int n_exp = wave_select(s_score + lo, n, k, nullptr, s_scratch, [&](int i, int pos) {
                 exp_l[pos] = lo + i;
                 s_slot[lo + i] = (int8_t)pos;
             });
@@ -247,7 +298,7 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     int keep;
     if (p_end <= 1024) {
         if (w == 0) {
-            const int kp = wave_select(s_score, p_end, TT - 1, nullptr,
+            const int kp = wave_select(s_score, p_end, TT - 1, nullptr, s_scratch,
                                        [&](int i, int pos) { s_node[i] = (int16_t)(pos + 1); });
             if (lane_id() == 0) s_nexp = kp;
         }
