@@ -37,6 +37,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef const __bf16 __attribute__((address_space(1))) *gbf16p;
 typedef const bf16x8 __attribute__((address_space(1))) *gbf16x8p;
 __device__ __forceinline__ bf16x8 gload8(gbf16p p) { return *(gbf16x8p)p; }
+typedef const char __attribute__((address_space(1))) *gbytep;
 
 // LDS transpose read of gfx950 (ds_read_b64_tr_b16).  Within each group of 16 lanes, lane p
 // supplies the address of 4 consecutive 16-bit values; with X the concatenation of the 16
@@ -55,6 +56,9 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const __bf16 *p) {
 #define ATT_WAVES 4
 #define ATT_MTILE (ATT_ROWS_PER_WAVE * ATT_WAVES)
 #define K_PITCH (128 + 8)   // bf16 elements per K row in LDS (272 B: conflict-free 16 B reads)
+// bf16 elements per row of a row-major V tile (288 B): the transposing read takes 4 rows x 32 B
+// per 16 lanes, and a pitch of 8 banks modulo 32 spreads those four rows over all 32 banks
+#define V_PITCH (128 + 32)
 #define VT_PITCH 40         // bf16 elements per V^T row in LDS (80 B)
 #define ATT_MAX_SPLITS 16
 
@@ -71,35 +75,73 @@ struct Partial {
     float2 *ml;  // [batch, splits, TT_cap, Hq]  (running max of scale*score, sum)
 };
 
+// 32-bit visibility window of one query over keys t0 .. t0+31, where off = t0 - L (uniform): the
+// prefix keys (negative positions) are visible, tree key j is visible iff bit j of the node's
+// ancestor set is set (bits at and past the node count are 0, which also hides the padding
+// keys past the end of the sequence).
+__device__ __forceinline__ u32 vis_window(int off, u64 mask0, u64 mask1) {
+    if (off <= -32) return ~0u;
+    if (off < 0) return ((u32)mask0 << (-off)) | ((1u << (-off)) - 1u);
+    if (off >= 128) return 0u;
+    const u64 lo = off < 64 ? mask0 : mask1, hi = off < 64 ? mask1 : 0ull;
+    const int sh = off & 63;
+    return (u32)((lo >> sh) | (sh ? hi << (64 - sh) : 0ull));
+}
+
+// ------------------------------------------------------------------- large-batch kernel -----
+// One workgroup = 128 query rows of one (sequence, kv head) (wave w: rows 32w .. 32w+31) times
+// one contiguous range of 64-key blocks.  The four waves share each K/V block through LDS, so a
+// block crosses the L2 -> LDS path once per 128 rows.  The blocks are loaded straight into LDS
+// (global_load_lds_dwordx4: a wave's 64 x 16 B land contiguously, lane after lane), double
+// buffered with one barrier per block: the loads of block i+1 are in flight while block i is
+// multiplied, and cost neither registers nor LDS-write instructions.
+//
+// Both tiles are row-major with unpadded 256-byte rows; bank conflicts are avoided by storing
+// the 16-byte chunk c of row r at chunk position c ^ f(r) (the permutation is applied on the
+// global side: lane p of a row fetches chunk p ^ f(r)):
+//   K: f(r) = r % 16.  The A-operand read of S^T = K Q^T has 16 lanes read the same chunk of 16
+//      consecutive rows, which now sit at 16 different chunk positions (all 64 banks).
+//   V: f(r) = 4 (r % 4) + (r / 4) % 4.  The transposing read takes 4 rows x 64 B per 32 lanes;
+//      the four rows now sit in four different 64-byte groups.
+// Long sequences are cut into ranges of `chunk` blocks (a sequence gets as many workgroups per
+// row tile as its own length needs, so ragged batches stay balanced); ranges leave (max, sum,
+// O) partials for attn_combine_kernel, a sequence that fits one range writes its output directly.
+#define TILE_KEYS 64
+#define TILE_BYTES (TILE_KEYS * 256)     // one K or V tile
+#define STAGE_BYTES (2 * TILE_BYTES)     // K tile + V tile of one stage
+#define TILE_LDS_BYTES (2 * STAGE_BYTES)
+typedef char __attribute__((address_space(3))) *ldsp;
+
 template <int D>
-__global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, Partial part) {
+__global__ __launch_bounds__(256, 2) void attn_tile_kernel(AttnArgs a, int chunk, int max_splits, Partial part) {
     static_assert(D == 128, "head dim");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     const int G = a.Hq / a.Hkv;
     // blockIdx.x = kv head: workgroups are dealt to the 8 XCDs round-robin by linear id, so all
-    // row tiles and splits of one kv head land on one XCD and share its L2 copy of that head's K/V
-    const int b = blockIdx.z / splits, sp = blockIdx.z % splits, h = blockIdx.x;
+    // row tiles and ranges of one kv head land on one XCD and share its L2 copy of that head's K/V
+    const int b = blockIdx.z / max_splits, sp = blockIdx.z % max_splits, h = blockIdx.x;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
     const int M = N * G;
     const int m0 = blockIdx.y * ATT_MTILE;
     if (m0 >= M) return;
     const int L = max(a.prefix_len[b], 0);
     const int Tk = L + N;
-    const int nb = (Tk + ATT_KB - 1) / ATT_KB;
-    const int per = (nb + splits - 1) / splits;
-    const int kb0 = sp * per, kb1 = min(nb, kb0 + per);
+    const int nb = (Tk + TILE_KEYS - 1) / TILE_KEYS;
+    const int nsplit = (nb + chunk - 1) / chunk;
+    if (sp >= nsplit) return;
+    const int kb0 = sp * chunk, kb1 = min(nb, kb0 + chunk);
 
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int half = lane >> 5, col = lane & 31;
-    const int mq = m0 + w * ATT_ROWS_PER_WAVE + col;  // this lane's query row
+    const bool active = m0 + 32 * w < M;  // waves past the last row only help with the loads
+    const int mq = m0 + 32 * w + col;
     const bool qvalid = mq < M;
     const int node = qvalid ? mq / G : 0;
     const int hq = h * G + (qvalid ? mq % G : 0);
 
-    __shared__ __attribute__((aligned(16))) __bf16 s_k[ATT_KB * K_PITCH];
-    __shared__ __attribute__((aligned(16))) __bf16 s_vt[D * VT_PITCH];
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
 
-    // ---- Q as the B operand of S^T = K Q^T: k-step s, lane half g -> d = 16 s + 8 g .. +8 --
     bf16x8 qreg[KSTEPS];
     {
         const __bf16 *qp = (const __bf16 *)a.q + (((int64_t)b * a.TT_cap + node) * a.Hq + hq) * D;
@@ -117,85 +159,151 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
     float m_run = -INFINITY, l_run = 0.f;
     const float c = a.scale * 1.4426950408889634f;
 
-    const __bf16 *kpre = (const __bf16 *)a.k_prefix[b], *vpre = (const __bf16 *)a.v_prefix[b];
-    const __bf16 *ktree = (const __bf16 *)a.k_tree + (int64_t)b * a.TT_cap * a.Hkv * D;
-    const __bf16 *vtree = (const __bf16 *)a.v_tree + (int64_t)b * a.TT_cap * a.Hkv * D;
+    const gbf16p kpre = (gbf16p)a.k_prefix[b] + (int64_t)h * a.kv_stride_head;
+    const gbf16p vpre = (gbf16p)a.v_prefix[b] + (int64_t)h * a.kv_stride_head;
+    const gbf16p ktree = (gbf16p)a.k_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
+    const gbf16p vtree = (gbf16p)a.v_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
+    const int64_t stok = a.kv_stride_tok, stree = (int64_t)a.Hkv * D;
+    // Loading role of a thread, the same for K and V: load i takes key 16 i + tid/16 of the block
+    // and lands at chunk position tid%16 of that row, so it fetches chunk (tid%16) ^ f(row); the
+    // 16 lanes of a row still cover its 256 bytes.  f(row) does not depend on i (16 | 16 i).
+    const int krow = tid >> 4, cpos = tid & 15;
+    const int kchunk = cpos ^ krow, vchunk = cpos ^ (((krow & 3) << 2) | (krow >> 2));
+    u32 koffp[4], voffp[4];  // inside the prefix: byte offsets from the block's first row
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        koffp[i] = (u32)((16 * i + krow) * stok + 8 * kchunk) * 2u;
+        voffp[i] = (u32)((16 * i + krow) * stok + 8 * vchunk) * 2u;
+    }
+    const bool small_stride = (int64_t)TILE_KEYS * stok * 2 < ((int64_t)1 << 31);
 
-    // staging role of this thread: key row tid/8 of the block, 16 d's starting at (tid%8)*16
-    const int skey = tid >> 3, sd0 = (tid & 7) * 16;
+    // Every load is unconditional.  Keys past the end are read from the last valid row; their
+    // scores are masked to -inf below, so their probabilities are exactly 0 and the duplicated V
+    // rows contribute nothing.  LDS destination of wave w, load i: rows 16 i + 4 w .. + 3.
+    auto fetch = [&](int kb, int stage) {
+        const ldsp kdst = (ldsp)s_dyn + stage * STAGE_BYTES + 4 * w * 256;
+        const ldsp vdst = kdst + TILE_BYTES;
+        if (small_stride && kb * TILE_KEYS + TILE_KEYS <= L) {  // block inside the prefix (uniform test)
+            const gbytep kbase = (gbytep)(kpre + (int64_t)kb * TILE_KEYS * stok);
+            const gbytep vbase = (gbytep)(vpre + (int64_t)kb * TILE_KEYS * stok);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                __builtin_amdgcn_global_load_lds(kbase + koffp[i], kdst + i * 16 * 256, 16, 0, 0);
+                __builtin_amdgcn_global_load_lds(vbase + voffp[i], vdst + i * 16 * 256, 16, 0, 0);
+            }
+        } else {                                                 // block touching the tree keys or the end
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = min(kb * TILE_KEYS + 16 * i + krow, Tk - 1);
+                const int64_t o = t < L ? (int64_t)t * stok : (int64_t)(t - L) * stree;
+                __builtin_amdgcn_global_load_lds((gbytep)((t < L ? kpre : ktree) + o + 8 * kchunk), kdst + i * 16 * 256,
+                                                 16, 0, 0);
+                __builtin_amdgcn_global_load_lds((gbytep)((t < L ? vpre : vtree) + o + 8 * vchunk), vdst + i * 16 * 256,
+                                                 16, 0, 0);
+            }
+        }
+    };
 
+    // Operand read offsets (bytes inside a tile).
+    // K, A operand of S^T: lane (col, half), k-step s reads chunk 2s + half of row 32 j + col.
+    u32 koff[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) koff[s] = (u32)(col * 256 + (((2 * s + half) ^ (col & 15)) << 4));
+    // V, A operand of O^T = V^T P^T through the transposing read.  Lane (column d = 32 db + col,
+    // half) needs, for e = 0..7, V[key 16 st + 8 (e/4) + 4 half + e%4][d]: two reads of 4 keys.  In
+    // a 16-lane group lane p16 = 4 r0 + q points at key r0 of the quadruple, columns 4q .. 4q+3 of
+    // the group's 16 columns: chunk 4 db + 2 a + q/2 (a = second 16-lane group of the half), byte
+    // 8 (q%2) inside it.  Row 16 st + 8 hi + 4 half + r0 has f = 4 r0 + 2 hi + half.
+    const int p16 = lane & 15, r0 = p16 >> 2, q4 = p16 & 3, grp = (lane >> 4) & 1;
+    u32 voff[DBLK][2];
+#pragma unroll
+    for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+        for (int hi = 0; hi < 2; ++hi)
+            voff[db][hi] = (u32)((8 * hi + 4 * half + r0) * 256 +
+                                 (((4 * db + 2 * grp + (q4 >> 1)) ^ (4 * r0 + 2 * hi + half)) << 4) + 8 * (q4 & 1));
+
+    ASTAMP(0);
+    fetch(kb0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of the block is in LDS
+    __syncthreads();
     for (int kb = kb0; kb < kb1; ++kb) {
-        // ---- stage K (row-major) and V (transposed) of this key block ---------------------
-        {
-            const int t = kb * ATT_KB + skey;
-            // keys past the end re-read the last valid row: masked to probability 0 below
-            const int tc = min(t, Tk - 1);
-            const int64_t off = tc < L ? (int64_t)tc * a.kv_stride_tok + (int64_t)h * a.kv_stride_head + sd0
-                                       : ((int64_t)(tc - L) * a.Hkv + h) * D + sd0;
-            const __bf16 *kp = (tc < L ? kpre : ktree) + off, *vp = (tc < L ? vpre : vtree) + off;
-            const bf16x8 k0 = *(const bf16x8 *)kp, k1 = *(const bf16x8 *)(kp + 8);
-            const bf16x8 v0 = *(const bf16x8 *)vp, v1 = *(const bf16x8 *)(vp + 8);
-            *(bf16x8 *)(s_k + skey * K_PITCH + sd0) = k0;
-            *(bf16x8 *)(s_k + skey * K_PITCH + sd0 + 8) = k1;
-            const int pos = vt_pos(skey);
+        const int cur = (kb - kb0) & 1;
+        ASTAMP(1 + (kb - kb0) * 6);
+        if (kb + 1 < kb1) fetch(kb + 1, cur ^ 1);  // the other stage was last read before the previous barrier
+        ASTAMP(2 + (kb - kb0) * 6);
+        if (active) {
+            const unsigned char *kt = s_dyn + cur * STAGE_BYTES, *vt = kt + TILE_BYTES;
+            // ---- S^T: 64 keys x 32 queries as two 32x32 blocks -----------------------------------
+            f32x16 sacc[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                s_vt[(sd0 + e) * VT_PITCH + pos] = v0[e];
-                s_vt[(sd0 + 8 + e) * VT_PITCH + pos] = v1[e];
+            for (int j = 0; j < 2; ++j) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[j][i] = 0.f;
+#pragma unroll
+                for (int s = 0; s < KSTEPS; ++s) {
+                    const bf16x8 ka = *(const bf16x8 *)(kt + j * 32 * 256 + koff[s]);
+                    sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc[j], 0, 0, 0);
+                }
             }
-        }
-        __syncthreads();
-
-        // ---- S^T block: 32 keys x 32 queries ---------------------------------------------------
-        f32x16 sacc;
+            ASTAMP(3 + (kb - kb0) * 6);
+            const int tbase = kb * TILE_KEYS;
+            if (tbase + TILE_KEYS > L) {  // only blocks that contain tree keys (or the end) need the mask
 #pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+                for (int j = 0; j < 2; ++j) {
+                    const u32 vis = vis_window(tbase + 32 * j - L, mask0, mask1) >> (4 * half);
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s) {
-            const bf16x8 ka = *(const bf16x8 *)(s_k + col * K_PITCH + 16 * s + 8 * half);
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc, 0, 0, 0);
-        }
-        // ---- mask, online softmax (this lane: one query, 16 of the 32 keys) ---------------
-        const int tbase = kb * ATT_KB;
-        const bool has_tree = tbase + ATT_KB > L;
-        float mloc = -INFINITY;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int t = tbase + 8 * (i >> 2) + 4 * half + (i & 3);
-            bool vis = true;
-            if (has_tree) {
-                const int j = t - L;
-                if (j >= 0) vis = j < N && (((j < 64 ? mask0 : mask1) >> (j & 63)) & 1ull);
+                    for (int i = 0; i < 16; ++i)
+                        sacc[j][i] = ((vis >> (8 * (i >> 2) + (i & 3))) & 1u) ? sacc[j][i] : -INFINITY;
+                }
             }
-            sacc[i] = vis ? sacc[i] : -INFINITY;
-            mloc = fmaxf(mloc, sacc[i]);
-        }
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-        const float m_new = fmaxf(m_run, mloc);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c);  // m_run = -inf -> 0
-        float psum = 0.f;
-        bf16x8 pb[2];
+            // ---- online softmax over the 64 keys (this lane: one query, 32 of the keys) ----------
+            float mloc = sacc[0][0];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float p = __builtin_amdgcn_exp2f((sacc[i] - m_use) * c);
-            psum += p;
-            pb[i >> 3][i & 7] = (__bf16)p;
-        }
-        l_run = l_run * alpha + psum;
-        m_run = m_new;
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int db = 0; db < DBLK; ++db)
+                for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, sacc[j][i]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            const float m_new = fmaxf(m_run, mloc);
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c);  // m_run = -inf -> 0
+            const float nmc = -m_use * c;
+            float psum = 0.f;
+            bf16x8 pb[2][2];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
-        // ---- O^T += V^T P^T ------------------------------------------------------------------------
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int db = 0; db < DBLK; ++db)
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sacc[j][i], c, nmc));
+                    psum += p;
+                    pb[j][i >> 3][i & 7] = (__bf16)p;
+                }
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
+            if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some query of this wave
 #pragma unroll
-            for (int st = 0; st < 2; ++st) {
-                const bf16x8 va = *(const bf16x8 *)(s_vt + (32 * db + col) * VT_PITCH + st * 16 + half * 8);
-                oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[db], 0, 0, 0);
+                for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
             }
+            ASTAMP(4 + (kb - kb0) * 6);
+            // ---- O^T += V^T P^T ------------------------------------------------------------------
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+                    for (int st = 0; st < 2; ++st) {
+                        const unsigned char *vb = vt + (32 * j + 16 * st) * 256;
+                        const bf16x4 lo = lds_read_tr4((const __bf16 *)(vb + voff[db][0]));
+                        const bf16x4 hi = lds_read_tr4((const __bf16 *)(vb + voff[db][1]));
+                        const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j][st], oacc[db], 0, 0, 0);
+                    }
+        }
+        ASTAMP(5 + (kb - kb0) * 6);
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of the next block has landed
+        ASTAMP(6 + (kb - kb0) * 6);
         __syncthreads();
     }
 
@@ -203,28 +311,27 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (!qvalid) return;
     const int64_t row = ((int64_t)b * a.TT_cap + node) * a.Hq + hq;
-    if (splits == 1) {
+    if (nsplit == 1) {
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
         __bf16 *op = (__bf16 *)a.out + row * D;
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
+            for (int q = 0; q < 4; ++q) {
                 bf16x4 o4;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][q4 * 4 + e] * inv);
-                *(bf16x4 *)(op + 32 * db + 8 * q4 + 4 * half) = o4;
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[db][q * 4 + e] * inv);
+                *(bf16x4 *)(op + 32 * db + 8 * q + 4 * half) = o4;
             }
     } else {
-        const int64_t prow = (((int64_t)b * splits + sp) * a.TT_cap + node) * a.Hq + hq;
+        const int64_t prow = (((int64_t)b * max_splits + sp) * a.TT_cap + node) * a.Hq + hq;
         float *op = part.o + prow * D;
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
-            for (int q4 = 0; q4 < 4; ++q4) {
-                float4 o4 = make_float4(oacc[db][q4 * 4], oacc[db][q4 * 4 + 1], oacc[db][q4 * 4 + 2],
-                                        oacc[db][q4 * 4 + 3]);
-                *(float4 *)(op + 32 * db + 8 * q4 + 4 * half) = o4;
+            for (int q = 0; q < 4; ++q) {
+                float4 o4 = make_float4(oacc[db][q * 4], oacc[db][q * 4 + 1], oacc[db][q * 4 + 2], oacc[db][q * 4 + 3]);
+                *(float4 *)(op + 32 * db + 8 * q + 4 * half) = o4;
             }
         if (half == 0) part.ml[prow] = make_float2(m_run, l_tot);
     }
@@ -237,9 +344,8 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(AttnArgs a, int splits, 
 // layout and V into transposed operand layout, next block prefetched into registers), so the
 // main loop has no barrier at all.  The partial results meet in LDS once at the end; nothing
 // goes through global scratch.  Two waves per SIMD hide each other's instruction latency.
-#define KT_ELEMS (ATT_KB * K_PITCH)    // per-wave K tile and V tile: 32 rows of 272 B each
-#define WT_ELEMS (2 * KT_ELEMS)        // both tiles of a wave: 17 KB
-typedef const char __attribute__((address_space(1))) *gbytep;
+#define KT_ELEMS (ATT_KB * K_PITCH)              // per-wave K tile: 32 rows of 272 B
+#define WT_ELEMS (KT_ELEMS + ATT_KB * V_PITCH)   // both tiles of a wave (V: 32 rows of 288 B): 17.5 KB
 
 // With KS > 1 the key blocks are additionally dealt over KS workgroups per (sequence, kv head,
 // row block); each leaves its partial (max, sum, O) in global scratch for a small merge kernel.
@@ -347,9 +453,9 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
         // frees its registers for the next prefetch, issued before any arithmetic on this block.
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int r = ((i >> 2) * 16 + 4 * kq + (i & 3)) * K_PITCH + 8 * dc;
-            *(bf16x8 *)(kt + r) = kn[i];
-            *(bf16x8 *)(vt + r) = vn[i];
+            const int r = (i >> 2) * 16 + 4 * kq + (i & 3);
+            *(bf16x8 *)(kt + r * K_PITCH + 8 * dc) = kn[i];
+            *(bf16x8 *)(vt + r * V_PITCH + 8 * dc) = vn[i];
         }
         if (kb + kstep < nb) fetch(kb + kstep);
         ASTAMP(2 + it_no * 5);
@@ -412,13 +518,13 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
         // 16-lane group lane p = 4j+q points at key j of the quadruple, columns d0 + 4q..4q+3.
         {
             const int p16 = lane & 15;
-            const __bf16 *vbase = vt + (4 * half + (p16 >> 2)) * K_PITCH + 16 * ((lane >> 4) & 1) + 4 * (p16 & 3);
+            const __bf16 *vbase = vt + (4 * half + (p16 >> 2)) * V_PITCH + 16 * ((lane >> 4) & 1) + 4 * (p16 & 3);
 #pragma unroll
             for (int db = 0; db < DBLK; ++db)
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
-                    const bf16x4 lo = lds_read_tr4(vbase + (16 * st) * K_PITCH + 32 * db);
-                    const bf16x4 hi = lds_read_tr4(vbase + (16 * st + 8) * K_PITCH + 32 * db);
+                    const bf16x4 lo = lds_read_tr4(vbase + (16 * st) * V_PITCH + 32 * db);
+                    const bf16x4 hi = lds_read_tr4(vbase + (16 * st + 8) * V_PITCH + 32 * db);
                     const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[db], 0, 0, 0);
                 }
@@ -576,24 +682,28 @@ __global__ __launch_bounds__(256) void attn_wave_merge_kernel(AttnArgs a, int KS
     }
 }
 
-// Merge the per-split partials: one thread per (row, 4 output columns).
+// Merge the per-range partials of the large-batch kernel: one thread per (row, 4 output
+// columns).  A sequence that fitted one range was written directly and is skipped here.
 template <int D>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, int splits, Partial part) {
+__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, int chunk, int max_splits, Partial part) {
     const int b = blockIdx.y;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
+    const int nb = (max(a.prefix_len[b], 0) + N + TILE_KEYS - 1) / TILE_KEYS;
+    const int nsplit = (nb + chunk - 1) / chunk;
+    if (nsplit <= 1) return;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int c4 = (int)(idx % (D / 4));
     const int64_t r = idx / (D / 4);  // row inside the sequence: node * Hq + head
     if (r >= (int64_t)N * a.Hq) return;
     const float c = a.scale * 1.4426950408889634f;
     float M = -INFINITY;
-    for (int sp = 0; sp < splits; ++sp)
-        M = fmaxf(M, part.ml[((int64_t)b * splits + sp) * a.TT_cap * a.Hq + r].x);
+    for (int sp = 0; sp < nsplit; ++sp)
+        M = fmaxf(M, part.ml[((int64_t)b * max_splits + sp) * a.TT_cap * a.Hq + r].x);
     const float Mu = M == -INFINITY ? 0.f : M;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
     float l = 0.f;
-    for (int sp = 0; sp < splits; ++sp) {
-        const int64_t prow = ((int64_t)b * splits + sp) * a.TT_cap * a.Hq + r;
+    for (int sp = 0; sp < nsplit; ++sp) {
+        const int64_t prow = ((int64_t)b * max_splits + sp) * a.TT_cap * a.Hq + r;
         const float2 ml = part.ml[prow];
         if (ml.y <= 0.f) continue;
         const float wgt = __builtin_amdgcn_exp2f((ml.x - Mu) * c);
@@ -756,25 +866,38 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
         *err = hipGetLastError();
         return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
     }
-    const int nb_max = (a.max_prefix_len + a.TT_cap + ATT_KB - 1) / ATT_KB;
-    int splits = 1;
-    if (base_wgs < 512) splits = (512 + base_wgs - 1) / base_wgs;
-    if (splits > ATT_MAX_SPLITS) splits = ATT_MAX_SPLITS;
-    if (splits > nb_max / 2) splits = nb_max / 2 > 0 ? nb_max / 2 : 1;
+    // Ranges of `chunk` 64-key blocks: towards ~1024 workgroups (two per compute unit, two rounds),
+    // at least 8 blocks per range, as many ranges as the scratch holds.
+    const int nb_max = (a.max_prefix_len + a.TT_cap + TILE_KEYS - 1) / TILE_KEYS;
+    int want = base_wgs >= 1024 ? 1 : (1024 + base_wgs - 1) / base_wgs;
+    if (want > 8) want = 8;
+    if (want > nb_max / 8) want = nb_max / 8;
     const size_t per = split_bytes(a.batch, a.TT_cap, a.Hq, a.D);
-    if (splits > 1 && (size_t)splits * per > a.ws_bytes) splits = (int)(a.ws_bytes / per);
-    if (splits < 1) splits = 1;
+    if (want > 1 && (!a.ws || (size_t)want * per > a.ws_bytes)) want = a.ws ? (int)(a.ws_bytes / per) : 1;
+    if (want < 1) want = 1;
+#ifdef DT_TIMESTAMPS
+    if (const char *e = getenv("DT_WANT")) want = atoi(e);
+#endif
+    const int chunk = (nb_max + want - 1) / want;
+    const int max_splits = (nb_max + chunk - 1) / chunk;
     Partial part;
     part.o = (float *)a.ws;
-    part.ml = (float2 *)((char *)a.ws + (size_t)a.batch * splits * a.TT_cap * a.Hq * a.D * 4);
-    dim3 grid(a.Hkv, mtiles, a.batch * splits);
-    launch_kernel(KID_ATTN, st, attn_mfma_kernel<128>, grid, dim3(256), 0, a, splits, part);
+    part.ml = (float2 *)((char *)a.ws + (size_t)a.batch * max_splits * a.TT_cap * a.Hq * a.D * 4);
+    static bool tile_lds_opt_in = false;
+    if (!tile_lds_opt_in) {
+        *err = hipFuncSetAttribute((const void *)attn_tile_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   TILE_LDS_BYTES);
+        if (*err != hipSuccess) return DT_ERR_HIP;
+        tile_lds_opt_in = true;
+    }
+    dim3 grid(a.Hkv, mtiles, a.batch * max_splits);
+    launch_kernel(KID_ATTN, st, attn_tile_kernel<128>, grid, dim3(256), TILE_LDS_BYTES, a, chunk, max_splits, part);
     *err = hipGetLastError();
     if (*err != hipSuccess) return DT_ERR_HIP;
-    if (splits > 1) {
+    if (max_splits > 1) {
         const int64_t items = (int64_t)a.TT_cap * a.Hq * (a.D / 4);
         dim3 cgrid((unsigned)((items + 255) / 256), a.batch);
-        launch_kernel(KID_ATTN_COMBINE, st, attn_combine_kernel<128>, cgrid, dim3(256), 0, a, splits, part);
+        launch_kernel(KID_ATTN_COMBINE, st, attn_combine_kernel<128>, cgrid, dim3(256), 0, a, chunk, max_splits, part);
         *err = hipGetLastError();
         if (*err != hipSuccess) return DT_ERR_HIP;
     }
