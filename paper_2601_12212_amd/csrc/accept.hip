@@ -29,10 +29,21 @@ __device__ __forceinline__ float load_logit(const void *base, int dtype, int64_t
     return dtype == DT_BF16 ? bf16_bits_to_float(((const uint16_t *)base)[idx]) : ((const float *)base)[idx];
 }
 
-__device__ __forceinline__ double wave_sum_f64(double v) {
+// Eight consecutive entries id .. id+7 of a row (entries at or past `hi` read as -inf).  The eight
+// loads are independent, so they are in flight together; aligned bf16 octets take one 16-byte load.
+__device__ __forceinline__ void load_logits8(const void *row, int dtype, int id, int hi, bool vec_ok, float out[8]) {
+    if (dtype == DT_BF16 && vec_ok && id + 8 <= hi) {
+        const uint4 raw = *(const uint4 *)((const uint16_t *)row + id);
+        const u32 wds[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
+        for (int e = 0; e < 4; ++e) {
+            out[2 * e] = __uint_as_float(wds[e] << 16);
+            out[2 * e + 1] = __uint_as_float(wds[e] & 0xFFFF0000u);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e] = id + e < hi ? load_logit(row, dtype, id + e) : -INFINITY;
+    }
 }
 
 __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
@@ -166,65 +177,89 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     if (!stochastic) {
         if (tid == 0) s_bonus = s_amax[best];
     } else {
-        // inverse CDF of softmax(row/T) at the bonus uniform, in double.  Wave w owns the
-        // contiguous span [w*span, (w+1)*span) of the row, walked in steps of 64 lanes x 8.
+        // Inverse CDF of softmax(row/T) of node `best` at the bonus uniform.  The row kernel left
+        // (max, sum exp((x - max)/T)) of every chunk of the row: their masses relative to the row
+        // maximum, accumulated in double, locate the chunk that holds the crossing; only that chunk
+        // is read again (thread t owns `epl` consecutive ids), element masses in fp32, running sums
+        // in double.  The comparison is "cumulative mass > u * total", the un-normalised form of
+        // the cdf > u test; it differs from an all-double evaluation by ~1e-6 in probability.
         const void *row = (const char *)a.target + (o + best) * a.row_stride * (a.dtype == DT_BF16 ? 2 : 4);
-        const double T = (double)a.temperature;
-        const double mT = (double)s_rowmax[best] / T;
-        const int span = ((a.V + 2047) / 2048) * 512;
-        const int lo = w * span, hi = min(a.V, lo + span);
-        double tot = 0.0;
-        for (int base = lo + lane * 8; base < hi; base += 512)
-            for (int e = 0; e < 8; ++e)
-                if (base + e < hi) tot += exp((double)load_logit(row, a.dtype, base + e) / T - mT);
-        tot = wave_sum_f64(tot);
-        if (lane == 0) s_wtot[w] = tot;
+        const float Mrow = s_rowmax[best];
+        const float cexp = 1.4426950408889634f * inv_t;
+        const int64_t g = o + best;
+        // chunk c in lane c (S <= 64), every wave for itself
+        double mass = 0.0;
+        if (lane < S) {
+            const float2 p = a.part_ms[g * S + lane];
+            if (p.y > 0.f) mass = (double)p.y * (double)__builtin_amdgcn_exp2f((p.x - Mrow) * cexp);
+        }
+        double cum = mass;  // inclusive scan over the chunks
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const double t = __shfl_up(cum, off, 64);
+            if (lane >= off) cum += t;
+        }
+        const double Z = __shfl(cum, 63, 64);
+        const double target_mass = (double)philox_uniform(a.seed, a.step, (u32)b, 0xFFFFFFFFu) * Z;
+        // first chunk whose cumulative mass passes the target; if rounding leaves none, the last with mass
+        const u64 passed = __ballot(cum > target_mass), massy = __ballot(mass > 0.0);
+        const int cstar = passed ? (int)__builtin_ctzll(passed) : massy ? 63 - (int)__builtin_clzll(massy) : 0;
+        const double before = __shfl(cum - mass, cstar, 64);
+        const int epl = a.chunk_elems / 256;
+        const int lo = cstar * a.chunk_elems, hi = min(a.V, lo + a.chunk_elems);
+        const int id0 = lo + tid * epl;
+        const bool vec_ok = ((uintptr_t)row & 15) == 0;  // id0 is a multiple of 8
+        double mine = 0.0;
+        for (int e0 = 0; e0 < epl; e0 += 8) {
+            float x[8];
+            load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) mine += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
+        }
+        double incl = mine;  // inclusive scan over the lanes of the wave
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const double t = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += t;
+        }
+        if (lane == 63) s_wtot[w] = incl;
         if (tid == 0) s_bonus = -1;
         __syncthreads();
-        const double Z = s_wtot[0] + s_wtot[1] + s_wtot[2] + s_wtot[3];
-        const double target_mass = (double)philox_uniform(a.seed, a.step, (u32)b, 0xFFFFFFFFu) * Z;
-        double before = 0.0;
-        for (int q = 0; q < w; ++q) before += s_wtot[q];
-        // the wave whose span contains the crossing walks it again
-        if (before <= target_mass && (target_mass < before + s_wtot[w])) {
-            double run = before;
-            for (int sb = lo; sb < hi; sb += 512) {
-                const int base = sb + lane * 8;
-                double p[8], mine = 0.0;
-                for (int e = 0; e < 8; ++e) {
-                    p[e] = base + e < hi ? exp((double)load_logit(row, a.dtype, base + e) / T - mT) : 0.0;
-                    mine += p[e];
-                }
-                double incl = mine;  // inclusive scan over lanes
-#pragma unroll
-                for (int off = 1; off < 64; off <<= 1) {
-                    double t = __shfl_up(incl, off, 64);
-                    if (lane >= off) incl += t;
-                }
-                const double step_total = __shfl(incl, 63, 64);
-                if (run + step_total > target_mass) {
-                    const u64 m = __ballot(run + incl > target_mass);
-                    const int first = __ffsll((long long)m) - 1;
-                    if (lane == first) {
-                        double c = run + incl - mine;
-                        int id = base + 7;
-                        for (int e = 0; e < 8; ++e) {
-                            c += p[e];
-                            if (c > target_mass) { id = base + e; break; }
-                        }
-                        s_bonus = min(id, a.V - 1);
-                    }
-                    break;
-                }
-                run += step_total;
+        double run = before;
+        for (int q = 0; q < w; ++q) run += s_wtot[q];
+        const bool cross = run + incl > target_mass;
+        const u64 m = __ballot(cross);
+        // the first crossing thread of the first crossing wave
+        bool earlier = false;
+        {
+            double r2 = before;
+            for (int q = 0; q < w; ++q) {
+                r2 += s_wtot[q];
+                earlier = earlier || r2 > target_mass;
             }
+        }
+        if (!earlier && m && lane == (int)__builtin_ctzll(m)) {
+            double cm = run + incl - mine;
+            int id = min(id0 + epl, hi) - 1;
+            bool done = false;
+            for (int e0 = 0; e0 < epl && !done; e0 += 8) {
+                float x[8];
+                load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    cm += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
+                    if (!done && cm > target_mass) { id = id0 + e0 + e; done = true; }
+                }
+            }
+            s_bonus = id;
         }
         __syncthreads();
         if (tid == 0 && s_bonus < 0) {
-            // the uniform lies above the rounded total mass: last token that carries mass
-            int id = a.V - 1;
-            while (id > 0 && !(exp((double)load_logit(row, a.dtype, id) / T - mT) > 0.0)) --id;
-            s_bonus = id;
+            // the chunk's re-computed mass falls just short of the crossing (rounding), or the row
+            // carries no mass at all: last token of the chunk that carries mass, else token 0
+            int id = hi - 1;
+            while (id > lo && !(__builtin_amdgcn_exp2f((load_logit(row, a.dtype, id) - Mrow) * cexp) > 0.f)) --id;
+            s_bonus = Z > 0.0 ? id : 0;
         }
     }
     __syncthreads();

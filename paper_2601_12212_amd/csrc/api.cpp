@@ -230,7 +230,7 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     aa.depth = depth; aa.logp = logp; aa.anc_mask = (const unsigned long long *)anc_mask; aa.TT_cap = TT_cap;
     aa.seed = philox_seed; aa.step = philox_step; aa.accept_len = accept_len; aa.best_node = best_node;
     aa.path_nodes = path_nodes; aa.out_tokens = out_tokens; aa.node_argmax = node_argmax;
-    aa.part_keys = rs.keys; aa.part_ms = rs.ms; aa.S = S;
+    aa.part_keys = rs.keys; aa.part_ms = rs.ms; aa.S = S; aa.chunk_elems = 256 * 8 * nl;
     e = dt::accept_launch(aa, st);
     if (e != hipSuccess) return hip_fail(e);
     return DT_OK;

@@ -70,10 +70,6 @@ __device__ __forceinline__ int vt_pos(int kk) {
     return step * 16 + half * 8 + idx;
 }
 
-struct Partial {
-    float *o;    // [batch, splits, TT_cap, Hq, D]
-    float2 *ml;  // [batch, splits, TT_cap, Hq]  (running max of scale*score, sum)
-};
 
 // 32-bit visibility window of one query over keys t0 .. t0+31, where off = t0 - L (uniform): the
 // prefix keys (negative positions) are visible, tree key j is visible iff bit j of the node's
@@ -103,33 +99,32 @@ __device__ __forceinline__ u32 vis_window(int off, u64 mask0, u64 mask1) {
 //      consecutive rows, which now sit at 16 different chunk positions (all 64 banks).
 //   V: f(r) = 4 (r % 4) + (r / 4) % 4.  The transposing read takes 4 rows x 64 B per 32 lanes;
 //      the four rows now sit in four different 64-byte groups.
-// Long sequences are cut into ranges of `chunk` blocks (a sequence gets as many workgroups per
-// row tile as its own length needs, so ragged batches stay balanced); ranges leave (max, sum,
-// O) partials for attn_combine_kernel, a sequence that fits one range writes its output directly.
 #define TILE_KEYS 64
 #define TILE_BYTES (TILE_KEYS * 256)     // one K or V tile
 #define STAGE_BYTES (2 * TILE_BYTES)     // K tile + V tile of one stage
 #define TILE_LDS_BYTES (2 * STAGE_BYTES)
 typedef char __attribute__((address_space(3))) *ldsp;
 
+// Where a (sequence, row tile, key range) result goes: the output rows directly when the range is
+// the whole sequence, else 128 partial rows (unnormalised O, running max, sum) for the combine.
+struct TileDest {
+    bool direct;
+    float *o;     // [128, D]
+    float2 *ml;   // [128]
+};
+
+// Rows m0 .. m0+127 of (sequence b, kv head h) against key blocks kb0 .. kb1-1 of that sequence.
+// Called by all 256 threads of the workgroup; ends behind a barrier, so calls can follow each other.
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_tile_kernel(AttnArgs a, int chunk, int max_splits, Partial part) {
+__device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s_dyn, int h, int b, int m0, int kb0,
+                                             int kb1, TileDest dst) {
     static_assert(D == 128, "head dim");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     const int G = a.Hq / a.Hkv;
-    // blockIdx.x = kv head: workgroups are dealt to the 8 XCDs round-robin by linear id, so all
-    // row tiles and ranges of one kv head land on one XCD and share its L2 copy of that head's K/V
-    const int b = blockIdx.z / max_splits, sp = blockIdx.z % max_splits, h = blockIdx.x;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
     const int M = N * G;
-    const int m0 = blockIdx.y * ATT_MTILE;
-    if (m0 >= M) return;
     const int L = max(a.prefix_len[b], 0);
     const int Tk = L + N;
-    const int nb = (Tk + TILE_KEYS - 1) / TILE_KEYS;
-    const int nsplit = (nb + chunk - 1) / chunk;
-    if (sp >= nsplit) return;
-    const int kb0 = sp * chunk, kb1 = min(nb, kb0 + chunk);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -139,8 +134,6 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(AttnArgs a, int chunk
     const bool qvalid = mq < M;
     const int node = qvalid ? mq / G : 0;
     const int hq = h * G + (qvalid ? mq % G : 0);
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
 
     bf16x8 qreg[KSTEPS];
     {
@@ -310,10 +303,9 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(AttnArgs a, int chunk
     // ---- epilogue -------------------------------------------------------------------------------
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (!qvalid) return;
-    const int64_t row = ((int64_t)b * a.TT_cap + node) * a.Hq + hq;
-    if (nsplit == 1) {
+    if (dst.direct) {
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-        __bf16 *op = (__bf16 *)a.out + row * D;
+        __bf16 *op = (__bf16 *)a.out + (((int64_t)b * a.TT_cap + node) * a.Hq + hq) * D;
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -324,8 +316,8 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(AttnArgs a, int chunk
                 *(bf16x4 *)(op + 32 * db + 8 * q + 4 * half) = o4;
             }
     } else {
-        const int64_t prow = (((int64_t)b * max_splits + sp) * a.TT_cap + node) * a.Hq + hq;
-        float *op = part.o + prow * D;
+        const int rit = 32 * w + col;  // row inside the tile
+        float *op = dst.o + (int64_t)rit * D;
 #pragma unroll
         for (int db = 0; db < DBLK; ++db)
 #pragma unroll
@@ -333,8 +325,195 @@ __global__ __launch_bounds__(256, 2) void attn_tile_kernel(AttnArgs a, int chunk
                 float4 o4 = make_float4(oacc[db][q * 4], oacc[db][q * 4 + 1], oacc[db][q * 4 + 2], oacc[db][q * 4 + 3]);
                 *(float4 *)(op + 32 * db + 8 * q + 4 * half) = o4;
             }
-        if (half == 0) part.ml[prow] = make_float2(m_run, l_tot);
+        if (half == 0) dst.ml[rit] = make_float2(m_run, l_tot);
     }
+}
+
+// One workgroup per (kv head, row tile, sequence), the whole key range: enough of them to fill
+// the chip several times over.  blockIdx.x = kv head: workgroups are dealt to the 8 XCDs
+// round-robin by linear id, so all row tiles of one kv head land on one XCD and share its L2
+// copy of that head's K/V.
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_tile_kernel(AttnArgs a) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
+    const int b = blockIdx.z, h = blockIdx.x, m0 = blockIdx.y * ATT_MTILE;
+    const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
+    if (m0 >= N * (a.Hq / a.Hkv)) return;
+    const int nb = (max(a.prefix_len[b], 0) + N + TILE_KEYS - 1) / TILE_KEYS;
+    TileDest dst;
+    dst.direct = true;
+    dst.o = nullptr;
+    dst.ml = nullptr;
+    tile_segment<D>(a, s_dyn, h, b, m0, 0, nb, dst);
+}
+
+// ---- balanced schedule for batches that cannot fill the chip with whole (sequence, tile) items --
+// Each kv head gets P workgroup slots (two per compute unit over all heads).  Sequences are
+// grouped into classes by their number of row tiles m; the key blocks of a class's sequences,
+// concatenated in batch order, form its C_m "columns" of cost m each.  Class m is given g_m
+// "gangs" of m slots (one per row tile, neighbours in launch order, so the tiles of a sequence walk
+// its K/V together and share it in L2); gang j takes columns [j T_m, (j+1) T_m) of the class, with
+// T_m = ceil(C_m / g_m), and the g_m are the ones that minimise max_m T_m under sum m g_m <= P.
+// A slot therefore works through a few (sequence, tile, key range) segments of near-equal total
+// length.  A sequence cut by a range boundary leaves partials: per slot one "head" (its first
+// segment, when that sequence began in an earlier gang) and one "tail" (a sequence that began
+// here and runs on).  Every wave derives the plan by itself from n_nodes / prefix_len with wave
+// operations (sequence b in lane b: batch <= 64; class m in lane m), so no barrier is involved.
+struct GangPartial {
+    float *o;     // [Hkv, P, 2, 128, D]
+    float2 *ml;   // [Hkv, P, 2, 128]
+    int *seq;     // [batch, 8]: where sequence b's partials are (written by the attention kernel)
+};
+enum { GS_FIRST = 0, GS_LAST, GS_BASE, GS_CLS, GS_T, GS_START, GS_WORDS = 8 };
+
+__device__ __forceinline__ int wave_excl_scan_i32(int v, int lane) {
+    int x = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int t = __shfl_up(x, o, 64);
+        if (lane >= o) x += t;
+    }
+    return x - v;
+}
+
+struct GangPlan {
+    int mt, nb;        // lane b: row tiles and key blocks of sequence b (0 past the batch)
+    int C, g, T;       // lane m: columns, gangs and columns per gang of class m
+};
+
+__device__ __forceinline__ GangPlan gang_plan(const AttnArgs &a, int P, int mt_max, int lane) {
+    GangPlan p;
+    p.mt = 0;
+    p.nb = 0;
+    if (lane < a.batch) {
+        const int N = min(max(a.n_nodes[lane], 1), a.TT_cap);
+        p.mt = (N * (a.Hq / a.Hkv) + ATT_MTILE - 1) / ATT_MTILE;
+        p.nb = (max(a.prefix_len[lane], 0) + N + TILE_KEYS - 1) / TILE_KEYS;
+    }
+    p.C = 0;
+    for (int m = 1; m <= mt_max; ++m) {
+        const int c = wave_sum_i32(p.mt == m ? p.nb : 0);
+        if (lane == m) p.C = c;
+    }
+    const int W = wave_sum_i32(lane * p.C);
+    // smallest T with sum_m m ceil(C_m / T) <= P: lane i probes T0 + i.  T = max C_m always fits
+    // (the host checks P >= 1 + 2 + .. + mt_max), so the loop ends.
+    int T0 = max(1, (W + P - 1) / P), T;
+    for (;;) {
+        const int t = T0 + lane;
+        int slots = 0;
+        for (int m = 1; m <= mt_max; ++m) slots += m * ((__builtin_amdgcn_readlane(p.C, m) + t - 1) / t);
+        const u64 ok = __ballot(slots <= P);
+        if (ok) {
+            T = T0 + (int)__builtin_ctzll(ok);
+            break;
+        }
+        T0 += 64;
+    }
+    p.g = (p.C + T - 1) / T;
+    p.T = p.g > 0 ? (p.C + p.g - 1) / p.g : 0;
+    return p;
+}
+
+template <int D>
+__global__ __launch_bounds__(256, 2) void attn_gang_kernel(AttnArgs a, int P, int mt_max, GangPartial part) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
+    const int h = blockIdx.x, y = blockIdx.y, lane = threadIdx.x & 63;
+    const GangPlan p = gang_plan(a, P, mt_max, lane);
+    // class, gang and row tile of slot y
+    int base = 0, cls = 0;
+    for (int m = 1; m <= mt_max; ++m) {
+        const int span = m * __builtin_amdgcn_readlane(p.g, m);
+        if (cls == 0) {
+            if (y < base + span) cls = m;
+            else base += span;
+        }
+    }
+    // Slots y, y+P, .. of head 0 also leave sequence y's entry of the table the combine kernel reads:
+    // first and last gang of the sequence, first slot, tile count and gang width of its class, and
+    // its first column.
+    if (h == 0 && threadIdx.x < 64) {
+        for (int b = y; b < a.batch; b += P) {
+            const int mb = __builtin_amdgcn_readlane(p.mt, b), nbb = __builtin_amdgcn_readlane(p.nb, b);
+            int bs = 0;
+            for (int m = 1; m < mb; ++m) bs += m * __builtin_amdgcn_readlane(p.g, m);
+            const int Tb = __builtin_amdgcn_readlane(p.T, mb);
+            const int csb = __builtin_amdgcn_readlane(wave_excl_scan_i32(p.mt == mb ? p.nb : 0, lane), b);
+            if (lane == 0) {
+                int *e = part.seq + b * GS_WORDS;
+                e[GS_FIRST] = csb / Tb;
+                e[GS_LAST] = (csb + nbb - 1) / Tb;
+                e[GS_BASE] = bs;
+                e[GS_CLS] = mb;
+                e[GS_T] = Tb;
+                e[GS_START] = csb;
+            }
+        }
+    }
+    if (cls == 0) return;  // spare slot
+    const int j = (y - base) / cls, tile = (y - base) % cls;
+    const int Tc = __builtin_amdgcn_readlane(p.T, cls), Cc = __builtin_amdgcn_readlane(p.C, cls);
+    const int lo = j * Tc, hi = min(Cc, lo + Tc);
+    // first column of every sequence of this class
+    const int val = p.mt == cls ? p.nb : 0;
+    const int cs = wave_excl_scan_i32(val, lane);
+    u64 segs = __ballot(val > 0 && cs < hi && cs + val > lo);
+    const int64_t slot = (int64_t)h * P + y;
+    while (segs) {
+        const int b = (int)__builtin_ctzll(segs);
+        segs &= segs - 1;
+        const int csb = __builtin_amdgcn_readlane(cs, b), nbb = __builtin_amdgcn_readlane(val, b);
+        const int kb0 = max(lo, csb) - csb, kb1 = min(hi, csb + nbb) - csb;
+        TileDest dst;
+        dst.direct = kb0 == 0 && kb1 == nbb;
+        const int which = csb < lo ? 0 : 1;
+        dst.o = part.o + (slot * 2 + which) * ATT_MTILE * D;
+        dst.ml = part.ml + (slot * 2 + which) * ATT_MTILE;
+        tile_segment<D>(a, s_dyn, h, b, tile * ATT_MTILE, kb0, kb1, dst);
+    }
+}
+
+// Merge of the partials of the balanced schedule: one thread per (row, 4 output columns) of
+// sequence blockIdx.y.  A sequence that stayed inside one gang was written directly.
+template <int D>
+__global__ __launch_bounds__(256) void attn_gang_combine_kernel(AttnArgs a, int P, GangPartial part) {
+    const int b = blockIdx.y;
+    const int *e = part.seq + b * GS_WORDS;
+    const int jf = e[GS_FIRST], jl = e[GS_LAST];
+    if (jf == jl) return;
+    const int base = e[GS_BASE], cls = e[GS_CLS], Tc = e[GS_T], csb = e[GS_START];
+    const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
+    const int G = a.Hq / a.Hkv;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int c4 = (int)(idx % (D / 4));
+    const int64_t r = idx / (D / 4);  // row inside the sequence: node * Hq + head
+    if (r >= (int64_t)N * a.Hq) return;
+    const int node = (int)(r / a.Hq), hq = (int)(r % a.Hq), h = hq / G;
+    const int mq = node * G + hq % G, tile = mq / ATT_MTILE, rit = mq % ATT_MTILE;
+    const float c = a.scale * 1.4426950408889634f;
+    auto prow = [&](int j) {
+        const int64_t slot = (int64_t)h * P + base + j * cls + tile;
+        return (slot * 2 + (csb < j * Tc ? 0 : 1)) * ATT_MTILE + rit;
+    };
+    float M = -INFINITY;
+    for (int j = jf; j <= jl; ++j) M = fmaxf(M, part.ml[prow(j)].x);
+    const float Mu = M == -INFINITY ? 0.f : M;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    float l = 0.f;
+    for (int j = jf; j <= jl; ++j) {
+        const int64_t pr = prow(j);
+        const float2 ml = part.ml[pr];
+        if (ml.y <= 0.f) continue;
+        const float wgt = __builtin_amdgcn_exp2f((ml.x - Mu) * c);
+        const float4 o = *(const float4 *)(part.o + pr * D + c4 * 4);
+        acc.x += o.x * wgt; acc.y += o.y * wgt; acc.z += o.z * wgt; acc.w += o.w * wgt;
+        l += ml.y * wgt;
+    }
+    const float inv = l > 0.f ? 1.0f / l : 0.f;
+    bf16x4 o4;
+    o4[0] = (__bf16)(acc.x * inv); o4[1] = (__bf16)(acc.y * inv);
+    o4[2] = (__bf16)(acc.z * inv); o4[3] = (__bf16)(acc.w * inv);
+    *(bf16x4 *)((__bf16 *)a.out + ((int64_t)b * a.TT_cap * a.Hq + r) * D + c4 * 4) = o4;
 }
 
 // ------------------------------------------------------------------- small-batch kernel -----
@@ -682,42 +861,6 @@ __global__ __launch_bounds__(256) void attn_wave_merge_kernel(AttnArgs a, int KS
     }
 }
 
-// Merge the per-range partials of the large-batch kernel: one thread per (row, 4 output
-// columns).  A sequence that fitted one range was written directly and is skipped here.
-template <int D>
-__global__ __launch_bounds__(256) void attn_combine_kernel(AttnArgs a, int chunk, int max_splits, Partial part) {
-    const int b = blockIdx.y;
-    const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
-    const int nb = (max(a.prefix_len[b], 0) + N + TILE_KEYS - 1) / TILE_KEYS;
-    const int nsplit = (nb + chunk - 1) / chunk;
-    if (nsplit <= 1) return;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int c4 = (int)(idx % (D / 4));
-    const int64_t r = idx / (D / 4);  // row inside the sequence: node * Hq + head
-    if (r >= (int64_t)N * a.Hq) return;
-    const float c = a.scale * 1.4426950408889634f;
-    float M = -INFINITY;
-    for (int sp = 0; sp < nsplit; ++sp)
-        M = fmaxf(M, part.ml[((int64_t)b * max_splits + sp) * a.TT_cap * a.Hq + r].x);
-    const float Mu = M == -INFINITY ? 0.f : M;
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float l = 0.f;
-    for (int sp = 0; sp < nsplit; ++sp) {
-        const int64_t prow = ((int64_t)b * max_splits + sp) * a.TT_cap * a.Hq + r;
-        const float2 ml = part.ml[prow];
-        if (ml.y <= 0.f) continue;
-        const float wgt = __builtin_amdgcn_exp2f((ml.x - Mu) * c);
-        const float4 o = *(const float4 *)(part.o + prow * D + c4 * 4);
-        acc.x += o.x * wgt; acc.y += o.y * wgt; acc.z += o.z * wgt; acc.w += o.w * wgt;
-        l += ml.y * wgt;
-    }
-    const float inv = l > 0.f ? 1.0f / l : 0.f;
-    bf16x4 o4;
-    o4[0] = (__bf16)(acc.x * inv); o4[1] = (__bf16)(acc.y * inv);
-    o4[2] = (__bf16)(acc.z * inv); o4[3] = (__bf16)(acc.w * inv);
-    *(bf16x4 *)((__bf16 *)a.out + ((int64_t)b * a.TT_cap * a.Hq + r) * D + c4 * 4) = o4;
-}
-
 // ------------------------------------------------------------------------------ fp32 path --
 // One wave per (node, head).  Keys are taken 64 at a time: lane j scores key j, the wave
 // agrees on the running maximum, then lane c accumulates output columns c, c+64.
@@ -794,14 +937,38 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------- launchers --
-static size_t split_bytes(int batch, int TT_cap, int Hq, int D) {
-    return (size_t)batch * TT_cap * Hq * ((size_t)D * 4 + 8);
+// compute units of the current device (256 when there is no device to ask, e.g. when only the
+// workspace size is wanted on a machine without one)
+static int compute_units() {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+            n_cu = n;
+        else
+            n_cu = 256;
+        (void)hipGetLastError();
+    }
+    return n_cu;
+}
+
+// scratch of the balanced large-batch schedule: (kv heads x slots per head) <= 2 x compute units
+// slots, two partials of 128 rows each, and the table of up to 64 sequences
+static size_t gang_bytes(int D) {
+    return (size_t)2 * compute_units() * 2 * ATT_MTILE * ((size_t)D * 4 + 8) + 64 * GS_WORDS * 4;
+}
+
+// scratch of the small-batch key splits: per (sequence, kv head, 32-row block) and split
+static size_t wave_split_bytes(int batch, int TT_cap, int Hq) {
+    return (size_t)batch * ((TT_cap * Hq + 31) / 32 + Hq) * (4 * 4 * 64 * 16 + 32 * 8);
 }
 
 size_t attn_workspace_bytes(int batch, int TT_cap, int Hq, int D) {
-    // room for 8 splits, capped at 256 MiB (the launcher uses fewer splits if scratch is short)
-    size_t want = split_bytes(batch, TT_cap, Hq, D) * 8;
+    if (D != 128) return 0;
+    const size_t w8 = wave_split_bytes(batch, TT_cap, Hq) * 8, g = gang_bytes(D);
     const size_t cap = (size_t)256 << 20;
+    const size_t want = w8 > g ? w8 : g;
     return want < cap ? want : cap;
 }
 
@@ -830,7 +997,7 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
         const int nb_max = (a.max_prefix_len + a.TT_cap + ATT_KB - 1) / ATT_KB;
         int KS = 256 / units;
         if (KS > 8) KS = 8;
-        if (KS > nb_max / 20) KS = nb_max / 20;
+        if (KS > nb_max / 11) KS = nb_max / 11;
         const size_t per_split = (size_t)units * (4 * 4 * 64 * 16 + 32 * 8);
         if (KS > 1 && (!a.ws || (size_t)KS * per_split > a.ws_bytes)) KS = a.ws ? (int)(a.ws_bytes / per_split) : 1;
         if (KS < 1) KS = 1;
@@ -866,42 +1033,38 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
         *err = hipGetLastError();
         return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
     }
-    // Ranges of `chunk` 64-key blocks: towards ~1024 workgroups (two per compute unit, two rounds),
-    // at least 8 blocks per range, as many ranges as the scratch holds.
-    const int nb_max = (a.max_prefix_len + a.TT_cap + TILE_KEYS - 1) / TILE_KEYS;
-    int want = base_wgs >= 1024 ? 1 : (1024 + base_wgs - 1) / base_wgs;
-    if (want > 8) want = 8;
-    if (want > nb_max / 8) want = nb_max / 8;
-    const size_t per = split_bytes(a.batch, a.TT_cap, a.Hq, a.D);
-    if (want > 1 && (!a.ws || (size_t)want * per > a.ws_bytes)) want = a.ws ? (int)(a.ws_bytes / per) : 1;
-    if (want < 1) want = 1;
-#ifdef DT_TIMESTAMPS
-    if (const char *e = getenv("DT_WANT")) want = atoi(e);
-#endif
-    const int chunk = (nb_max + want - 1) / want;
-    const int max_splits = (nb_max + chunk - 1) / chunk;
-    Partial part;
-    part.o = (float *)a.ws;
-    part.ml = (float2 *)((char *)a.ws + (size_t)a.batch * max_splits * a.TT_cap * a.Hq * a.D * 4);
     static bool tile_lds_opt_in = false;
     if (!tile_lds_opt_in) {
         *err = hipFuncSetAttribute((const void *)attn_tile_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    TILE_LDS_BYTES);
+        if (*err == hipSuccess)
+            *err = hipFuncSetAttribute((const void *)attn_gang_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       TILE_LDS_BYTES);
         if (*err != hipSuccess) return DT_ERR_HIP;
         tile_lds_opt_in = true;
     }
-    dim3 grid(a.Hkv, mtiles, a.batch * max_splits);
-    launch_kernel(KID_ATTN, st, attn_tile_kernel<128>, grid, dim3(256), TILE_LDS_BYTES, a, chunk, max_splits, part);
+    // Fewer whole (sequence, kv head, row tile) items than four rounds of two workgroups per compute
+    // unit: the balanced schedule (needs one lane per sequence and a slot for every tile count).
+    const int P = 2 * compute_units() / a.Hkv;
+    const bool gang = base_wgs < 8 * compute_units() && a.batch <= 64 && mtiles <= 63 && P >= mtiles * (mtiles + 1) / 2 &&
+                      a.ws && (size_t)a.Hkv * P * 2 * ATT_MTILE * ((size_t)a.D * 4 + 8) + 64 * GS_WORDS * 4 <= a.ws_bytes;
+    if (!gang) {
+        launch_kernel(KID_ATTN, st, attn_tile_kernel<128>, dim3(a.Hkv, mtiles, a.batch), dim3(256), TILE_LDS_BYTES, a);
+        *err = hipGetLastError();
+        return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
+    }
+    GangPartial part;
+    part.o = (float *)a.ws;
+    part.ml = (float2 *)((char *)a.ws + (size_t)a.Hkv * P * 2 * ATT_MTILE * a.D * 4);
+    part.seq = (int *)((char *)a.ws + (size_t)a.Hkv * P * 2 * ATT_MTILE * ((size_t)a.D * 4 + 8));
+    launch_kernel(KID_ATTN, st, attn_gang_kernel<128>, dim3(a.Hkv, P), dim3(256), TILE_LDS_BYTES, a, P, mtiles, part);
     *err = hipGetLastError();
     if (*err != hipSuccess) return DT_ERR_HIP;
-    if (max_splits > 1) {
-        const int64_t items = (int64_t)a.TT_cap * a.Hq * (a.D / 4);
-        dim3 cgrid((unsigned)((items + 255) / 256), a.batch);
-        launch_kernel(KID_ATTN_COMBINE, st, attn_combine_kernel<128>, cgrid, dim3(256), 0, a, chunk, max_splits, part);
-        *err = hipGetLastError();
-        if (*err != hipSuccess) return DT_ERR_HIP;
-    }
-    return DT_OK;
+    const int64_t items = (int64_t)a.TT_cap * a.Hq * (a.D / 4);
+    launch_kernel(KID_ATTN_COMBINE, st, attn_gang_combine_kernel<128>, dim3((unsigned)((items + 255) / 256), a.batch),
+                  dim3(256), 0, a, P, part);
+    *err = hipGetLastError();
+    return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
 }
 
 }  // namespace dt

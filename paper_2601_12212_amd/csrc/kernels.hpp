@@ -105,7 +105,8 @@ struct AcceptArgs {
     int32_t *accept_len, *best_node, *path_nodes, *out_tokens, *node_argmax;
     const unsigned long long *part_keys;  // [batch*TT_cap, S]
     const float2 *part_ms;
-    int S;
+    int S;            // chunks per row
+    int chunk_elems;  // vocabulary entries per chunk
 };
 hipError_t accept_launch(const AcceptArgs &a, hipStream_t st);
 

@@ -180,6 +180,28 @@ def test_attention_key_splits_and_long_prefix():
     check_case(oracle_case(0, cfg=small_cfg([(128, 6, 6), (7, 2, 3)], [4097, 640], Hq=4, Hkv=4)), sample_attention=300)
 
 
+def test_attention_balanced_schedule_on_ragged_batches():
+    # enough (sequence, kv head, row tile) items for the large-batch kernel, too few to fill the chip:
+    # every kv head's workgroup slots share out the key blocks of all sequences evenly, so one slot
+    # walks through several short sequences (written directly) and parts of long ones (partials that
+    # a second kernel merges).  Row-tile counts 1..3, empty and one-block prefixes, TT = 1.
+    rng = np.random.default_rng(77)
+    params, plen = [], []
+    for i in range(24):
+        TT = int(rng.choice([1, 7, 32, 33, 64, 65, 96]))
+        params.append((TT, int(rng.integers(1, 6)), int(rng.integers(1, 7))))
+        plen.append(int(rng.choice([0, 1, 63, 64, 65, 300, 900, 2500])))
+    plen[3], plen[4] = 6000, 0
+    check_case(oracle_case(0, cfg=small_cfg(params, plen, V=2053, Hq=32, Hkv=8)), sample_attention=48)
+    # one class only, sequences much longer than a slot's share: every sequence is cut several times
+    check_case(oracle_case(0, cfg=small_cfg([(96, 4, 6)] * 3, [5000, 4100, 37], V=2053, Hq=64, Hkv=8)),
+               sample_attention=64)
+    # more whole items than slots would need splitting: plain one-workgroup-per-item launch (batch > 64)
+    params = [(int(rng.choice([5, 40])), 3, 3) for _ in range(70)]
+    check_case(oracle_case(0, cfg=small_cfg(params, [int(rng.integers(0, 200)) for _ in range(70)], V=1031,
+                                            Hq=8, Hkv=2)), sample_attention=16)
+
+
 def test_stochastic_small_and_many_steps():
     cfg = small_cfg([(40, 5, 4), (64, 6, 6)], [100, 31], V=3001, mode=dt_synth.STOCHASTIC)
     case = oracle_case(0, cfg=cfg)
