@@ -31,6 +31,11 @@
  * accumulated in double; log-probabilities and scores are rounded to float exactly
  * once per operation: lp = fl32(x - lse), score = fl32(score[parent] + lp).
  *
+ *   - Appendix, "System Profiling and Overhead Analysis": after verification the
+ *     "input update" brings the KV cache to the state the next step starts from --
+ *     the accepted tokens stay, the rejected ones are discarded, and positions
+ *     continue from the new length (ref_commit_rows).
+ *
  * Pins: every function here is pinned by tests (library sorts, closed forms,
  * brute-force enumeration of token strings and of root-to-leaf paths, float64
  * dense-mask attention, Philox known-answer vectors).  Not pinned: that the
@@ -545,5 +550,43 @@ int ref_accept(int mode, float temperature, const void *target, int dtype, int V
     if (node_argmax) for (int i = 0; i < N; ++i) node_argmax[i] = amax[i];
     if (accepted) for (int i = 0; i < N; ++i) accepted[i] = acc[i];
     if (min_margin) *min_margin = (float)margin;
+    return REF_OK;
+}
+
+/* ------------------------------------------------------------- input update (KV commit) */
+
+/*
+ * "Input update" after verification (Appendix, System Profiling and Overhead Analysis): the
+ * KV cache keeps the accepted tokens and discards the rejected ones.  The keys/values of
+ * all tree tokens were produced by the verification pass into a buffer of their own, so
+ * "discard" means: only the rows on the accepted path are appended to the cache.
+ *
+ * One sequence, one cache tensor (K or V of one layer):
+ *   cache       element (t, g, c) at t*stride_tok + g*stride_head + c; rows 0..L-1 hold the prefix
+ *   cap         rows the cache can hold
+ *   tree        [N, Hkv, D] rows of the tree tokens (row 0 = root)
+ *   path_nodes  path_nodes[0..len] = root .. deepest accepted node (output of ref_accept)
+ * Cache row L+s receives tree row path_nodes[s], s = 0..len, for as long as the row fits
+ * (L+s < cap).  *new_len = min(cap, L+len+1): the position of the next root (the bonus token),
+ * whose own keys/values are computed by the next step.
+ */
+int ref_commit_rows(void *cache, int dtype, int64_t cap, int64_t L, int64_t stride_tok, int64_t stride_head,
+                    int Hkv, int D, const void *tree, int N, const int32_t *path_nodes, int len,
+                    int64_t *new_len)
+{
+    if (!cache || !tree || !path_nodes || !new_len) return REF_ERR_ARG;
+    if (L < 0 || L > cap || len < 0 || len > REF_D_MAX || N < 1 || Hkv < 1 || D < 1) return REF_ERR_ARG;
+    size_t esz = dtype == REF_F32 ? 4 : 2;
+    for (int s = 0; s <= len; ++s) {
+        int node = path_nodes[s];
+        if (node < 0 || node >= N) return REF_ERR_ARG;
+        int64_t t = L + s;
+        if (t >= cap) break;
+        for (int g = 0; g < Hkv; ++g)
+            for (int c = 0; c < D; ++c)
+                memcpy((char *)cache + (size_t)(t * stride_tok + g * stride_head + c) * esz,
+                       (const char *)tree + ((size_t)((int64_t)node * Hkv + g) * D + c) * esz, esz);
+    }
+    *new_len = L + len + 1 < cap ? L + len + 1 : cap;
     return REF_OK;
 }

@@ -148,6 +148,27 @@ def accept(mode, target, tokens, parents, depth, logp=None, temperature=1.0, d_c
                 node_argmax=amax, accepted=accepted.astype(bool), min_margin=margin.value)
 
 
+def commit_rows(cache, L, tree, path_nodes, accept_len, head_major=False):
+    """Input update for one sequence and one cache tensor, in place.
+
+    cache: [cap, Hkv, D] (or [Hkv, cap, D] with head_major), rows 0..L-1 valid; tree: [N, Hkv, D].
+    Returns the new length."""
+    assert cache.flags.c_contiguous and cache.dtype == tree.dtype
+    tree = np.ascontiguousarray(tree)
+    N, Hkv, D = tree.shape
+    if head_major:
+        assert cache.shape[0] == Hkv and cache.shape[2] == D
+        cap, st, sh = cache.shape[1], D, cache.shape[1] * D
+    else:
+        assert cache.shape[1] == Hkv and cache.shape[2] == D
+        cap, st, sh = cache.shape[0], Hkv * D, D
+    path = np.ascontiguousarray(path_nodes, np.int32)
+    new_len = C.c_int64(0)
+    _check(lib().ref_commit_rows(_p(cache), _dt(cache), C.c_int64(cap), C.c_int64(L), C.c_int64(st), C.c_int64(sh),
+                                 Hkv, D, _p(tree), N, _p(path), int(accept_len), C.byref(new_len)), "ref_commit_rows")
+    return new_len.value
+
+
 def philox4x32(ctr, key):
     c = (C.c_uint32 * 4)(*ctr)
     k = (C.c_uint32 * 2)(*key)
