@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=400)
+    ap.add_argument("--commit-layers", type=int, default=32,
+                    help="layers of the separately timed input update (0: skip it)")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run a plain device copy of this many MB (a kernel of known traffic, for scaling "
                          "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE readings)")
@@ -206,6 +208,39 @@ def main():
     roofline["traffic_source"] = os.path.relpath(pmc_path, ROOT) if traffic else None
     roofline_all = [roof(n) for n in sorted(with_bytes, key=lambda n: -kbytes[n])]
 
+    # ---- the input update that follows the step (not part of the timed step): all layers' K/V rows of
+    #      the accepted paths appended to the caches; timed on its own with dispatch-attached events ----
+    commit = None
+    if args.commit_layers > 0:
+        st0 = steps[0]
+        nl, cap_rows, L0 = args.commit_layers, 16, 4     # the kernel's work does not depend on the prefix length
+        i64 = dict(dtype=torch.int64, device="cuda")
+        tk = [torch.randn((cfg.B, st0.TT_cap, cfg.Hkv, cfg.D), device="cuda").to(tdtype) for _ in range(2 * nl)]
+        ck = [[torch.zeros((cap_rows, cfg.Hkv, cfg.D), dtype=tdtype, device="cuda") for _ in range(cfg.B)]
+              for _ in range(2 * nl)]
+        ptr_rows = lambda rows: torch.tensor([[t.data_ptr() for t in row] for row in rows], **i64)
+        ktp = torch.tensor([t.data_ptr() for t in tk[:nl]], **i64)
+        vtp = torch.tensor([t.data_ptr() for t in tk[nl:]], **i64)
+        kpp, vpp = ptr_rows(ck[:nl]), ptr_rows(ck[nl:])
+        plen = torch.full((cfg.B,), L0, dtype=torch.int32, device="cuda")
+        pcap = torch.full((cfg.B,), cap_rows, dtype=torch.int32, device="cuda")
+        new_len = torch.empty_like(plen)
+        nroot = torch.empty_like(plen)
+        n_c = 200
+        dt.dt_profile_enable(n_c + 8)
+        for _ in range(n_c):
+            dt.dt_commit(tk[0], cfg.Hkv, cfg.D, ktp, vtp, kpp, vpp, plen, pcap, cfg.Hkv * cfg.D, cfg.D, st0.n_nodes,
+                         st0.path_nodes, st0.accept_len, st0.out_tokens, st0.TT_cap, new_len, nroot)
+        torch.cuda.synchronize()
+        name, ms, n = dt.dt_profile_read(8)
+        dt.dt_profile_enable(0)
+        rows = int((st0.accept_len.cpu() + 1).sum())
+        cbytes = 2 * 2 * nl * rows * cfg.Hkv * cfg.D * e            # read + write, K and V, every layer
+        commit = {"avg_us": round(ms * 1e3 / max(n, 1), 3), "layers": nl, "rows": rows, "bytes": cbytes,
+                  "gbps": round(cbytes / (ms * 1e-3 / max(n, 1)) / 1e9, 1), "in_timed_step": False}
+        log("  kernel %-20s avg %8.2f us  (%d layers, %d accepted-path rows, %.2f MB moved; outside the timed step)"
+            % ("commit", commit["avg_us"], nl, rows, cbytes / 1e6))
+
     if args.calibration_copy_mb > 0:
         n = args.calibration_copy_mb * 1000 * 1000 // 4
         src = torch.arange(n, dtype=torch.float32, device="cuda")
@@ -257,6 +292,7 @@ def main():
         "pct_hbm_peak_step": round(100.0 * bytes_step / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
         "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                     for k, v in kern.items()},
+        "input_update": commit,
         "roofline": roofline,
         "roofline_all_streams": roofline_all,
         "cpu_baseline": cpu,

@@ -170,13 +170,39 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
               void *ws, size_t ws_bytes);
 
 /*
+ * Input update after verification (paper Appendix, "System Profiling and Overhead Analysis": the
+ * input update brings the KV cache to the state of the next step -- accepted tokens kept, rejected
+ * ones discarded, positions continued).  For every sequence b, layer l and both of K and V, the tree
+ * rows of the accepted path are appended to the prefix cache:
+ *     cache_l,b row prefix_len[b] + s  <-  tree_l row (b, path_nodes[b, s]),   s = 0 .. accept_len[b]
+ * for as long as the row fits (row < prefix_cap[b]); nothing else in the cache is touched.
+ *   k_tree, v_tree    device arrays [n_layers] of device pointers to [batch, TT_cap, Hkv, D] (type t)
+ *   k_prefix,v_prefix device arrays [n_layers * batch] (layer-major) of device pointers to the caches;
+ *                     element (token t, kv head g, c) at t*kv_stride_tok + g*kv_stride_head + c
+ *   prefix_len,prefix_cap  [batch] valid rows and capacity in rows of every cache of sequence b
+ *   n_nodes, path_nodes [batch, DT_D_MAX+1], accept_len, out_tokens [batch, DT_D_MAX+1]: as written
+ *                     by dt_build_tree / dt_accept
+ *   new_prefix_len [batch]  out: min(prefix_cap, prefix_len + accept_len + 1), the position of the next
+ *                     root; must not alias prefix_len (every workgroup reads the old length)
+ *   next_root_token [batch] out, may be NULL: the bonus token out_tokens[b, accept_len[b]]
+ * 16-byte copies are used when D*sizeof(t), both strides and all base pointers allow it.  No workspace.
+ * Errors: null pointers, new_prefix_len == prefix_len, non-positive sizes -> DT_ERR_INVALID_ARG;
+ * TT_cap outside 1..DT_TT_MAX or n_layers > 65535 -> DT_ERR_LIMIT.
+ */
+int dt_commit(void *stream, int batch, int n_layers, dt_dtype t, int Hkv, int D, const void *const *k_tree,
+              const void *const *v_tree, void *const *k_prefix, void *const *v_prefix, const int32_t *prefix_len,
+              const int32_t *prefix_cap, int64_t kv_stride_tok, int64_t kv_stride_head, const int32_t *n_nodes,
+              const int32_t *path_nodes, const int32_t *accept_len, const int32_t *out_tokens, int TT_cap,
+              int32_t *new_prefix_len, int32_t *next_root_token);
+
+/*
  * Optional per-kernel timing, for measurement only (off by default; not part of the step).
  * dt_profile_enable(n > 0) pre-creates n HIP event pairs and switches timing on: every kernel
  * launched by the calls above then carries an event pair on its dispatch that records the
  * kernel's own begin and end (not usable while the stream is being captured into a graph).
  * dt_profile_enable(0) switches it off.  dt_profile_read sums, for one kernel id
  * (0 draft row chunks, 1 row merge, 2 tree, 3 attention, 4 attention combine, 5 target row
- * chunks, 6 accept, 7 dt_topk_rows chunks), the elapsed milliseconds of the launches recorded
+ * chunks, 6 accept, 7 dt_topk_rows chunks, 8 commit), the elapsed milliseconds of the launches recorded
  * since the last enable, waiting for them to finish.  Not thread-safe.
  */
 int dt_profile_enable(int max_launches);

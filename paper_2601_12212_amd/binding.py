@@ -48,13 +48,14 @@ def load_library():
                                           vp, i32, vp, vp, sz]
         lib.dt_accept.argtypes = [vp, i32, i32, f32, vp, i32, i32, i64, vp, vp, vp, vp, vp, vp, i32, u64, u64,
                                   vp, vp, vp, vp, vp, vp, sz]
+        lib.dt_commit.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i32, vp, vp]
         lib.dt_profile_enable.argtypes = [i32]
         lib.dt_profile_enable.restype = i32
         lib.dt_profile_read.argtypes = [i32, C.POINTER(C.c_double), C.POINTER(i32)]
         lib.dt_profile_read.restype = i32
         lib.dt_profile_kernel_name.argtypes = [i32]
         lib.dt_profile_kernel_name.restype = C.c_char_p
-        for fn in ("dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept"):
+        for fn in ("dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept", "dt_commit"):
             getattr(lib, fn).restype = i32
         _lib = lib
     return _lib
@@ -129,6 +130,18 @@ def dt_accept(mode, temperature, target_logits, n_nodes, tokens, parents, depth,
         _ptr(n_nodes), _ptr(tokens), _ptr(parents), _ptr(depth), _ptr(logp), _ptr(anc_mask), TT_cap, philox_seed,
         philox_step, _ptr(accept_len), _ptr(best_node), _ptr(path_nodes), _ptr(out_tokens), _ptr(node_argmax),
         _ptr(ws), ws.numel() * ws.element_size()))
+
+
+def dt_commit(dtype_of, Hkv, D, k_tree_ptrs, v_tree_ptrs, k_prefix_ptrs, v_prefix_ptrs, prefix_len, prefix_cap,
+              kv_stride_tok, kv_stride_head, n_nodes, path_nodes, accept_len, out_tokens, TT_cap, new_prefix_len,
+              next_root_token):
+    """k_tree_ptrs / v_tree_ptrs: int64 device tensors [n_layers]; k_prefix_ptrs / v_prefix_ptrs: [n_layers, batch];
+    dtype_of: any tensor of the cache dtype."""
+    n_layers, batch = k_prefix_ptrs.shape
+    _check("dt_commit", load_library().dt_commit(
+        _stream(), batch, n_layers, _dtype(dtype_of), Hkv, D, _ptr(k_tree_ptrs), _ptr(v_tree_ptrs), _ptr(k_prefix_ptrs),
+        _ptr(v_prefix_ptrs), _ptr(prefix_len), _ptr(prefix_cap), kv_stride_tok, kv_stride_head, _ptr(n_nodes),
+        _ptr(path_nodes), _ptr(accept_len), _ptr(out_tokens), TT_cap, _ptr(new_prefix_len), _ptr(next_root_token)))
 
 
 def dt_profile_enable(max_launches):

@@ -236,4 +236,30 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     return DT_OK;
 }
 
+int dt_commit(void *stream, int batch, int n_layers, dt_dtype t, int Hkv, int D, const void *const *k_tree,
+              const void *const *v_tree, void *const *k_prefix, void *const *v_prefix, const int32_t *prefix_len,
+              const int32_t *prefix_cap, int64_t kv_stride_tok, int64_t kv_stride_head, const int32_t *n_nodes,
+              const int32_t *path_nodes, const int32_t *accept_len, const int32_t *out_tokens, int TT_cap,
+              int32_t *new_prefix_len, int32_t *next_root_token) {
+    if (batch < 0 || n_layers < 0 || bad_dtype(t)) return DT_ERR_INVALID_ARG;
+    if (batch == 0 || n_layers == 0) return DT_OK;
+    if (!k_tree || !v_tree || !k_prefix || !v_prefix || !prefix_len || !prefix_cap || !n_nodes || !path_nodes ||
+        !accept_len || !out_tokens || !new_prefix_len || new_prefix_len == prefix_len)
+        return DT_ERR_INVALID_ARG;
+    if (Hkv < 1 || D < 1 || kv_stride_tok < 1 || kv_stride_head < 1) return DT_ERR_INVALID_ARG;
+    if (TT_cap < 1 || TT_cap > DT_TT_MAX || n_layers > 65535) return DT_ERR_LIMIT;
+    dt::CommitArgs a = {};
+    a.batch = batch; a.n_layers = n_layers; a.dtype = t; a.Hkv = Hkv; a.D = D;
+    a.k_tree = k_tree; a.v_tree = v_tree; a.k_prefix = k_prefix; a.v_prefix = v_prefix;
+    a.prefix_len = prefix_len; a.prefix_cap = prefix_cap; a.kv_stride_tok = kv_stride_tok; a.kv_stride_head = kv_stride_head;
+    a.n_nodes = n_nodes; a.path_nodes = path_nodes; a.accept_len = accept_len; a.out_tokens = out_tokens; a.TT_cap = TT_cap;
+    const int esz = t == DT_BF16 ? 2 : 4;
+    a.vec16 = (D * esz) % 16 == 0 && (kv_stride_tok * esz) % 16 == 0 && (kv_stride_head * esz) % 16 == 0;
+    a.new_prefix_len = new_prefix_len; a.next_root_token = next_root_token;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
+    hipError_t e = dt::commit_launch(a, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
 }  // extern "C"

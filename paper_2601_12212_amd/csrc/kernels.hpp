@@ -13,7 +13,7 @@ namespace dt {
 // of pre-created HIP events attached to its dispatch (hipExtLaunchKernelGGL), which record the
 // kernel's own begin and end; dt_profile_read sums the elapsed times per kernel id.
 enum KernelId { KID_ROWS_DRAFT = 0, KID_ROWS_MERGE, KID_TREE, KID_ATTN, KID_ATTN_COMBINE, KID_ROWS_TARGET,
-                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COUNT };
+                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COMMIT, KID_COUNT };
 bool prof_next(int kid, hipEvent_t *start, hipEvent_t *stop);  // false when timing is off
 
 template <typename F, typename... Args>
@@ -109,5 +109,21 @@ struct AcceptArgs {
     int chunk_elems;  // vocabulary entries per chunk
 };
 hipError_t accept_launch(const AcceptArgs &a, hipStream_t st);
+
+// --------------------------------------------------------------- input update (commit.hip)
+struct CommitArgs {
+    int batch, n_layers, dtype, Hkv, D;
+    const void *const *k_tree;   // [n_layers] -> [batch, TT_cap, Hkv, D]
+    const void *const *v_tree;
+    void *const *k_prefix;       // [n_layers * batch], layer-major
+    void *const *v_prefix;
+    const int32_t *prefix_len, *prefix_cap;
+    int64_t kv_stride_tok, kv_stride_head;
+    const int32_t *n_nodes, *path_nodes, *accept_len, *out_tokens;
+    int TT_cap;
+    int vec16;                   // rows of D elements and both strides are multiples of 16 bytes
+    int32_t *new_prefix_len, *next_root_token;
+};
+hipError_t commit_launch(const CommitArgs &a, hipStream_t st);
 
 }  // namespace dt

@@ -91,3 +91,12 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_accept(*acc(mode=1, logp=None)) == -1
     assert lib.dt_accept(*acc(mode=1, T=0.0)) == -1
     assert lib.dt_accept(*acc(wsb=8)) == -3
+    # commit: null pointers, new length aliasing the old one, TT_cap over the limit, nothing to do
+    other = C.c_void_p(512)
+    com = lambda **kw: [None, kw.get("batch", 1), kw.get("layers", 2), 1, 8, 128, one, one, kw.get("kp", one), one, one,
+                        one, 1024, 128, one, one, one, one, kw.get("TT_cap", 60), kw.get("new", other), None]
+    assert lib.dt_commit(*com(kp=None)) == -1
+    assert lib.dt_commit(*com(new=one)) == -1
+    assert lib.dt_commit(*com(TT_cap=129)) == -2
+    assert lib.dt_commit(*com(batch=0)) == 0
+    assert lib.dt_commit(*com(layers=0)) == 0
