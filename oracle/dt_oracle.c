@@ -163,6 +163,7 @@ typedef struct {
     int level;       /* 1..d */
     int from_row;    /* draft row whose top-k produced it */
     int own_row;     /* draft row it was handed when expanded, else -1 */
+    int own_slot;    /* its slot in its level's expanded set, else -1 */
 } cand_t;
 
 typedef struct {
@@ -219,12 +220,21 @@ static int select_best(const cand_t *pool, int lo, int hi, int keep, unsigned ch
  *   node was handed, -1 if never expanded), anc_mask[node][W] with W = ceil(TT_cap/64)
  *   (bit j set iff j is the node itself or one of its ancestors), n_nodes,
  *   min_margin (see select_best; +inf if no such comparison occurred).
+ * Optional (all three NULL or all three given), what a draft model sitting between the levels
+ * is told after level l = 1..d-1 (Algorithm 2: the nodes chosen at a level are the draft
+ * model's next inputs), indexed [l*REF_K_MAX + slot]:
+ *   exp_count[l]     number of nodes of level l that are expanded (exp_count[0] = 0)
+ *   exp_tok          their tokens, in slot order (= ascending pool index)
+ *   exp_parent_slot  slot of the parent in level l-1's expanded set (-1: the root)
+ *   exp_mask[..][4]  draft-side tree mask over draft rows: bit r set iff draft row r belongs to
+ *                    the node itself or to one of its ancestors (row 0 = the root)
  */
 int ref_build_tree(const void *rows, int dtype, int V, int64_t row_stride, int n_rows_avail,
                    int TT, int d, int k, int32_t root_token, int TT_cap,
                    int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth,
                    float *score, float *logp, int32_t *src_row, uint64_t *anc_mask,
-                   float *min_margin)
+                   float *min_margin, int32_t *exp_count, int32_t *exp_tok, int32_t *exp_parent_slot,
+                   uint64_t *exp_mask)
 {
     if (!rows || !n_nodes || !tokens || !parents || !depth || !score || !logp || !src_row || !anc_mask)
         return REF_ERR_ARG;
@@ -244,7 +254,11 @@ int ref_build_tree(const void *rows, int dtype, int V, int64_t row_stride, int n
     float tv[REF_K_MAX];
     int32_t ti[REF_K_MAX];
     if (!pool || !kept || !node_of) { rc = REF_ERR_INTERNAL; goto done; }
-    for (int i = 0; i < P; ++i) { pool[i].own_row = -1; pool[i].parent_pool = -1; }
+    for (int i = 0; i < P; ++i) { pool[i].own_row = -1; pool[i].own_slot = -1; pool[i].parent_pool = -1; }
+    if (exp_count) {
+        if (!exp_tok || !exp_parent_slot || !exp_mask) { rc = REF_ERR_ARG; goto done; }
+        for (int l = 0; l < REF_D_MAX; ++l) exp_count[l] = 0;
+    }
 
     /* node 0: the root */
     tokens[0] = root_token; parents[0] = -1; depth[0] = 0; score[0] = 0.0f; logp[0] = 0.0f;
@@ -276,6 +290,17 @@ int ref_build_tree(const void *rows, int dtype, int V, int64_t row_stride, int n
                 if (!exp_flag[i]) continue;
                 int row = 1 + (l - 1) * k + slot;
                 pool[i].own_row = row;
+                pool[i].own_slot = slot;
+                if (exp_count) {
+                    int e = l * REF_K_MAX + slot;
+                    exp_tok[e] = pool[i].tok;
+                    exp_parent_slot[e] = pool[i].parent_pool < 0 ? -1 : pool[pool[i].parent_pool].own_slot;
+                    for (int w = 0; w < 4; ++w) exp_mask[(size_t)e * 4 + w] = 0;
+                    exp_mask[(size_t)e * 4] = 1ull; /* the root's row */
+                    for (int j = i; j >= 0; j = pool[j].parent_pool) /* the node and its ancestors */
+                        exp_mask[(size_t)e * 4 + pool[j].own_row / 64] |= 1ull << (pool[j].own_row % 64);
+                    exp_count[l] = slot + 1;
+                }
                 const char *rp = (const char *)rows + (int64_t)row * row_stride * esz;
                 int nvr = ref_row_reduce(rp, dtype, V, k, tv, ti, &lse);
                 if (nvr < 0) { free(exp_flag); rc = nvr; goto done; }

@@ -73,8 +73,11 @@ def topk_rows(logits, k):
     return val, idx, lse
 
 
-def build_tree(rows, TT, d, k, root_token=0, TT_cap=TT_MAX):
-    """A1-A4 for one sequence.  rows [>= 1+(d-1)k, V].  Returns a dict of node arrays."""
+def build_tree(rows, TT, d, k, root_token=0, TT_cap=TT_MAX, with_levels=False):
+    """A1-A4 for one sequence.  rows [>= 1+(d-1)k, V].  Returns a dict of node arrays.
+
+    with_levels: also "levels", a list indexed by level l = 1..d-1 of dicts (tokens, parent_slot, rows, mask)
+    describing the nodes expanded at that level -- what a draft model between the levels is handed."""
     rows = np.ascontiguousarray(rows)
     R, V = rows.shape
     W = (TT_cap + 63) // 64
@@ -87,12 +90,22 @@ def build_tree(rows, TT, d, k, root_token=0, TT_cap=TT_MAX):
     src_row = np.full(TT_cap, -1, np.int32)
     mask = np.zeros((TT_cap, W), np.uint64)
     margin = C.c_float(0)
+    ecnt = np.zeros(D_MAX, np.int32) if with_levels else None
+    etok = np.full((D_MAX, K_MAX), -1, np.int32) if with_levels else None
+    epar = np.full((D_MAX, K_MAX), -1, np.int32) if with_levels else None
+    emask = np.zeros((D_MAX, K_MAX, 4), np.uint64) if with_levels else None
     _check(lib().ref_build_tree(_p(rows), _dt(rows), V, C.c_int64(V), R, TT, d, k, root_token, TT_cap,
                                 C.byref(n), _p(tokens), _p(parents), _p(depth), _p(score), _p(logp),
-                                _p(src_row), _p(mask), C.byref(margin)), "ref_build_tree")
+                                _p(src_row), _p(mask), C.byref(margin), _p(ecnt), _p(etok), _p(epar), _p(emask)),
+           "ref_build_tree")
     N = n.value
-    return dict(n_nodes=N, tokens=tokens[:N], parents=parents[:N], depth=depth[:N], score=score[:N],
-                logp=logp[:N], src_row=src_row[:N], anc_mask=mask[:N], min_margin=margin.value)
+    out = dict(n_nodes=N, tokens=tokens[:N], parents=parents[:N], depth=depth[:N], score=score[:N],
+               logp=logp[:N], src_row=src_row[:N], anc_mask=mask[:N], min_margin=margin.value)
+    if with_levels:
+        out["levels"] = [None] + [dict(tokens=etok[l, :ecnt[l]], parent_slot=epar[l, :ecnt[l]],
+                                       rows=1 + (l - 1) * k + np.arange(ecnt[l]), mask=emask[l, :ecnt[l]])
+                                  for l in range(1, max(d, 1))]
+    return out
 
 
 def tree_attention(q, k_tree, v_tree, k_prefix, v_prefix, anc_mask, scale, samples=None, TT_cap=TT_MAX):

@@ -44,6 +44,35 @@ def brute_tree(draft_fn, V, TT, d, k):
     return kept, score
 
 
+def brute_frontiers(draft_fn, V, d, k):
+    """The strings expanded at levels 1..d-1, each level as an ORDERED list: a level's chosen strings are
+    listed parent by parent (in the order the parents were listed one level up) and, under one parent, in
+    the order of that parent's top-k list.  Returns [None, level 1, ..., level d-1]."""
+    def topk(string):
+        x = draft_fn(string).astype(np.float64)
+        lse = logsumexp(x)
+        order = sorted(range(V), key=lambda t: (-x[t], t))[:k]
+        return [(t, x[t] - lse) for t in order if x[t] > -np.inf]
+
+    score = {(): 0.0}
+    out = [None]
+    frontier = [()]
+    for level in range(1, d):
+        cands = []                      # in (parent order, rank under the parent) order
+        for s in frontier:
+            for t, lp in topk(s):
+                score[s + (t,)] = score[s] + lp
+                cands.append(s + (t,))
+        chosen = set(sorted(cands, key=lambda c: -score[c])[:k])
+        frontier = [c for c in cands if c in chosen]
+        out.append(frontier)
+        if not frontier:
+            break
+    while len(out) < max(d, 1):
+        out.append([])
+    return out
+
+
 def brute_greedy_accept(strings, target_fn):
     """strings: set of kept token strings (the tree without the root).
 

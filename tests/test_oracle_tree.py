@@ -7,7 +7,7 @@ import pytest
 
 import dt_synth
 from oracle import ref
-from tests._brute import brute_tree, toy_logits
+from tests._brute import brute_frontiers, brute_tree, toy_logits
 from tests._drive import node_strings, rows_from_fn
 
 
@@ -185,3 +185,49 @@ def test_exact_score_ties_across_rows_go_to_the_lowest_pool_index():
     # the first level-1 node; the two level-3 nodes kept are the children of the first of those.
     assert set(node_strings(t)) == {(), (0,), (1,), (0, 0), (0, 1), (1, 0), (1, 1), (0, 0, 0), (0, 0, 1)}
     assert t["min_margin"] == 0.0          # such an input is exactly what the margin guard flags
+
+
+@pytest.mark.parametrize("V,TT,d,k", [(8, 6, 3, 2), (8, 3, 3, 3), (6, 12, 4, 2), (7, 5, 2, 3), (5, 9, 3, 3)])
+def test_level_outputs_match_the_brute_force_frontiers(V, TT, d, k):
+    # what a draft model between the levels is handed: the expanded nodes of every level, in slot order.
+    # The brute force works on token strings only; TT is small on purpose (the rerank may later drop
+    # expanded nodes from the tree, the level outputs must not care).
+    for seed in range(6):
+        fn = lambda s: toy_logits(100 + seed, s, V)
+        rows = rows_from_fn(ref.build_tree, fn, V, d, k)
+        t = ref.build_tree(rows, TT, d, k, with_levels=True)
+        want = brute_frontiers(fn, V, d, k)
+        strings = {0: [()]}
+        for l in range(1, d):
+            lv = t["levels"][l]
+            mine = []
+            for s in range(len(lv["tokens"])):
+                par = () if lv["parent_slot"][s] < 0 else strings[l - 1][lv["parent_slot"][s]]
+                assert (lv["parent_slot"][s] < 0) == (l == 1)
+                mine.append(par + (int(lv["tokens"][s]),))
+            strings[l] = mine
+            assert mine == want[l], (seed, l)
+            for s in range(len(mine)):
+                # draft-side mask: own row, the parent's mask, nothing else
+                bits = {r for r in range(256) if (int(lv["mask"][s][r // 64]) >> (r % 64)) & 1}
+                up = {0} if l == 1 else {r for r in range(256)
+                                         if (int(t["levels"][l - 1]["mask"][lv["parent_slot"][s]][r // 64]) >> (r % 64)) & 1}
+                assert bits == up | {int(lv["rows"][s])} and len(bits) == l + 1
+
+
+def test_level_outputs_survive_a_rerank_that_drops_expanded_nodes_and_stop_without_candidates():
+    V, d, k = 8, 4, 3
+    fn = lambda s: toy_logits(7, s, V)
+    rows = rows_from_fn(ref.build_tree, fn, V, d, k)
+    small = ref.build_tree(rows, 2, d, k, with_levels=True)        # the tree keeps one node only
+    big = ref.build_tree(rows, 40, d, k, with_levels=True)
+    for l in range(1, d):
+        assert np.array_equal(small["levels"][l]["tokens"], big["levels"][l]["tokens"])
+        assert np.array_equal(small["levels"][l]["parent_slot"], big["levels"][l]["parent_slot"])
+    assert small["n_nodes"] == 2
+    one = ref.build_tree(rows, 1, d, k, with_levels=True)          # TT = 1: nothing is drafted at all
+    assert all(len(one["levels"][l]["tokens"]) == 0 for l in range(1, d))
+    rows2 = rows.copy()
+    rows2[1:1 + k] = -np.inf                                         # level-1 nodes propose nothing
+    t = ref.build_tree(rows2, 40, d, k, with_levels=True)
+    assert len(t["levels"][1]["tokens"]) == k and len(t["levels"][2]["tokens"]) == 0 and len(t["levels"][3]["tokens"]) == 0
