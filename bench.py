@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=400)
+    ap.add_argument("--streaming-build", type=int, default=1,
+                    help="also time the level-at-a-time build of the same tree (0: skip)")
     ap.add_argument("--commit-layers", type=int, default=32,
                     help="layers of the separately timed input update (0: skip it)")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
@@ -241,6 +243,49 @@ def main():
         log("  kernel %-20s avg %8.2f us  (%d layers, %d accepted-path rows, %.2f MB moved; outside the timed step)"
             % ("commit", commit["avg_us"], nl, rows, cbytes / 1e6))
 
+    # ---- the same tree built one level at a time (a draft model would run between the calls); outside
+    #      the timed step.  Level l's rows are the draft rows the one-shot build reads for that level. ----
+    streaming = None
+    if args.streaming_build and len(set(cfg.params)) == 1:
+        TT0, d0, k0 = cfg.params[0]
+        st0 = steps[0]
+        rows_b = [st0.draft_logits[int(st0.host_row_off[b]):int(st0.host_row_off[b + 1])] for b in range(cfg.B)]
+        lvl = [torch.stack([r[0] for r in rows_b])]
+        for l in range(2, d0 + 1):
+            lvl.append(torch.cat([r[1 + (l - 2) * k0:1 + (l - 1) * k0] for r in rows_b]).contiguous())
+        state = torch.zeros(dt.dt_level_state_bytes(cfg.B), dtype=torch.uint8, device="cuda")
+        ws2 = torch.empty(dt.dt_workspace_bytes(cfg.B, cfg.B * k0, cfg.V, st0.TT_cap, 1, 1), dtype=torch.uint8,
+                          device="cuda")
+        i32 = dict(dtype=torch.int32, device="cuda")
+        nx = torch.zeros(cfg.B, **i32)
+        ex = [torch.zeros((cfg.B, 32), **i32) for _ in range(4)]
+        em = torch.zeros((cfg.B, 32, 4), dtype=torch.int64, device="cuda")
+        outs = [torch.zeros_like(st0.n_nodes), torch.zeros_like(st0.tokens), torch.zeros_like(st0.parents),
+                torch.zeros_like(st0.depth), torch.zeros_like(st0.score), torch.zeros_like(st0.logp),
+                torch.zeros_like(st0.src_row), torch.zeros_like(st0.anc_mask)]
+
+        def build_by_levels():
+            for l in range(1, d0 + 1):
+                dt.dt_expand_level(l, st0.params, lvl[l - 1], k0, st0.prefix_len, st0.TT_cap, state, nx, *ex, em, ws2)
+            dt.dt_finish_tree(st0.params, cfg.V, st0.root_token, st0.TT_cap, state, *outs)
+
+        for _ in range(5):
+            build_by_levels()
+        torch.cuda.synchronize()
+        same = bool(torch.equal(outs[1], st0.tokens) and torch.equal(outs[2], st0.parents) and
+                    torch.equal(outs[0], st0.n_nodes))
+        n_s = 100
+        s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s0.record()
+        for _ in range(n_s):
+            build_by_levels()
+        s1.record()
+        torch.cuda.synchronize()
+        streaming = {"us_per_build": round(s0.elapsed_time(s1) * 1e3 / n_s, 2), "levels": d0, "calls": d0 + 1,
+                     "launches": 3 * d0 + 1, "same_tree_as_one_shot": same, "in_timed_step": False}
+        log("  level-at-a-time build: %.1f us for %d levels + finish (%d launches, eager); same tree: %s"
+            % (streaming["us_per_build"], d0, 3 * d0 + 1, same))
+
     if args.calibration_copy_mb > 0:
         n = args.calibration_copy_mb * 1000 * 1000 // 4
         src = torch.arange(n, dtype=torch.float32, device="cuda")
@@ -293,6 +338,7 @@ def main():
         "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()}
                     for k, v in kern.items()},
         "input_update": commit,
+        "streaming_build": streaming,
         "roofline": roofline,
         "roofline_all_streams": roofline_all,
         "cpu_baseline": cpu,

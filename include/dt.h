@@ -170,6 +170,43 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
               void *ws, size_t ws_bytes);
 
 /*
+ * The same tree, built one level at a time, for a draft model that sits between the levels
+ * (paper Appendix B, Algorithm 2: every pass of the expansion loop runs the draft model on the
+ * nodes chosen one level up, then chooses the next ones).  Call pattern per step:
+ *     for level = 1 .. max d:   [draft model] -> dt_expand_level(level, logits of this pass)
+ *     dt_finish_tree            -> the outputs of dt_build_tree
+ * `state` (dt_level_state_bytes(batch) bytes, 256-byte aligned, caller-owned, contents opaque, need not
+ * be cleared) carries the row results from call to call; all calls of one step use the same batch,
+ * params, V and TT_cap.
+ *
+ * dt_expand_level, level l: level_logits holds the rows of this pass, sequence b's row s at
+ * level_logits + (b*R + s)*row_stride with R = 1 for level 1 (the root's next-token row) and
+ * R = rows_per_seq (>= every k, <= DT_K_MAX) otherwise; row s belongs to the s-th node that the
+ * previous call reported for sequence b (rows at and past that call's n_expand[b] are ignored).
+ * The call scores the candidates of level l and reports the nodes of level l that are expanded
+ * next, in slot order (= ascending pool index):
+ *   n_expand        [batch]            how many (0 when l >= d, TT == 1, or nothing is viable)
+ *   exp_token       [batch, DT_K_MAX]  their tokens
+ *   exp_parent_slot [batch, DT_K_MAX]  slot of the parent in the previous call's list (-1: the root)
+ *   exp_row         [batch, DT_K_MAX]  the draft row each is handed, 1 + (l-1)k + slot
+ *   exp_pos         [batch, DT_K_MAX]  position id prefix_len[b] + l (prefix_len may be NULL: l)
+ *   exp_mask        [batch, DT_K_MAX, 4]  draft-side tree mask over draft rows (bit r: row r belongs to
+ *                                      the node or one of its ancestors; row 0 = root)
+ * Workspace: dt_workspace_bytes(batch, batch*R, V, TT_cap, 1, 1) bytes.
+ * dt_finish_tree reranks and emits exactly what dt_build_tree would from the same rows.
+ * Errors as dt_build_tree; level outside 1..DT_D_MAX, rows_per_seq outside 1..DT_K_MAX or a
+ * misaligned state -> DT_ERR_INVALID_ARG.
+ */
+int dt_level_state_bytes(int batch, size_t *bytes);
+int dt_expand_level(void *stream, int batch, int level, const dt_params *params, const void *level_logits, dt_dtype t,
+                    int V, int64_t row_stride, int rows_per_seq, const int32_t *prefix_len, int TT_cap, void *state,
+                    int32_t *n_expand, int32_t *exp_token, int32_t *exp_parent_slot, int32_t *exp_row, int32_t *exp_pos,
+                    uint64_t *exp_mask, void *ws, size_t ws_bytes);
+int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, const int32_t *root_token, int TT_cap,
+                   const void *state, int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth, float *score,
+                   float *logp, int32_t *src_row, uint64_t *anc_mask);
+
+/*
  * Input update after verification (paper Appendix, "System Profiling and Overhead Analysis": the
  * input update brings the KV cache to the state of the next step -- accepted tokens kept, rejected
  * ones discarded, positions continued).  For every sequence b, layer l and both of K and V, the tree

@@ -48,6 +48,9 @@ def load_library():
                                           vp, i32, vp, vp, sz]
         lib.dt_accept.argtypes = [vp, i32, i32, f32, vp, i32, i32, i64, vp, vp, vp, vp, vp, vp, i32, u64, u64,
                                   vp, vp, vp, vp, vp, vp, sz]
+        lib.dt_level_state_bytes.argtypes = [i32, C.POINTER(sz)]
+        lib.dt_expand_level.argtypes = [vp, i32, i32, vp, vp, i32, i32, i64, i32, vp, i32, vp] + [vp] * 6 + [vp, sz]
+        lib.dt_finish_tree.argtypes = [vp, i32, vp, i32, vp, i32, vp] + [vp] * 8
         lib.dt_commit.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i32, vp, vp]
         lib.dt_profile_enable.argtypes = [i32]
         lib.dt_profile_enable.restype = i32
@@ -55,7 +58,8 @@ def load_library():
         lib.dt_profile_read.restype = i32
         lib.dt_profile_kernel_name.argtypes = [i32]
         lib.dt_profile_kernel_name.restype = C.c_char_p
-        for fn in ("dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept", "dt_commit"):
+        for fn in ("dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept", "dt_commit",
+                   "dt_level_state_bytes", "dt_expand_level", "dt_finish_tree"):
             getattr(lib, fn).restype = i32
         _lib = lib
     return _lib
@@ -130,6 +134,31 @@ def dt_accept(mode, temperature, target_logits, n_nodes, tokens, parents, depth,
         _ptr(n_nodes), _ptr(tokens), _ptr(parents), _ptr(depth), _ptr(logp), _ptr(anc_mask), TT_cap, philox_seed,
         philox_step, _ptr(accept_len), _ptr(best_node), _ptr(path_nodes), _ptr(out_tokens), _ptr(node_argmax),
         _ptr(ws), ws.numel() * ws.element_size()))
+
+
+def dt_level_state_bytes(batch):
+    out = C.c_size_t(0)
+    _check("dt_level_state_bytes", load_library().dt_level_state_bytes(batch, C.byref(out)))
+    return out.value
+
+
+def dt_expand_level(level, params, level_logits, rows_per_seq, prefix_len, TT_cap, state, n_expand, exp_token,
+                    exp_parent_slot, exp_row, exp_pos, exp_mask, ws):
+    """level_logits: [batch * R, V] with R = 1 at level 1, rows_per_seq otherwise."""
+    batch = params.shape[0]
+    V = level_logits.shape[1]
+    _check("dt_expand_level", load_library().dt_expand_level(
+        _stream(), batch, level, _ptr(params), _ptr(level_logits), _dtype(level_logits), V, level_logits.stride(0),
+        rows_per_seq, _ptr(prefix_len), TT_cap, _ptr(state), _ptr(n_expand), _ptr(exp_token), _ptr(exp_parent_slot),
+        _ptr(exp_row), _ptr(exp_pos), _ptr(exp_mask), _ptr(ws), ws.numel() * ws.element_size()))
+
+
+def dt_finish_tree(params, V, root_token, TT_cap, state, n_nodes, tokens, parents, depth, score, logp, src_row,
+                   anc_mask):
+    batch = params.shape[0]
+    _check("dt_finish_tree", load_library().dt_finish_tree(
+        _stream(), batch, _ptr(params), V, _ptr(root_token), TT_cap, _ptr(state), _ptr(n_nodes), _ptr(tokens),
+        _ptr(parents), _ptr(depth), _ptr(score), _ptr(logp), _ptr(src_row), _ptr(anc_mask)))
 
 
 def dt_commit(dtype_of, Hkv, D, k_tree_ptrs, v_tree_ptrs, k_prefix_ptrs, v_prefix_ptrs, prefix_len, prefix_cap,

@@ -58,6 +58,26 @@ inline TopkScratch topk_scratch(void *ws, int64_t rows, int S) {
 }
 inline bool topk_v_ok(int V) { return V >= 1 && dt::rows_chunks_per_row(V, dt::rows_topk_nl(V)) <= 64; }
 
+struct LevelState {  // row results of one sequence after the other, then the per-sequence counts
+    float *top_val;    // [batch, DT_STATE_ROWS, DT_K_MAX]
+    int32_t *top_id;
+    float *lse;        // [batch, DT_STATE_ROWS]
+    int32_t *n_exp;    // [batch] nodes expanded at the last level processed
+    size_t bytes;
+};
+inline LevelState level_state(void *st, int batch) {
+    LevelState r;
+    char *p = (char *)st;
+    const size_t rows = (size_t)batch * DT_STATE_ROWS;
+    size_t off = 0;
+    r.top_val = (float *)(p + off); off += align_up(rows * DT_K_MAX * 4);
+    r.top_id = (int32_t *)(p + off); off += align_up(rows * DT_K_MAX * 4);
+    r.lse = (float *)(p + off); off += align_up(rows * 4);
+    r.n_exp = (int32_t *)(p + off); off += align_up((size_t)batch * 4);
+    r.bytes = off;
+    return r;
+}
+
 inline int hip_fail(hipError_t e) {
     g_last_hip = (int)e;
     return DT_ERR_HIP;
@@ -232,6 +252,76 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     aa.path_nodes = path_nodes; aa.out_tokens = out_tokens; aa.node_argmax = node_argmax;
     aa.part_keys = rs.keys; aa.part_ms = rs.ms; aa.S = S; aa.chunk_elems = 256 * 8 * nl;
     e = dt::accept_launch(aa, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
+int dt_level_state_bytes(int batch, size_t *bytes) {
+    if (!bytes || batch < 0) return DT_ERR_INVALID_ARG;
+    *bytes = level_state(nullptr, batch).bytes;
+    return DT_OK;
+}
+
+int dt_expand_level(void *stream, int batch, int level, const dt_params *params, const void *level_logits, dt_dtype t,
+                    int V, int64_t row_stride, int rows_per_seq, const int32_t *prefix_len, int TT_cap, void *state,
+                    int32_t *n_expand, int32_t *exp_token, int32_t *exp_parent_slot, int32_t *exp_row, int32_t *exp_pos,
+                    uint64_t *exp_mask, void *ws, size_t ws_bytes) {
+    if (batch < 0 || bad_dtype(t) || level < 1 || level > DT_D_MAX) return DT_ERR_INVALID_ARG;
+    if (batch == 0) return DT_OK;
+    if (!params || !level_logits || !state || !n_expand || !exp_token || !exp_parent_slot || !exp_row || !exp_pos ||
+        !exp_mask || row_stride < V || (uintptr_t)state % 256)
+        return DT_ERR_INVALID_ARG;
+    if (rows_per_seq < 1 || rows_per_seq > DT_K_MAX) return DT_ERR_INVALID_ARG;
+    if (!topk_v_ok(V) || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
+    const int rps = level == 1 ? 1 : rows_per_seq;
+    const int64_t total_rows = (int64_t)batch * rps;
+    const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
+    if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
+    TopkScratch rs = topk_scratch(ws, total_rows, S);
+    if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
+    LevelState ls = level_state(state, batch);
+
+    dt::RowArgs a = {};
+    a.logits = level_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
+    a.mode = dt::ROWS_LEVEL; a.batch = batch; a.params = params; a.TT_cap = TT_cap;
+    a.level = level; a.rows_per_seq = rps; a.state_rows = DT_STATE_ROWS; a.n_exp_prev = ls.n_exp;
+    a.want_lse = 1; a.inv_t = 1.0f;
+    a.lane_max = rs.lane_max; a.part_ms = rs.ms;
+    hipStream_t st = (hipStream_t)stream;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
+    hipError_t e = dt::rows_launch_stream(a, total_rows, nl, st);
+    if (e != hipSuccess) return hip_fail(e);
+    e = dt::rows_launch_select(a, total_rows, nl, ls.top_val, ls.top_id, ls.lse, DT_K_MAX, st);
+    if (e != hipSuccess) return hip_fail(e);
+
+    dt::TreeArgs ta = {};
+    ta.batch = batch; ta.params = params; ta.V = V; ta.row_off = nullptr; ta.seq_rows = DT_STATE_ROWS;
+    ta.TT_cap = TT_cap; ta.top_val = ls.top_val; ta.top_id = ls.top_id; ta.lse = ls.lse;
+    ta.expand_level = level; ta.prefix_len = prefix_len; ta.n_expand = n_expand; ta.state_n_exp = ls.n_exp;
+    ta.exp_token = exp_token; ta.exp_parent_slot = exp_parent_slot; ta.exp_row = exp_row; ta.exp_pos = exp_pos;
+    ta.exp_mask = (unsigned long long *)exp_mask;
+    e = dt::tree_launch(ta, st);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
+int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, const int32_t *root_token, int TT_cap,
+                   const void *state, int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth, float *score,
+                   float *logp, int32_t *src_row, uint64_t *anc_mask) {
+    if (batch < 0) return DT_ERR_INVALID_ARG;
+    if (batch == 0) return DT_OK;
+    if (!params || !root_token || !state || !n_nodes || !tokens || !parents || !depth || !score || !logp || !src_row ||
+        !anc_mask || (uintptr_t)state % 256)
+        return DT_ERR_INVALID_ARG;
+    if (V < 1 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
+    LevelState ls = level_state((void *)state, batch);
+    dt::TreeArgs ta = {};
+    ta.batch = batch; ta.params = params; ta.V = V; ta.row_off = nullptr; ta.seq_rows = DT_STATE_ROWS;
+    ta.root_token = root_token; ta.TT_cap = TT_cap; ta.top_val = ls.top_val; ta.top_id = ls.top_id; ta.lse = ls.lse;
+    ta.n_nodes = n_nodes; ta.tokens = tokens; ta.parents = parents; ta.depth = depth; ta.src_row = src_row;
+    ta.score = score; ta.logp = logp; ta.anc_mask = (unsigned long long *)anc_mask;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
+    hipError_t e = dt::tree_launch(ta, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);
     return DT_OK;
 }

@@ -24,7 +24,8 @@ inline void launch_kernel(int kid, hipStream_t st, F kernel, dim3 grid, dim3 blo
 }
 
 // ------------------------------------------------------------------ row kernels (rows.hip)
-enum RowMode { ROWS_UNIFORM = 0, ROWS_DRAFT = 1, ROWS_TARGET = 2 };
+enum RowMode { ROWS_UNIFORM = 0, ROWS_DRAFT = 1, ROWS_TARGET = 2, ROWS_LEVEL = 3 };
+#define DT_STATE_ROWS (1 + (DT_D_MAX - 1) * DT_K_MAX)  // draft rows a sequence can own
 
 struct RowArgs {
     const void *logits;
@@ -43,6 +44,9 @@ struct RowArgs {
     unsigned long long *part_keys;  // arg max rows: [rows, S] best key of every chunk
     float *lane_max;      // top-k rows: [rows, S*256] one maximum per lane
     float2 *part_ms;      // (max, sum exp((x-max)*inv_t)): [rows, S] (arg max rows), [rows, S*4] (top-k rows)
+    // ROWS_LEVEL: rows of one level of every sequence, results scattered into the build state
+    int level, rows_per_seq, state_rows;
+    const int32_t *n_exp_prev;  // [batch] nodes expanded one level up
 };
 
 int rows_chunks_per_row(int V, int nl);
@@ -67,6 +71,12 @@ struct TreeArgs {
     int32_t *n_nodes, *tokens, *parents, *depth, *src_row;
     float *score, *logp;
     unsigned long long *anc_mask;
+    // level-at-a-time build.  row_off == nullptr: sequence b's row results start at b * seq_rows.
+    int64_t seq_rows;
+    int expand_level;       // 0: whole tree; l > 0: only the set of level-l nodes to expand
+    const int32_t *prefix_len;  // may be null (positions then count from 0)
+    int32_t *n_expand, *state_n_exp, *exp_token, *exp_parent_slot, *exp_row, *exp_pos;  // [batch(, DT_K_MAX)]
+    unsigned long long *exp_mask;  // [batch, DT_K_MAX, 4]
 };
 hipError_t tree_launch(const TreeArgs &a, hipStream_t st);
 

@@ -17,13 +17,26 @@ namespace dt {
 struct RowMeta {
     bool valid;
     int k;
+    int64_t out;  // row index of the results (top-k values, ids, lse)
 };
 
 __device__ __forceinline__ RowMeta row_meta(const RowArgs &a, int64_t g) {
     RowMeta m;
     m.valid = true;
     m.k = a.k_uniform;
-    if (a.mode == ROWS_DRAFT) {
+    m.out = g;
+    if (a.mode == ROWS_LEVEL) {
+        // level-at-a-time build: row s of sequence b in this call is the row of the s-th node expanded
+        // one level up (level 1: the root's row); its results go to the sequence's row slot in the state
+        const int b = (int)(g / a.rows_per_seq), s = (int)(g % a.rows_per_seq);
+        const dt_params p = a.params[b];
+        const int TT = min(max(p.TT, 1), a.TT_cap), d = min(max(p.d, 1), DT_D_MAX);
+        const int k = min(max(p.k, 1), min(DT_K_MAX, a.V));
+        const int cnt = a.level == 1 ? 1 : min(max(a.n_exp_prev[b], 0), k);
+        m.k = k;
+        m.valid = TT > 1 && a.level <= d && s < cnt;
+        m.out = (int64_t)b * a.state_rows + (a.level == 1 ? 0 : 1 + (a.level - 2) * k + s);
+    } else if (a.mode == ROWS_DRAFT) {
         // sequence b with row_off[b] <= g < row_off[b+1]
         int lo = 0, hi = a.batch;
         while (hi - lo > 1) {
@@ -191,8 +204,8 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     __shared__ int s_n2;
     __shared__ u64 s_best[4];
 
-    float *tv = top_val + g * out_stride;
-    int32_t *ti = top_id ? top_id + g * out_stride : nullptr;
+    float *tv = top_val + meta.out * out_stride;
+    int32_t *ti = top_id ? top_id + meta.out * out_stride : nullptr;
     auto emit = [&](int r, u64 key) {
         float v = key_val(key);
         u32 id = key_idx(key);
@@ -257,7 +270,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
         const float Mw = wave_max(M);
         float term = (Ssum > 0.f) ? Ssum * __builtin_amdgcn_exp2f((M - Mw) * cexp) : 0.f;
         term = wave_sum(term);
-        if (lane == 0) lse[g] = (Mw == -INFINITY) ? -INFINITY : Mw * a.inv_t + __logf(term);
+        if (lane == 0) lse[meta.out] = (Mw == -INFINITY) ? -INFINITY : Mw * a.inv_t + __logf(term);
     }
 
     if (!slow) {

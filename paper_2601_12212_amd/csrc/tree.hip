@@ -219,7 +219,8 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     const dt_params prm = a.params[b];
     const int TT = min(max(prm.TT, 1), a.TT_cap), d = min(max(prm.d, 1), DT_D_MAX);
     const int k = min(max(prm.k, 1), min(DT_K_MAX, a.V));
-    const int64_t r0 = a.row_off[b];
+    const int64_t r0 = a.row_off ? a.row_off[b] : (int64_t)b * a.seq_rows;
+    const int xl = a.expand_level;  // > 0: only the nodes of level xl that are expanded next
     const float *tv = a.top_val + r0 * DT_K_MAX;
     const int32_t *ti = a.top_id + r0 * DT_K_MAX;
     const float *lse = a.lse + r0;
@@ -235,7 +236,11 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     __shared__ u32 s_scratch[64];
 
     STAMP(0);
-    if (tid == 0) {
+    if (xl > 0 && (TT == 1 || xl >= d)) {  // nothing is drafted below level d
+        if (tid == 0) { a.n_expand[b] = 0; a.state_n_exp[b] = 0; }
+        return;
+    }
+    if (tid == 0 && xl == 0) {
         a.tokens[o] = a.root_token[b];
         a.parents[o] = -1;
         a.depth[o] = 0;
@@ -249,7 +254,9 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
         if (tid == 0) a.n_nodes[b] = 1;
         return;
     }
-    const int P = k + (d - 1) * k * k;
+    // candidates through level d, or through level xl when only that level's choice is wanted (the
+    // rows of deeper levels do not exist yet)
+    const int P = xl > 0 ? k + (xl - 1) * k * k : k + (d - 1) * k * k;
     // Every candidate's own log-probability is known up front: the draft row that would
     // produce pool index p is fixed by p alone (only its parent is decided later).  Park
     // lp in s_score; the level loop turns it into the cumulative score in place.
@@ -265,7 +272,8 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
 
     // ---- expansion, level by level -----------------------------------------------------------
     int p_end = k;  // pool indices below p_end hold real scores (levels computed so far)
-    for (int l = 1; l < d; ++l) {
+    const int l_end = xl > 0 ? xl + 1 : d;
+    for (int l = 1; l < l_end; ++l) {
         const int lo = l == 1 ? 0 : k + (l - 2) * k * k;
         const int n = l == 1 ? k : k * k;
         if (w == 0) {
@@ -279,6 +287,38 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
         STAMP(2 + 2 * l);
         __syncthreads();
         const int n_exp = s_nexp;
+        if (l == xl) {
+            // ---- what the draft model is handed for its next pass: node s of the chosen set ----------
+            if (tid < n_exp) {
+                const int pi = s_exp[l][tid];
+                const Decoded dc = decode(pi, k);
+                const int64_t e = (int64_t)b * DT_K_MAX + tid;
+                a.exp_token[e] = ti[dc.row * DT_K_MAX + dc.rank];
+                a.exp_parent_slot[e] = l == 1 ? -1 : dc.slot;
+                const int own = 1 + (l - 1) * k + tid;
+                a.exp_row[e] = own;
+                a.exp_pos[e] = (a.prefix_len ? max(a.prefix_len[b], 0) : 0) + l;
+                // draft-side mask over draft rows: the root's row, the rows of the ancestors, its own
+                u64 m0 = 1ull, m1 = 0ull, m2 = 0ull, m3 = 0ull;
+                auto set = [&](int r) {
+                    const u64 bit = 1ull << (r & 63);
+                    const int wd = r >> 6;
+                    m0 |= wd == 0 ? bit : 0ull; m1 |= wd == 1 ? bit : 0ull;
+                    m2 |= wd == 2 ? bit : 0ull; m3 |= wd == 3 ? bit : 0ull;
+                };
+                set(own);
+                int pp = l == 1 ? -1 : s_exp[l - 1][dc.slot];
+                for (int guard = 0; guard < DT_D_MAX && pp >= 0; ++guard) {
+                    const Decoded dp = decode(pp, k);
+                    set(1 + (dp.level - 1) * k + s_slot[pp]);
+                    pp = dp.level == 1 ? -1 : s_exp[dp.level - 1][dp.slot];
+                }
+                a.exp_mask[e * 4] = m0; a.exp_mask[e * 4 + 1] = m1;
+                a.exp_mask[e * 4 + 2] = m2; a.exp_mask[e * 4 + 3] = m3;
+            }
+            if (tid == 0) { a.n_expand[b] = n_exp; a.state_n_exp[b] = n_exp; }
+            return;
+        }
         if (n_exp == 0) break;
         const int nlo = k + (l - 1) * k * k;
         for (int t = tid; t < k * k; t += 256) {
@@ -291,6 +331,10 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
         STAMP(3 + 2 * l);
     }
 
+    if (xl > 0) {  // an earlier level had nothing viable to expand
+        if (tid == 0) { a.n_expand[b] = 0; a.state_n_exp[b] = 0; }
+        return;
+    }
     __syncthreads();  // every wave has read s_nexp before it is reused below
 
     // ---- rerank: the TT-1 best of the whole pool ----------------------------------------------

@@ -91,6 +91,22 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_accept(*acc(mode=1, logp=None)) == -1
     assert lib.dt_accept(*acc(mode=1, T=0.0)) == -1
     assert lib.dt_accept(*acc(wsb=8)) == -3
+    # level-at-a-time build: level / rows-per-sequence out of range, misaligned state, null outputs
+    lev = lambda **kw: [None, kw.get("batch", 1), kw.get("level", 1), one, one, 1, 1024, 1024, kw.get("rps", 8), None, 60,
+                        kw.get("state", ws), kw.get("nexp", one), one, one, one, one, one, ws, kw.get("wsb", 1 << 24)]
+    assert lib.dt_expand_level(*lev(level=0)) == -1
+    assert lib.dt_expand_level(*lev(level=9)) == -1
+    assert lib.dt_expand_level(*lev(rps=33)) == -1
+    assert lib.dt_expand_level(*lev(state=C.c_void_p(4100))) == -1
+    assert lib.dt_expand_level(*lev(nexp=None)) == -1
+    assert lib.dt_expand_level(*lev(wsb=16)) == -3
+    assert lib.dt_expand_level(*lev(batch=0)) == 0
+    fin = lambda **kw: [None, kw.get("batch", 1), one, 1024, one, kw.get("TT_cap", 60), kw.get("state", ws)] + [one] * 8
+    assert lib.dt_finish_tree(*fin(TT_cap=0)) == -2
+    assert lib.dt_finish_tree(*fin(state=None)) == -1
+    assert lib.dt_finish_tree(*fin(batch=0)) == 0
+    nbytes = C.c_size_t(0)
+    assert lib.dt_level_state_bytes(3, C.byref(nbytes)) == 0 and nbytes.value >= 3 * 225 * (32 * 8 + 4)
     # commit: null pointers, new length aliasing the old one, TT_cap over the limit, nothing to do
     other = C.c_void_p(512)
     com = lambda **kw: [None, kw.get("batch", 1), kw.get("layers", 2), 1, 8, 128, one, one, kw.get("kp", one), one, one,

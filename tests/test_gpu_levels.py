@@ -1,0 +1,157 @@
+"""GPU parity of the level-at-a-time build (dt_expand_level / dt_finish_tree) against the oracle.
+
+A toy draft model (a seeded function from a token string to a logit row) sits between the levels, as a real
+one would: each call's rows are computed from the strings of the nodes the previous call reported."""
+import numpy as np
+import pytest
+
+import dt_synth
+from oracle import ref
+from tests._brute import toy_logits
+from tests._cases import TREE_MARGIN, assert_tree_equal
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def drive(params, prefix_len, V, bf16, seed):
+    import paper_2601_12212_amd as dt
+    B = len(params)
+    KR = max(p[2] for p in params)
+    TT_cap = max(p[0] for p in params)
+    max_d = max(p[1] for p in params)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    d_params = torch.tensor(params, **i32)
+    d_plen = torch.tensor(prefix_len, **i32)
+    state = torch.full((dt.dt_level_state_bytes(B),), 0xEE, dtype=torch.uint8, device="cuda")   # never cleared
+    ws = torch.empty(dt.dt_workspace_bytes(B, B * KR, V, TT_cap, 1, 1), dtype=torch.uint8, device="cuda")
+    n_exp = torch.full((B,), -5, **i32)
+    e_tok = torch.full((B, 32), -5, **i32); e_par = torch.full((B, 32), -5, **i32)
+    e_row = torch.full((B, 32), -5, **i32); e_pos = torch.full((B, 32), -5, **i32)
+    e_mask = torch.zeros((B, 32, 4), dtype=torch.int64, device="cuda")
+
+    def fn(b, s):
+        x = toy_logits(seed * 100 + b, s, V, sigma=3.0)
+        return dt_synth.bf16_bits_to_f32(dt_synth.f32_to_bf16_bits(x)) if bf16 else x
+
+    rows_all = [np.zeros((1 + (d - 1) * k, V), np.float32) for (TT, d, k) in params]
+    strings = [{0: [()]} for _ in range(B)]
+    got_levels = [dict() for _ in range(B)]
+    rng = np.random.default_rng(seed)
+    for level in range(1, max_d + 1):
+        R = 1 if level == 1 else KR
+        logits = (rng.standard_normal((B * R, V)) * 50).astype(np.float32)      # rows nobody may look at
+        for b, (TT, d, k) in enumerate(params):
+            for s, st in enumerate(strings[b].get(level - 1, [])):
+                row = fn(b, st)
+                logits[b * R + s] = row
+                if level <= d:
+                    rows_all[b][0 if level == 1 else 1 + (level - 2) * k + s] = row
+        dev = torch.from_numpy(logits).cuda()
+        if bf16:
+            dev = dev.to(torch.bfloat16)
+        dt.dt_expand_level(level, d_params, dev, KR, d_plen, TT_cap, state, n_exp, e_tok, e_par, e_row, e_pos, e_mask, ws)
+        torch.cuda.synchronize()
+        for b in range(B):
+            n = int(n_exp[b])
+            tok, par = e_tok[b, :n].cpu().numpy(), e_par[b, :n].cpu().numpy()
+            prev = strings[b].get(level - 1, [])
+            strings[b][level] = [(prev[par[s]] if par[s] >= 0 else ()) + (int(tok[s]),) for s in range(n)]
+            got_levels[b][level] = dict(tokens=tok, parent_slot=par, rows=e_row[b, :n].cpu().numpy(),
+                                        pos=e_pos[b, :n].cpu().numpy(),
+                                        mask=e_mask[b, :n].cpu().numpy().view(np.uint64))
+    # finish
+    n_nodes = torch.zeros(B, **i32)
+    mk = lambda dtype: torch.zeros((B, TT_cap), dtype=dtype, device="cuda")
+    tokens, parents, depth, src_row = mk(torch.int32), mk(torch.int32), mk(torch.int32), mk(torch.int32)
+    score, logp = mk(torch.float32), mk(torch.float32)
+    anc = torch.zeros((B, TT_cap, 2), dtype=torch.int64, device="cuda")
+    roots = torch.tensor([100 + b for b in range(B)], **i32)
+    dt.dt_finish_tree(d_params, V, roots, TT_cap, state, n_nodes, tokens, parents, depth, score, logp, src_row, anc)
+    torch.cuda.synchronize()
+    for b, (TT, d, k) in enumerate(params):
+        rows = dt_synth.f32_to_bf16_bits(rows_all[b]) if bf16 else rows_all[b]
+        want = ref.build_tree(rows, TT, d, k, 100 + b, with_levels=True)
+        assert want["min_margin"] >= TREE_MARGIN, ("pick another seed", b, want["min_margin"])
+        N = int(n_nodes[b])
+        got = dict(n_nodes=N, tokens=tokens[b, :N].cpu().numpy(), parents=parents[b, :N].cpu().numpy(),
+                   depth=depth[b, :N].cpu().numpy(), src_row=src_row[b, :N].cpu().numpy(),
+                   score=score[b, :N].cpu().numpy(), logp=logp[b, :N].cpu().numpy(),
+                   anc_mask=anc[b, :N].cpu().numpy().view(np.uint64))
+        assert_tree_equal(got, want, "seq %d" % b)
+        for level in range(1, max_d + 1):
+            g = got_levels[b][level]
+            if level >= d or TT == 1:
+                assert len(g["tokens"]) == 0, (b, level)
+                continue
+            w = want["levels"][level]
+            assert np.array_equal(g["tokens"], w["tokens"]), (b, level)
+            assert np.array_equal(g["parent_slot"], w["parent_slot"]), (b, level)
+            assert np.array_equal(g["rows"], w["rows"]), (b, level)
+            assert np.array_equal(g["mask"], w["mask"]), (b, level)
+            assert (g["pos"] == prefix_len[b] + level).all()
+
+
+def test_level_by_level_fp32_ragged_batch():
+    drive([(30, 4, 3), (60, 6, 4), (1, 3, 2), (12, 1, 5), (128, 8, 2), (20, 3, 8)], [5, 0, 9, 1000, 77, 3], V=300,
+          bf16=False, seed=1)
+
+
+def test_level_by_level_bf16_wide_levels():
+    drive([(96, 4, 16), (64, 3, 32), (40, 5, 6)], [11, 12, 13], V=4099, bf16=True, seed=2)
+
+
+def test_the_level_loop_can_be_captured_and_replayed():
+    # The d-level loop with the finish call as one HIP graph (the draft model's passes would be nodes in
+    # between; here each level's logits sit in their own buffer).  Replayed several times with the outputs
+    # wiped and eager work in between; every replay must reproduce the eager result.
+    import paper_2601_12212_amd as dt
+    params, V, KR, TT_cap, d = [(40, 4, 5), (25, 3, 4)], 1000, 5, 40, 4
+    B = len(params)
+    i32 = dict(dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(3)
+    d_params = torch.tensor(params, **i32)
+    level_logits = [torch.from_numpy((rng.standard_normal((B * (1 if l == 1 else KR), V)) * 3).astype(np.float32)).cuda()
+                    for l in range(1, d + 1)]
+    state = torch.zeros(dt.dt_level_state_bytes(B), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(dt.dt_workspace_bytes(B, B * KR, V, TT_cap, 1, 1), dtype=torch.uint8, device="cuda")
+    n_exp = torch.zeros(B, **i32)
+    ex = [torch.zeros((B, 32), **i32) for _ in range(4)]
+    e_mask = torch.zeros((B, 32, 4), dtype=torch.int64, device="cuda")
+    roots = torch.tensor([1, 2], **i32)
+    outs = [torch.zeros(B, **i32)] + [torch.zeros((B, TT_cap), **i32) for _ in range(3)] + \
+           [torch.zeros((B, TT_cap), dtype=torch.float32, device="cuda") for _ in range(2)] + \
+           [torch.zeros((B, TT_cap), **i32), torch.zeros((B, TT_cap, 2), dtype=torch.int64, device="cuda")]
+
+    def run():
+        for l in range(1, d + 1):
+            dt.dt_expand_level(l, d_params, level_logits[l - 1], KR, None, TT_cap, state, n_exp, *ex, e_mask, ws)
+        dt.dt_finish_tree(d_params, V, roots, TT_cap, state, *outs)
+
+    run()
+    torch.cuda.synchronize()
+    eager = [o.clone() for o in outs]
+    assert int(eager[0].min()) > 1
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run()                                      # first touches on the capture stream
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            run()
+    for rep in range(3):
+        for o in outs:
+            o.fill_(-3)
+        state.fill_(rep)                           # the state carries nothing from one step to the next
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        N = eager[0]
+        for o, e in zip(outs, eager):
+            if o.dim() == 1:
+                assert torch.equal(o, e), rep
+            else:
+                for b in range(B):
+                    assert torch.equal(o[b, :int(N[b])], e[b, :int(N[b])]), (rep, b)
+        (torch.ones(1000, device="cuda") * 2).sum().item()    # eager work between replays
