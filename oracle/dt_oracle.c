@@ -35,6 +35,11 @@
  *     "input update" brings the KV cache to the state the next step starts from --
  *     the accepted tokens stay, the rejected ones are discarded, and positions
  *     continue from the new length (ref_commit_rows).
+ *   - Section 3.3 "Addressing the Challenges with Re-SpS" and Algorithm 1: the state is the
+ *     concatenation of three hidden-state vectors, the policy is a small MLP (Appendix A,
+ *     "Network Architecture"), a chosen action is reused for N decision points; Appendix A,
+ *     "Action Space in Implementation": the table of actions (ref_action_table,
+ *     ref_policy_logits, ref_policy_step).
  *
  * Pins: every function here is pinned by tests (library sorts, closed forms,
  * brute-force enumeration of token strings and of root-to-leaf paths, float64
@@ -614,4 +619,111 @@ int ref_commit_rows(void *cache, int dtype, int64_t cap, int64_t L, int64_t stri
     }
     *new_len = L + len + 1 < cap ? L + len + 1 : cap;
     return REF_OK;
+}
+
+/* ------------------------------------------------- action selection (policy + action cache) */
+
+/*
+ * Action table (Appendix A, "Action Space in Implementation"): all (TT, d, k) with
+ * TT in {32,48,64,80,96,128}, d in {3..8}, k in {8,12,16,20,32}, kept only if TT <= k^(d-1).
+ * Order (the paper gives none): TT-major, then d, then k.  out holds 3 ints per action.
+ * Returns the number of actions written (at most cap).
+ */
+int ref_action_table(int32_t *out, int cap)
+{
+    static const int TTs[] = {32, 48, 64, 80, 96, 128}, ds[] = {3, 4, 5, 6, 7, 8}, ks[] = {8, 12, 16, 20, 32};
+    int n = 0;
+    for (int a = 0; a < 6; ++a)
+        for (int b = 0; b < 6; ++b)
+            for (int c = 0; c < 5; ++c) {
+                double lim = pow((double)ks[c], (double)(ds[b] - 1));
+                if ((double)TTs[a] > lim) continue;
+                if (n < cap) { out[3 * n] = TTs[a]; out[3 * n + 1] = ds[b]; out[3 * n + 2] = ks[c]; }
+                ++n;
+            }
+    return n;
+}
+
+/*
+ * Policy network (Appendix A, "Network Architecture": an MLP with two hidden layers of H units on
+ * the state s_t = the three concatenated hidden-state vectors, Section 3.3; the defaults of the PPO
+ * implementation the paper names: tanh activations, one linear layer onto the action logits).
+ * Weight matrices are stored [in][out] row-major: W1 [F][H], W2 [H][H], W3 [H][A].
+ * Everything in double; logits[A] out.
+ */
+int ref_policy_logits(const float *feat, int F, int H, int A, const float *W1, const float *b1, const float *W2,
+                      const float *b2, const float *W3, const float *b3, double *logits)
+{
+    if (!feat || !W1 || !b1 || !W2 || !b2 || !W3 || !b3 || !logits || F < 1 || H < 1 || A < 1) return REF_ERR_ARG;
+    double *h1 = (double *)malloc(sizeof(double) * (size_t)H), *h2 = (double *)malloc(sizeof(double) * (size_t)H);
+    if (!h1 || !h2) { free(h1); free(h2); return REF_ERR_INTERNAL; }
+    for (int o = 0; o < H; ++o) {
+        double s = (double)b1[o];
+        for (int i = 0; i < F; ++i) s += (double)feat[i] * (double)W1[(size_t)i * H + o];
+        h1[o] = tanh(s);
+    }
+    for (int o = 0; o < H; ++o) {
+        double s = (double)b2[o];
+        for (int i = 0; i < H; ++i) s += h1[i] * (double)W2[(size_t)i * H + o];
+        h2[o] = tanh(s);
+    }
+    for (int a = 0; a < A; ++a) {
+        double s = (double)b3[a];
+        for (int i = 0; i < H; ++i) s += h2[i] * (double)W3[(size_t)i * A + a];
+        logits[a] = s;
+    }
+    free(h1); free(h2);
+    return REF_OK;
+}
+
+/*
+ * One decision point of Algorithm 1 ("Re-SpS with Action Caching") for one sequence.
+ *   cache_step, cached_action: in/out (start: 0 and -1 = nothing cached)
+ *   logits: the policy's action logits for the current state (read only when the policy is queried)
+ *   mode 0: the action of largest logit, ties -> lowest index; mode 1: a sample of softmax(logits) by
+ *   inverse CDF (double) at the Philox uniform with node index 0xFFFFFFFE
+ * The policy is queried iff cache_step == 0 or nothing is cached; the chosen action is then used for
+ * N consecutive decision points (cache_step counts them and is reset once it reaches N).
+ * Returns the action; *queried tells whether the policy was used; *margin (may be NULL) is lowered to
+ * the gap that decided a queried action (top-2 logit gap, or distance of the uniform to the CDF edges).
+ */
+int ref_policy_step(int *cache_step, int *cached_action, const double *logits, int A, int N, int mode,
+                    uint64_t seed, uint64_t step, uint32_t seq, int *queried, double *margin)
+{
+    if (!cache_step || !cached_action || !queried || A < 1 || N < 1) return REF_ERR_ARG;
+    if (*cache_step == 0 || *cached_action < 0) {
+        if (!logits) return REF_ERR_ARG;
+        int best = 0;
+        for (int a = 1; a < A; ++a)
+            if (logits[a] > logits[best]) best = a;
+        int act = best;
+        if (mode == 0) {
+            for (int a = 0; a < A; ++a)
+                if (a != best && margin && logits[best] - logits[a] < *margin) *margin = logits[best] - logits[a];
+        } else {
+            double Z = 0.0;
+            for (int a = 0; a < A; ++a) Z += exp(logits[a] - logits[best]);
+            double u = (double)ref_uniform(seed, step, seq, 0xFFFFFFFEu), cdf = 0.0, prev = 0.0;
+            act = -1;
+            for (int a = 0; a < A; ++a) {
+                prev = cdf;
+                cdf += exp(logits[a] - logits[best]) / Z;
+                if (cdf > u) { act = a; break; }
+            }
+            if (act < 0) act = A - 1;
+            else if (margin) {
+                if (cdf - u < *margin) *margin = cdf - u;
+                if (act > 0 && u - prev < *margin) *margin = u - prev;
+            }
+        }
+        *cached_action = act;
+        *cache_step = 1;
+        *queried = 1;
+    } else {
+        *cache_step += 1;
+        *queried = 0;
+    }
+    int act = *cached_action;
+    if (*cache_step >= N) *cache_step = 0;
+    return act;
 }

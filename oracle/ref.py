@@ -182,6 +182,37 @@ def commit_rows(cache, L, tree, path_nodes, accept_len, head_major=False):
     return new_len.value
 
 
+def action_table():
+    """Appendix A action table after the TT <= k^(d-1) filter: int32 [n, 3] rows (TT, d, k)."""
+    out = np.zeros((256, 3), np.int32)
+    n = lib().ref_action_table(_p(out), 256)
+    return out[:n].copy()
+
+
+def policy_logits(feat, W1, b1, W2, b2, W3, b3):
+    """MLP logits in float64.  feat [F] float32; W1 [F,H], W2 [H,H], W3 [H,A] float32 ([in][out])."""
+    f32 = lambda a: np.ascontiguousarray(a, np.float32)
+    feat, W1, b1, W2, b2, W3, b3 = map(f32, (feat, W1, b1, W2, b2, W3, b3))
+    F, H = W1.shape
+    A = W3.shape[1]
+    assert feat.shape == (F,) and W2.shape == (H, H) and W3.shape[0] == H
+    out = np.zeros(A, np.float64)
+    _check(lib().ref_policy_logits(_p(feat), F, H, A, _p(W1), _p(b1), _p(W2), _p(b2), _p(W3), _p(b3), _p(out)),
+           "ref_policy_logits")
+    return out
+
+
+def policy_step(cache_step, cached_action, logits, N, mode=0, seed=0, step=0, seq=0):
+    """One decision point of Algorithm 1.  Returns dict(action, cache_step, cached_action, queried, margin)."""
+    cs, ca, q = C.c_int(cache_step), C.c_int(cached_action), C.c_int(0)
+    margin = C.c_double(np.inf)
+    lg = None if logits is None else np.ascontiguousarray(logits, np.float64)
+    act = _check(lib().ref_policy_step(C.byref(cs), C.byref(ca), _p(lg), 1 if lg is None else len(lg), N, mode,
+                                       C.c_uint64(seed), C.c_uint64(step), C.c_uint32(seq), C.byref(q),
+                                       C.byref(margin)), "ref_policy_step")
+    return dict(action=act, cache_step=cs.value, cached_action=ca.value, queried=bool(q.value), margin=margin.value)
+
+
 def philox4x32(ctr, key):
     c = (C.c_uint32 * 4)(*ctr)
     k = (C.c_uint32 * 2)(*key)
