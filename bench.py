@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=400)
+    ap.add_argument("--policy-features", type=int, default=3 * 4096,
+                    help="state size of the separately timed policy step (0: skip it)")
     ap.add_argument("--streaming-build", type=int, default=1,
                     help="also time the level-at-a-time build of the same tree (0: skip)")
     ap.add_argument("--commit-layers", type=int, default=32,
@@ -243,6 +245,38 @@ def main():
         log("  kernel %-20s avg %8.2f us  (%d layers, %d accepted-path rows, %.2f MB moved; outside the timed step)"
             % ("commit", commit["avg_us"], nl, rows, cbytes / 1e6))
 
+    # ---- action selection (policy MLP + action cache), outside the timed step: evaluated at every call
+    #      here (interval 1); with the paper's interval of 30 it runs once per 30 steps -------------------
+    policy = None
+    if args.policy_features > 0:
+        F, H = args.policy_features, 128
+        table = torch.tensor(dt.dt_action_table(), dtype=torch.int32, device="cuda")
+        A = table.shape[0]
+        g = torch.Generator(device="cuda").manual_seed(5)
+        rn = lambda *sh: torch.randn(*sh, generator=g, device="cuda")
+        Wts = [rn(F, H) / F ** 0.5, rn(H) * 0.1, rn(H, H) / H ** 0.5, rn(H) * 0.1, rn(H, A) / H ** 0.5, rn(A) * 0.1]
+        feat = rn(cfg.B, F).to(tdtype)
+        i32 = dict(dtype=torch.int32, device="cuda")
+        cs, ca = torch.zeros(cfg.B, **i32), torch.full((cfg.B,), -1, **i32)
+        pout = torch.zeros((cfg.B, 3), **i32)
+        wsp = torch.empty(dt.dt_policy_workspace_bytes(cfg.B, F, H), dtype=torch.uint8, device="cuda")
+        n_p = 200
+        for _ in range(5):
+            dt.dt_policy_step(feat, *Wts, table, 1, 0, 0, 0, cs, ca, pout, None, None, None, wsp)
+        dt.dt_profile_enable(2 * n_p + 8)
+        for i in range(n_p):
+            dt.dt_policy_step(feat, *Wts, table, 1, 0, 0, i, cs, ca, pout, None, None, None, wsp)
+        torch.cuda.synchronize()
+        _, ms1, n1 = dt.dt_profile_read(9)
+        _, ms2, n2 = dt.dt_profile_read(10)
+        dt.dt_profile_enable(0)
+        pbytes = F * H * 4 + cfg.B * F * e
+        policy = {"layer1_us": round(ms1 * 1e3 / max(n1, 1), 3), "head_us": round(ms2 * 1e3 / max(n2, 1), 3),
+                  "features": int(F), "hidden": int(H), "actions": int(A), "layer1_bytes": int(pbytes),
+                  "layer1_gbps": round(pbytes / (ms1 * 1e-3 / max(n1, 1)) / 1e9, 1), "in_timed_step": False}
+        log("  policy: layer 1 %.2f us (%.1f MB, %.0f GB/s), head %.2f us; %d features, %d actions; outside the timed step"
+            % (policy["layer1_us"], pbytes / 1e6, policy["layer1_gbps"], policy["head_us"], F, A))
+
     # ---- the same tree built one level at a time (a draft model would run between the calls); outside
     #      the timed step.  Level l's rows are the draft rows the one-shot build reads for that level. ----
     streaming = None
@@ -339,6 +373,7 @@ def main():
                     for k, v in kern.items()},
         "input_update": commit,
         "streaming_build": streaming,
+        "policy": policy,
         "roofline": roofline,
         "roofline_all_streams": roofline_all,
         "cpu_baseline": cpu,

@@ -207,6 +207,39 @@ int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, cons
                    float *logp, int32_t *src_row, uint64_t *anc_mask);
 
 /*
+ * Action selection on the device (paper Section 3.3 and Algorithm 1 "Re-SpS with Action Caching";
+ * Appendix A "Action Space in Implementation", "Network Architecture").
+ *
+ * dt_action_table (host): writes the actions (TT, d, k) of the printed value sets that pass the printed
+ * filter TT <= k^(d-1), in the order TT, then d, then k, into table[0 .. min(capacity, *n_actions));
+ * *n_actions is their number (177).  The caller copies the table to the device.
+ *
+ * dt_policy_step: one decision point for every sequence.  If nothing is cached for sequence b
+ * (cached_action[b] < 0) or its interval is over (cache_step[b] == 0) the policy is evaluated on
+ * features[b] = the concatenated hidden-state vectors (F values, type feat_t, row stride feat_stride):
+ *     logits = W3^T tanh(W2^T tanh(W1^T x + b1) + b2) + b3          (fp32, weights [in][out] row-major:
+ *     W1 [F,H], W2 [H,H], W3 [H,n_actions]; H in {64,128}; n_actions <= 256)
+ * and the action is the largest logit (ties -> lowest index) or, with sample = 1, the inverse-CDF
+ * sample of softmax(logits) at the Philox uniform with node index 0xFFFFFFFE (see dt_accept); it is
+ * cached and cache_step[b] = 1.  Otherwise the cached action is used again and cache_step[b] += 1.
+ * cache_step[b] returns to 0 when it reaches cache_interval, so an action serves cache_interval
+ * consecutive decision points.  Outputs: params_out[b] = action_table[action] (a device array that
+ * dt_build_tree / dt_expand_level take as `params`: no host round trip), action_out[b], queried_out[b]
+ * (1 if the policy ran), logits_out[b, n_actions] (written only where the policy ran); the last
+ * three may be NULL.  Start of a generation: cache_step = 0, cached_action = -1.
+ * Workspace: dt_policy_workspace_bytes(batch, F, H), 256-byte aligned.
+ * Errors: H not 64/128 or n_actions > 256 -> DT_ERR_LIMIT; null pointers, cache_interval < 1,
+ * feat_stride < F -> DT_ERR_INVALID_ARG.
+ */
+int dt_action_table(dt_params *table, int capacity, int *n_actions);
+int dt_policy_workspace_bytes(int batch, int F, int H, size_t *bytes);
+int dt_policy_step(void *stream, int batch, dt_dtype feat_t, const void *features, int64_t feat_stride, int F, int H,
+                   int n_actions, const float *W1, const float *b1, const float *W2, const float *b2, const float *W3,
+                   const float *b3, const dt_params *action_table, int cache_interval, int sample, uint64_t philox_seed,
+                   uint64_t philox_step, int32_t *cache_step, int32_t *cached_action, dt_params *params_out,
+                   int32_t *action_out, int32_t *queried_out, float *logits_out, void *ws, size_t ws_bytes);
+
+/*
  * Input update after verification (paper Appendix, "System Profiling and Overhead Analysis": the
  * input update brings the KV cache to the state of the next step -- accepted tokens kept, rejected
  * ones discarded, positions continued).  For every sequence b, layer l and both of K and V, the tree
@@ -239,7 +272,7 @@ int dt_commit(void *stream, int batch, int n_layers, dt_dtype t, int Hkv, int D,
  * kernel's own begin and end (not usable while the stream is being captured into a graph).
  * dt_profile_enable(0) switches it off.  dt_profile_read sums, for one kernel id
  * (0 draft row chunks, 1 row merge, 2 tree, 3 attention, 4 attention combine, 5 target row
- * chunks, 6 accept, 7 dt_topk_rows chunks, 8 commit), the elapsed milliseconds of the launches recorded
+ * chunks, 6 accept, 7 dt_topk_rows chunks, 8 commit, 9 policy layer 1, 10 policy head), the elapsed milliseconds of the launches recorded
  * since the last enable, waiting for them to finish.  Not thread-safe.
  */
 int dt_profile_enable(int max_launches);

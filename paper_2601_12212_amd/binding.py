@@ -51,6 +51,10 @@ def load_library():
         lib.dt_level_state_bytes.argtypes = [i32, C.POINTER(sz)]
         lib.dt_expand_level.argtypes = [vp, i32, i32, vp, vp, i32, i32, i64, i32, vp, i32, vp] + [vp] * 6 + [vp, sz]
         lib.dt_finish_tree.argtypes = [vp, i32, vp, i32, vp, i32, vp] + [vp] * 8
+        lib.dt_action_table.argtypes = [vp, i32, C.POINTER(i32)]
+        lib.dt_policy_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
+        lib.dt_policy_step.argtypes = [vp, i32, i32, vp, i64, i32, i32, i32] + [vp] * 7 + [i32, i32, u64, u64] + \
+                                      [vp] * 6 + [vp, sz]
         lib.dt_commit.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i32, vp, vp]
         lib.dt_profile_enable.argtypes = [i32]
         lib.dt_profile_enable.restype = i32
@@ -59,7 +63,8 @@ def load_library():
         lib.dt_profile_kernel_name.argtypes = [i32]
         lib.dt_profile_kernel_name.restype = C.c_char_p
         for fn in ("dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept", "dt_commit",
-                   "dt_level_state_bytes", "dt_expand_level", "dt_finish_tree"):
+                   "dt_level_state_bytes", "dt_expand_level", "dt_finish_tree", "dt_action_table",
+                   "dt_policy_workspace_bytes", "dt_policy_step"):
             getattr(lib, fn).restype = i32
         _lib = lib
     return _lib
@@ -159,6 +164,33 @@ def dt_finish_tree(params, V, root_token, TT_cap, state, n_nodes, tokens, parent
     _check("dt_finish_tree", load_library().dt_finish_tree(
         _stream(), batch, _ptr(params), V, _ptr(root_token), TT_cap, _ptr(state), _ptr(n_nodes), _ptr(tokens),
         _ptr(parents), _ptr(depth), _ptr(score), _ptr(logp), _ptr(src_row), _ptr(anc_mask)))
+
+
+def dt_action_table():
+    """-> list of (TT, d, k): the action table of the paper's appendix after its filter (host side)."""
+    lib = load_library()
+    n = C.c_int(0)
+    buf = (C.c_int32 * (3 * 256))()
+    _check("dt_action_table", lib.dt_action_table(buf, 256, C.byref(n)))
+    return [(buf[3 * i], buf[3 * i + 1], buf[3 * i + 2]) for i in range(n.value)]
+
+
+def dt_policy_workspace_bytes(batch, F, H):
+    out = C.c_size_t(0)
+    _check("dt_policy_workspace_bytes", load_library().dt_policy_workspace_bytes(batch, F, H, C.byref(out)))
+    return out.value
+
+
+def dt_policy_step(features, W1, b1, W2, b2, W3, b3, action_table, cache_interval, sample, philox_seed, philox_step,
+                   cache_step, cached_action, params_out, action_out, queried_out, logits_out, ws):
+    """features [batch, F]; W1 [F,H], W2 [H,H], W3 [H,A] float32 ([in][out]); action_table int32 [A,3] on the device."""
+    batch, F = features.shape
+    H, A = W3.shape
+    _check("dt_policy_step", load_library().dt_policy_step(
+        _stream(), batch, _dtype(features), _ptr(features), features.stride(0), F, H, A, _ptr(W1), _ptr(b1), _ptr(W2),
+        _ptr(b2), _ptr(W3), _ptr(b3), _ptr(action_table), cache_interval, int(sample), philox_seed, philox_step,
+        _ptr(cache_step), _ptr(cached_action), _ptr(params_out), _ptr(action_out), _ptr(queried_out), _ptr(logits_out),
+        _ptr(ws), ws.numel() * ws.element_size()))
 
 
 def dt_commit(dtype_of, Hkv, D, k_tree_ptrs, v_tree_ptrs, k_prefix_ptrs, v_prefix_ptrs, prefix_len, prefix_cap,

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdt.so")
-SOURCES = ["api.cpp", "profile.cpp", "rows.hip", "tree.hip", "attention.hip", "accept.hip", "commit.hip"]
+SOURCES = ["api.cpp", "profile.cpp", "rows.hip", "tree.hip", "attention.hip", "accept.hip", "commit.hip", "policy.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          # packed-FP32 code generation is switched off: some of its instruction forms have given wrong
          # results on this hardware now and then, without any error

@@ -326,6 +326,59 @@ int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, cons
     return DT_OK;
 }
 
+int dt_action_table(dt_params *table, int capacity, int *n_actions) {
+    // Appendix A, "Action Space in Implementation": the printed value sets, combinations with
+    // TT > k^(d-1) filtered out; enumeration order TT, then d, then k
+    static const int TTs[] = {32, 48, 64, 80, 96, 128}, ds[] = {3, 4, 5, 6, 7, 8}, ks[] = {8, 12, 16, 20, 32};
+    if (!n_actions || capacity < 0 || (capacity > 0 && !table)) return DT_ERR_INVALID_ARG;
+    int n = 0;
+    for (int TT : TTs)
+        for (int d : ds)
+            for (int k : ks) {
+                long long lim = 1;  // k^(d-1), saturated well above every TT
+                for (int i = 1; i < d && lim < (1 << 20); ++i) lim *= k;
+                if (TT > lim) continue;
+                if (n < capacity) { table[n].TT = TT; table[n].d = d; table[n].k = k; }
+                ++n;
+            }
+    *n_actions = n;
+    return DT_OK;
+}
+
+int dt_policy_workspace_bytes(int batch, int F, int H, size_t *bytes) {
+    if (!bytes || batch < 0 || F < 1 || H < 1) return DT_ERR_INVALID_ARG;
+    const size_t S = ((size_t)F + POLICY_KS - 1) / POLICY_KS;
+    *bytes = align_up(S * (size_t)batch * H * 4) + 256;
+    return DT_OK;
+}
+
+int dt_policy_step(void *stream, int batch, dt_dtype feat_t, const void *features, int64_t feat_stride, int F, int H,
+                   int n_actions, const float *W1, const float *b1, const float *W2, const float *b2, const float *W3,
+                   const float *b3, const dt_params *action_table, int cache_interval, int sample, uint64_t philox_seed,
+                   uint64_t philox_step, int32_t *cache_step, int32_t *cached_action, dt_params *params_out,
+                   int32_t *action_out, int32_t *queried_out, float *logits_out, void *ws, size_t ws_bytes) {
+    if (batch < 0 || bad_dtype(feat_t)) return DT_ERR_INVALID_ARG;
+    if (batch == 0) return DT_OK;
+    if (!features || !W1 || !b1 || !W2 || !b2 || !W3 || !b3 || !action_table || !cache_step || !cached_action ||
+        !params_out || feat_stride < F || F < 1 || cache_interval < 1 || (sample != 0 && sample != 1))
+        return DT_ERR_INVALID_ARG;
+    if ((H != 64 && H != 128) || n_actions < 1 || n_actions > 256) return DT_ERR_LIMIT;
+    size_t need = 0;
+    dt_policy_workspace_bytes(batch, F, H, &need);
+    if (!ws || (uintptr_t)ws % 256 || ws_bytes < need) return DT_ERR_WORKSPACE;
+    dt::PolicyArgs a = {};
+    a.batch = batch; a.feat_dtype = feat_t; a.F = F; a.H = H; a.A = n_actions; a.N = cache_interval; a.mode = sample;
+    a.feat = features; a.feat_stride = feat_stride;
+    a.W1 = W1; a.b1 = b1; a.W2 = W2; a.b2 = b2; a.W3 = W3; a.b3 = b3; a.table = action_table;
+    a.seed = philox_seed; a.step = philox_step; a.cache_step = cache_step; a.cached_action = cached_action;
+    a.params_out = params_out; a.action_out = action_out; a.queried_out = queried_out; a.logits_out = logits_out;
+    a.partial = (float *)ws; a.S = (F + POLICY_KS - 1) / POLICY_KS;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
+    hipError_t e = dt::policy_launch(a, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
 int dt_commit(void *stream, int batch, int n_layers, dt_dtype t, int Hkv, int D, const void *const *k_tree,
               const void *const *v_tree, void *const *k_prefix, void *const *v_prefix, const int32_t *prefix_len,
               const int32_t *prefix_cap, int64_t kv_stride_tok, int64_t kv_stride_head, const int32_t *n_nodes,

@@ -96,6 +96,23 @@ __device__ __forceinline__ u64 readlane_u64(u64 v, int lane) {
     return ((u64)hi << 32) | lo;
 }
 
+// Philox4x32-10 (Salmon et al., SC'11): first output word for counter (c0,c1,c2,c3), key (k0,k1).
+__device__ __forceinline__ u32 philox4x32_10_word0(u32 c0, u32 c1, u32 c2, u32 c3, u32 k0, u32 k1) {
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const u32 hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const u32 hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        const u32 n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return c0;
+}
+__device__ __forceinline__ float philox_uniform(u64 seed, u64 step, u32 seq, u32 node) {
+    u32 x = philox4x32_10_word0(node, seq, (u32)step, (u32)(step >> 32), (u32)seed, (u32)(seed >> 32));
+    return (float)(x >> 8) * (1.0f / 16777216.0f);
+}
+
 // (max, sum of exp relative to max) pairs: the associative combine of log-sum-exp partials.
 __device__ __forceinline__ void lse_combine(float &m, float &s, float m2, float s2) {
     float M = fmaxf(m, m2);

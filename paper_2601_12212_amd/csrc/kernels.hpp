@@ -13,7 +13,7 @@ namespace dt {
 // of pre-created HIP events attached to its dispatch (hipExtLaunchKernelGGL), which record the
 // kernel's own begin and end; dt_profile_read sums the elapsed times per kernel id.
 enum KernelId { KID_ROWS_DRAFT = 0, KID_ROWS_MERGE, KID_TREE, KID_ATTN, KID_ATTN_COMBINE, KID_ROWS_TARGET,
-                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COMMIT, KID_COUNT };
+                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COMMIT, KID_POLICY_L1, KID_POLICY_HEAD, KID_COUNT };
 bool prof_next(int kid, hipEvent_t *start, hipEvent_t *stop);  // false when timing is off
 
 template <typename F, typename... Args>
@@ -135,5 +135,23 @@ struct CommitArgs {
     int32_t *new_prefix_len, *next_root_token;
 };
 hipError_t commit_launch(const CommitArgs &a, hipStream_t st);
+
+// ------------------------------------------------------------ action selection (policy.hip)
+#define POLICY_KS 64  // inputs of layer 1 per workgroup
+struct PolicyArgs {
+    int batch, feat_dtype, F, H, A, N, mode;
+    const void *feat;
+    int64_t feat_stride;
+    const float *W1, *b1, *W2, *b2, *W3, *b3;  // weights [in][out]
+    const dt_params *table;                    // [A]
+    unsigned long long seed, step;
+    int32_t *cache_step, *cached_action;       // [batch] in/out
+    dt_params *params_out;
+    int32_t *action_out, *queried_out;         // may be null
+    float *logits_out;                         // [batch, A], may be null
+    float *partial;                            // [S, batch, H]
+    int S;
+};
+hipError_t policy_launch(const PolicyArgs &a, hipStream_t st);
 
 }  // namespace dt

@@ -107,6 +107,15 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_finish_tree(*fin(batch=0)) == 0
     nbytes = C.c_size_t(0)
     assert lib.dt_level_state_bytes(3, C.byref(nbytes)) == 0 and nbytes.value >= 3 * 225 * (32 * 8 + 4)
+    # policy: hidden size / action count over the limits, bad interval, small workspace
+    pol = lambda **kw: [None, kw.get("batch", 1), 1, one, 12288, 12288, kw.get("H", 128), kw.get("A", 177)] + [one] * 7 + \
+                       [kw.get("N", 30), kw.get("sample", 0), 0, 0, one, one, one, None, None, None, ws, kw.get("wsb", 1 << 24)]
+    assert lib.dt_policy_step(*pol(H=100)) == -2
+    assert lib.dt_policy_step(*pol(A=300)) == -2
+    assert lib.dt_policy_step(*pol(N=0)) == -1
+    assert lib.dt_policy_step(*pol(sample=2)) == -1
+    assert lib.dt_policy_step(*pol(wsb=64)) == -3
+    assert lib.dt_policy_step(*pol(batch=0)) == 0
     # commit: null pointers, new length aliasing the old one, TT_cap over the limit, nothing to do
     other = C.c_void_p(512)
     com = lambda **kw: [None, kw.get("batch", 1), kw.get("layers", 2), 1, 8, 128, one, one, kw.get("kp", one), one, one,
@@ -116,3 +125,10 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_commit(*com(TT_cap=129)) == -2
     assert lib.dt_commit(*com(batch=0)) == 0
     assert lib.dt_commit(*com(layers=0)) == 0
+
+
+def test_action_table_matches_the_oracle_and_the_golden_sets():
+    from oracle import ref
+    table = dt.dt_action_table()
+    assert table == [tuple(int(v) for v in r) for r in ref.action_table()]
+    assert len(table) == 177 and dt.dt_policy_workspace_bytes(4, 12288, 128) >= 192 * 4 * 128 * 4
