@@ -478,11 +478,45 @@ static double row_lse_t(const void *row, int dtype, int V, double T)
 }
 
 /*
+ * Inverse-CDF sample of softmax(row / T) at the uniform u, the CDF accumulated in double: the first
+ * id with cdf > u (if rounding leaves none: the last id that carries mass).  *margin is lowered to
+ * the distance of u to the edges of the chosen bin.
+ */
+static int row_sample_t(const void *row, int dtype, int V, double T, double u, double *margin)
+{
+    double l = row_lse_t(row, dtype, V, T);
+    double cdf = 0.0, prev = 0.0;
+    int last_pos = 0;
+    for (int v = 0; v < V; ++v) {
+        double p = exp((double)elem(row, dtype, v) / T - l);
+        if (p > 0.0) last_pos = v;
+        prev = cdf;
+        cdf += p;
+        if (cdf > u) {
+            if (cdf - u < *margin) *margin = cdf - u;
+            if (v > 0 && u - prev < *margin) *margin = u - prev;
+            return v;
+        }
+    }
+    return last_pos;
+}
+
+/*
  * Verify one sequence's tree against the target logits (row i = target's next-token
  * logits after node i) and walk the longest accepted path.
  *   mode 0 (greedy): node i>0 is accepted iff tokens[i] == argmax of its parent's row.
  *   mode 1 (stochastic): accepted iff u_i < min(1, P_T(tokens[i]) / P_d(tokens[i])),
  *     P_T = softmax(target[parent]/T), P_d = exp(logp[i]), u_i = ref_uniform(.., node i).
+ *   mode 2 (target-sampled, distribution preserving): every node i draws the target's own next
+ *     token y_i ~ softmax(target[i]/T) by inverse CDF at u = ref_uniform(.., node 0x80000000 + depth[i])
+ *     (one uniform per depth: at most one node per depth lies on the walk); node i>0 is accepted iff
+ *     tokens[i] == y_parent, and the bonus token is y_best.  With the children of a node being a fixed
+ *     set (the draft's top-k, not samples), this is what sibling-by-sibling rejection sampling with
+ *     residual renormalisation reduces to: child x_1 is accepted with probability p(x_1), after its
+ *     rejection x_2 with p(x_2)/(1-p(x_1)), ..., i.e. child x_j overall with probability p(x_j), and
+ *     otherwise the token comes from p restricted to the non-children -- exactly one draw from p.  The
+ *     emitted tokens are therefore the target's own autoregressive samples for the same uniforms.
+ *     node_argmax then receives y_i instead of the arg max.
  * ok[i] = accepted[i] and ok[parent]; best = deepest ok node, ties -> lowest index.
  * out_tokens = draft tokens along root->best (root excluded) followed by the bonus
  * token: greedy arg max of row best, or the inverse-CDF sample of softmax(row best/T)
@@ -501,8 +535,9 @@ int ref_accept(int mode, float temperature, const void *target, int dtype, int V
     if (!target || !tokens || !parents || !depth || !accept_len || !best_node || !path_nodes || !out_tokens)
         return REF_ERR_ARG;
     if (N < 1 || N > REF_TT_MAX || V < 1 || row_stride < V || d_cap < 1 || d_cap > REF_D_MAX) return REF_ERR_ARG;
-    if (mode != 0 && mode != 1) return REF_ERR_ARG;
-    if (mode == 1 && (!logp || !(temperature > 0.0f))) return REF_ERR_ARG;
+    if (mode != 0 && mode != 1 && mode != 2) return REF_ERR_ARG;
+    if (mode == 1 && !logp) return REF_ERR_ARG;
+    if (mode != 0 && !(temperature > 0.0f)) return REF_ERR_ARG;
     const int esz = dtype == REF_F32 ? 4 : 2;
     int amax[REF_TT_MAX];
     unsigned char acc[REF_TT_MAX], ok[REF_TT_MAX];
@@ -514,6 +549,14 @@ int ref_accept(int mode, float temperature, const void *target, int dtype, int V
 
     acc[0] = 1;
     if (mode == 0) {
+        for (int i = 1; i < N; ++i) acc[i] = tokens[i] == amax[parents[i]];
+    } else if (mode == 2) {
+        double T = (double)temperature;
+        for (int i = 0; i < N; ++i) {
+            if (depth[i] < 0 || depth[i] > REF_D_MAX) return REF_ERR_ARG;
+            double u = (double)ref_uniform(seed, step, seq, 0x80000000u + (uint32_t)depth[i]);
+            amax[i] = row_sample_t((const char *)target + (int64_t)i * row_stride * esz, dtype, V, T, u, &margin);
+        }
         for (int i = 1; i < N; ++i) acc[i] = tokens[i] == amax[parents[i]];
     } else {
         double T = (double)temperature;
@@ -550,7 +593,7 @@ int ref_accept(int mode, float temperature, const void *target, int dtype, int V
     }
 
     int bonus;
-    if (mode == 0) {
+    if (mode == 0 || mode == 2) {
         bonus = amax[best];
     } else {
         double T = (double)temperature;

@@ -18,7 +18,7 @@ _LIB = os.path.join(_HERE, "libdt_oracle.so")
 
 TT_MAX, D_MAX, K_MAX = 128, 8, 32
 F32, BF16 = 0, 1
-GREEDY, STOCHASTIC = 0, 1
+GREEDY, STOCHASTIC, SAMPLED = 0, 1, 2
 
 
 def build(force=False):

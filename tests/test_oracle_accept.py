@@ -232,3 +232,95 @@ def test_argmax_ties_go_to_the_lowest_token_id():
     bits = dt_synth.f32_to_bf16_bits(target)
     b = ref.accept(ref.GREEDY, bits, tokens, parents, depth)
     assert b["best_node"] == 1 and np.array_equal(a["out_tokens"], b["out_tokens"])
+
+
+# ------------------------------------------------- target-sampled (distribution-preserving) mode
+
+def _ar_sample(tfn, ctx, n, T, seed, step, seq):
+    """The target's own autoregressive sampling with the uniforms of one speculative step: position j of the
+    step uses the uniform of depth j.  numpy cumsum / searchsorted, no oracle code."""
+    out, s = [], ctx
+    for j in range(n):
+        x = tfn(s).astype(np.float64) / T
+        p = np.exp(x - x.max()); p /= p.sum()
+        u = ref.uniform(seed, step, seq, 0x80000000 + j)
+        tok = int(np.searchsorted(np.cumsum(p), u, side="right"))
+        out.append(min(tok, len(p) - 1))
+        s += (out[-1],)
+    return out
+
+
+def test_sampled_verification_emits_the_targets_own_samples_token_for_token():
+    """One speculative step in mode 2 returns exactly the leading tokens of the autoregressive sample drawn
+    with the same uniforms: as many as form a path of the tree, plus one (the bonus)."""
+    V = 6
+    rng = np.random.default_rng(21)
+    lens = []
+    for trial in range(150):
+        TT, d, k = int(rng.integers(1, 30)), int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        T = float(rng.choice([0.7, 1.0, 1.6]))
+        dfn = lambda s: toy_logits(40 + trial % 7, s, V)
+        tfn = lambda s: toy_logits(40 + trial % 7, s, V) + toy_logits(90, s, V, sigma=0.7)   # close to the draft
+        rows = rows_from_fn(ref.build_tree, dfn, V, d, k)
+        t = ref.build_tree(rows, TT, d, k, 0)
+        strs = node_strings(t)
+        target = np.stack([tfn(st) for st in strs])
+        a = ref.accept(ref.SAMPLED, target, t["tokens"], t["parents"], t["depth"], temperature=T, seed=5, step=trial, seq=3)
+        if a["min_margin"] < 1e-9:
+            continue
+        ar = _ar_sample(tfn, (), d + 1, T, 5, trial, 3)
+        n = 0
+        while n < d and tuple(ar[: n + 1]) in set(strs):
+            n += 1
+        assert a["accept_len"] == n, trial
+        assert a["out_tokens"][: n + 1].tolist() == ar[: n + 1], trial
+        assert strs[a["best_node"]] == tuple(ar[:n])
+        lens.append(n)
+    assert max(lens) >= 2 and min(lens) == 0
+
+
+def test_sampled_verification_preserves_the_target_distribution():
+    """Whatever the tree, the first emitted token is distributed as softmax(target(root)/T), and the second,
+    given the first, as the target's next-token distribution after it."""
+    V, T = 5, 1.3
+    dfn = lambda s: toy_logits(3, s, V)
+    tfn = lambda s: toy_logits(3, s, V) * 0.5 + toy_logits(4, s, V, sigma=1.0)
+    rows = rows_from_fn(ref.build_tree, dfn, V, 3, 2)
+    t = ref.build_tree(rows, 7, 3, 2, 0)
+    strs = node_strings(t)
+    target = np.stack([tfn(st) for st in strs])
+    steps = 20000
+    first = np.zeros(V)
+    pair = np.zeros((V, V))
+    n_two = 0
+    for step in range(steps):
+        a = ref.accept(ref.SAMPLED, target, t["tokens"], t["parents"], t["depth"], temperature=T, seed=8, step=step)
+        out = a["out_tokens"]
+        first[out[0]] += 1
+        if a["accept_len"] >= 1:
+            pair[out[0], out[1]] += 1
+            n_two += 1
+    sm = lambda x: np.exp(x / T - np.max(x / T)) / np.exp(x / T - np.max(x / T)).sum()
+    p1 = sm(tfn(()).astype(np.float64))
+    assert np.abs(first / steps - p1).max() < 4 * np.sqrt(0.25 / steps)
+    assert n_two > 2000
+    for tok in range(V):
+        if pair[tok].sum() > 1500:                       # first tokens that are in the tree and drawn often
+            p2 = sm(tfn((tok,)).astype(np.float64))
+            assert np.abs(pair[tok] / pair[tok].sum() - p2).max() < 4.5 * np.sqrt(0.25 / pair[tok].sum())
+
+
+def test_sampled_verification_with_a_one_hot_target_is_greedy():
+    V = 7
+    rng = np.random.default_rng(4)
+    dfn = lambda s: toy_logits(6, s, V)
+    rows = rows_from_fn(ref.build_tree, dfn, V, 3, 3)
+    t = ref.build_tree(rows, 12, 3, 3, 0)
+    target = np.full((t["n_nodes"], V), -30.0, np.float32)
+    for i in range(t["n_nodes"]):
+        target[i, rng.integers(0, V)] = 30.0
+    g = ref.accept(ref.GREEDY, target, t["tokens"], t["parents"], t["depth"])
+    for step in range(20):
+        s = ref.accept(ref.SAMPLED, target, t["tokens"], t["parents"], t["depth"], temperature=1.0, seed=1, step=step)
+        assert s["accept_len"] == g["accept_len"] and np.array_equal(s["out_tokens"], g["out_tokens"])
+        assert np.array_equal(s["node_argmax"], g["node_argmax"])
