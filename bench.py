@@ -51,6 +51,10 @@ def main():
     ap.add_argument("--eager", action="store_true", help="plain stream launches instead of HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-steps", type=int, default=400)
+    ap.add_argument("--attention-layers", type=int, default=32,
+                    help="layers of the separately timed all-layer attention graph (0: skip it)")
+    ap.add_argument("--sampled-verify", type=int, default=1,
+                    help="also time dt_accept in its distribution-preserving mode (0: skip)")
     ap.add_argument("--policy-features", type=int, default=3 * 4096,
                     help="state size of the separately timed policy step (0: skip it)")
     ap.add_argument("--streaming-build", type=int, default=1,
@@ -245,6 +249,62 @@ def main():
         log("  kernel %-20s avg %8.2f us  (%d layers, %d accepted-path rows, %.2f MB moved; outside the timed step)"
             % ("commit", commit["avg_us"], nl, rows, cbytes / 1e6))
 
+    # ---- all layers' attention of one verification pass as one HIP graph (outside the timed step; the
+    #      layers share this step's Q/K/V buffers, so it measures launch chaining, not cache behaviour
+    #      across distinct layer data) ---------------------------------------------------------------------
+    layers_graph = None
+    if args.attention_layers > 0 and not args.eager:
+        try:
+            nl_a = args.attention_layers
+            side = torch.cuda.Stream()
+            with torch.cuda.stream(side):
+                steps[0].tree_attention()
+                torch.cuda.synchronize()
+                lg = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(lg, stream=side):
+                    for _ in range(nl_a):
+                        steps[0].tree_attention()
+            for _ in range(3):
+                lg.replay()
+            torch.cuda.synchronize()
+            a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a0.record()
+            for _ in range(20):
+                lg.replay()
+            a1.record()
+            torch.cuda.synchronize()
+            per_layer = a0.elapsed_time(a1) * 1e3 / (20 * nl_a)
+            layers_graph = {"layers": nl_a, "us_per_layer": round(per_layer, 3), "in_timed_step": False}
+            log("  attention of %d layers in one graph: %.2f us per layer; outside the timed step" % (nl_a, per_layer))
+        except Exception as ex:                  # noqa: BLE001
+            log("attention layer graph failed: %s" % ex)
+
+    # ---- distribution-preserving verification (every node draws the target's own token), outside the
+    #      timed step: the same target rows, mode DT_ACCEPT_SAMPLED ---------------------------------------
+    sampled = None
+    if args.sampled_verify:
+        st0 = steps[0]
+        n_v = 200
+        call = lambda i: dt.dt_accept(dt.DT_ACCEPT_SAMPLED, 1.0, st0.target_logits, st0.n_nodes, st0.tokens,
+                                      st0.parents, st0.depth, st0.logp, st0.anc_mask, cfg.philox_seed, i,
+                                      st0.accept_len, st0.best_node, st0.path_nodes, st0.out_tokens,
+                                      st0.node_argmax, st0.ws)
+        for i in range(5):
+            call(i)
+        dt.dt_profile_enable(3 * n_v + 8)
+        for i in range(n_v):
+            call(i)
+        torch.cuda.synchronize()
+        t_rows, t_samp, t_acc = (dt.dt_profile_read(kid) for kid in (5, 11, 6))
+        dt.dt_profile_enable(0)
+        us = lambda t: round(t[1] * 1e3 / max(t[2], 1), 3)
+        sampled = {"rows_target_chunk_us": us(t_rows), "node_sample_us": us(t_samp), "accept_us": us(t_acc),
+                   "in_timed_step": False}
+        log("  sampled verification: target rows %.2f us, per-node draws %.2f us, accept %.2f us; outside the timed step"
+            % (sampled["rows_target_chunk_us"], sampled["node_sample_us"], sampled["accept_us"]))
+        steps[0].accept(0)          # leave the greedy result behind for what follows
+        torch.cuda.synchronize()
+
     # ---- action selection (policy MLP + action cache), outside the timed step: evaluated at every call
     #      here (interval 1); with the paper's interval of 30 it runs once per 30 steps -------------------
     policy = None
@@ -374,6 +434,8 @@ def main():
         "input_update": commit,
         "streaming_build": streaming,
         "policy": policy,
+        "sampled_verification": sampled,
+        "attention_layers_graph": layers_graph,
         "roofline": roofline,
         "roofline_all_streams": roofline_all,
         "cpu_baseline": cpu,

@@ -15,7 +15,7 @@ from typing import List, Tuple
 
 import numpy as np
 
-GREEDY, STOCHASTIC = 0, 1
+GREEDY, STOCHASTIC, SAMPLED = 0, 1, 2
 
 
 def f32_to_bf16_bits(x):

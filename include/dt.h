@@ -48,7 +48,7 @@ typedef struct {
 } dt_params;
 
 typedef enum { DT_F32 = 0, DT_BF16 = 1 } dt_dtype;
-typedef enum { DT_ACCEPT_GREEDY = 0, DT_ACCEPT_STOCHASTIC = 1 } dt_accept_mode;
+typedef enum { DT_ACCEPT_GREEDY = 0, DT_ACCEPT_STOCHASTIC = 1, DT_ACCEPT_SAMPLED = 2 } dt_accept_mode;
 
 typedef enum {
     DT_OK = 0,
@@ -151,6 +151,14 @@ int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int 
  *                parent / temperature), P_d = exp(logp[i]); u_i is the first word of
  *                Philox4x32-10(counter = (i, b, step lo, step hi), key = (seed lo, seed hi)),
  *                mapped to [0,1) as (word >> 8) * 2^-24.
+ *   sampled    : distribution-preserving verification for trees whose children are a fixed set (the
+ *                draft's top-k): every node i draws the target's own next token y_i from
+ *                softmax(row i / temperature) by inverse CDF at the Philox uniform with node index
+ *                0x80000000 + depth[i]; node i > 0 is accepted iff tokens[i] == y of its parent, and
+ *                the bonus token is y_best.  (Sibling-by-sibling rejection with renormalised residuals
+ *                accepts child x with probability p(x) overall and otherwise draws from p outside the
+ *                children: one draw from p.)  The emitted tokens are the target's autoregressive
+ *                samples for the same uniforms.  node_argmax then holds y_i.
  * The walk ends at `best`, the deepest node all of whose ancestors (and itself) are accepted,
  * ties -> lowest node index.  Outputs per sequence:
  *   accept_len [batch]               depth of best = number of accepted draft tokens
@@ -160,7 +168,7 @@ int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int 
  *                                    row best; stochastic: inverse-CDF sample of softmax(row best /
  *                                    temperature) at the uniform with node index 0xFFFFFFFF), then -1
  *   node_argmax[batch, TT_cap]       argmax of every node row (may be NULL)
- * Errors: stochastic with temperature <= 0 or logp NULL -> DT_ERR_INVALID_ARG.
+ * Errors: stochastic / sampled with temperature <= 0, stochastic with logp NULL -> DT_ERR_INVALID_ARG.
  */
 int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, const void *target_logits,
               dt_dtype t, int V, int64_t row_stride, const int32_t *n_nodes, const int32_t *tokens,
@@ -272,7 +280,7 @@ int dt_commit(void *stream, int batch, int n_layers, dt_dtype t, int Hkv, int D,
  * kernel's own begin and end (not usable while the stream is being captured into a graph).
  * dt_profile_enable(0) switches it off.  dt_profile_read sums, for one kernel id
  * (0 draft row chunks, 1 row merge, 2 tree, 3 attention, 4 attention combine, 5 target row
- * chunks, 6 accept, 7 dt_topk_rows chunks, 8 commit, 9 policy layer 1, 10 policy head), the elapsed milliseconds of the launches recorded
+ * chunks, 6 accept, 7 dt_topk_rows chunks, 8 commit, 9 policy layer 1, 10 policy head, 11 per-node target samples), the elapsed milliseconds of the launches recorded
  * since the last enable, waiting for them to finish.  Not thread-safe.
  */
 int dt_profile_enable(int max_launches);

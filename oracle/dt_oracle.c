@@ -524,13 +524,16 @@ static int row_sample_t(const void *row, int dtype, int V, double T, double u, d
  * unused slots are -1.  node_argmax (may be NULL) gets the arg max of every row.
  * accepted (may be NULL) gets the per-node accept flags.
  * min_margin (may be NULL): stochastic only, the smallest |u_i - alpha_i| over nodes
- * with alpha_i < 1 and the distance of the bonus uniform to its CDF bin edges.
+ * with alpha_i < 1 and the distance of the bonus uniform to its CDF bin edges; mode 2: the
+ * smallest distance of a uniform to its CDF bin edges over the nodes whose draw decides the
+ * output (the nodes with all ancestors accepted).  node_margin (may be NULL; mode 2 only):
+ * that distance for every node.
  */
 int ref_accept(int mode, float temperature, const void *target, int dtype, int V, int64_t row_stride,
                int N, const int32_t *tokens, const int32_t *parents, const int32_t *depth,
                const float *logp, int d_cap, uint64_t seed, uint64_t step, uint32_t seq,
                int32_t *accept_len, int32_t *best_node, int32_t *path_nodes, int32_t *out_tokens,
-               int32_t *node_argmax, uint8_t *accepted, float *min_margin)
+               int32_t *node_argmax, uint8_t *accepted, float *min_margin, float *node_margin)
 {
     if (!target || !tokens || !parents || !depth || !accept_len || !best_node || !path_nodes || !out_tokens)
         return REF_ERR_ARG;
@@ -542,6 +545,7 @@ int ref_accept(int mode, float temperature, const void *target, int dtype, int V
     int amax[REF_TT_MAX];
     unsigned char acc[REF_TT_MAX], ok[REF_TT_MAX];
     double margin = INFINITY;
+    double nmargin[REF_TT_MAX];
 
 #pragma omp parallel for schedule(dynamic)
     for (int i = 0; i < N; ++i)
@@ -555,7 +559,8 @@ int ref_accept(int mode, float temperature, const void *target, int dtype, int V
         for (int i = 0; i < N; ++i) {
             if (depth[i] < 0 || depth[i] > REF_D_MAX) return REF_ERR_ARG;
             double u = (double)ref_uniform(seed, step, seq, 0x80000000u + (uint32_t)depth[i]);
-            amax[i] = row_sample_t((const char *)target + (int64_t)i * row_stride * esz, dtype, V, T, u, &margin);
+            nmargin[i] = INFINITY;
+            amax[i] = row_sample_t((const char *)target + (int64_t)i * row_stride * esz, dtype, V, T, u, &nmargin[i]);
         }
         for (int i = 1; i < N; ++i) acc[i] = tokens[i] == amax[parents[i]];
     } else {
@@ -584,6 +589,11 @@ int ref_accept(int mode, float temperature, const void *target, int dtype, int V
         ok[i] = acc[i] && ok[parents[i]];
         if (ok[i] && depth[i] > depth[best]) best = i; /* strict: ties keep the lowest index */
     }
+    if (mode == 2)
+        for (int i = 0; i < N; ++i) {
+            if (ok[i] && nmargin[i] < margin) margin = nmargin[i];
+            if (node_margin) node_margin[i] = (float)nmargin[i];
+        }
     int len = depth[best];
     if (len > d_cap) return REF_ERR_ARG;
     for (int s = 0; s <= d_cap; ++s) { path_nodes[s] = -1; out_tokens[s] = -1; }

@@ -152,13 +152,14 @@ def accept(mode, target, tokens, parents, depth, logp=None, temperature=1.0, d_c
     amax = np.empty(N, np.int32)
     accepted = np.empty(N, np.uint8)
     margin = C.c_float(0)
+    nmargin = np.full(N, np.inf, np.float32)
     _check(lib().ref_accept(mode, C.c_float(temperature), _p(target), _dt(target), V, C.c_int64(V), N,
                             _p(tokens), _p(parents), _p(depth), _p(logp), d_cap,
                             C.c_uint64(seed), C.c_uint64(step), C.c_uint32(seq),
                             C.byref(alen), C.byref(best), _p(path), _p(out_tok), _p(amax), _p(accepted),
-                            C.byref(margin)), "ref_accept")
+                            C.byref(margin), _p(nmargin)), "ref_accept")
     return dict(accept_len=alen.value, best_node=best.value, path_nodes=path, out_tokens=out_tok,
-                node_argmax=amax, accepted=accepted.astype(bool), min_margin=margin.value)
+                node_argmax=amax, accepted=accepted.astype(bool), min_margin=margin.value, node_margin=nmargin)
 
 
 def commit_rows(cache, L, tree, path_nodes, accept_len, head_major=False):

@@ -7,7 +7,7 @@ _LIB_PATH = os.path.join(_HERE, "libdt.so")
 
 DT_TT_MAX, DT_D_MAX, DT_K_MAX, DT_MASK_WORDS = 128, 8, 32, 2
 DT_F32, DT_BF16 = 0, 1
-DT_ACCEPT_GREEDY, DT_ACCEPT_STOCHASTIC = 0, 1
+DT_ACCEPT_GREEDY, DT_ACCEPT_STOCHASTIC, DT_ACCEPT_SAMPLED = 0, 1, 2
 
 _lib = None
 

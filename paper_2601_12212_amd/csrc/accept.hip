@@ -29,11 +29,119 @@ __device__ __forceinline__ void load_logits8(const void *row, int dtype, int id,
     }
 }
 
+// Inverse-CDF sample of softmax(row g / T) at the uniform u, by the whole workgroup (256 threads; contains
+// barriers).  The row kernel left (max, sum exp((x - max)/T)) of every chunk of the row: their masses
+// relative to the row maximum Mrow, accumulated in double, locate the chunk that holds the crossing; only
+// that chunk is read again (thread t owns `epl` consecutive ids), element masses in fp32, running sums in
+// double.  The comparison is "cumulative mass > u * total", the un-normalised form of the cdf > u test;
+// it differs from an all-double evaluation by ~1e-6 in probability.  The result is left in *s_out.
+__device__ __forceinline__ void sample_row_block(const AcceptArgs &a, int64_t g, float Mrow, float u, float inv_t,
+                                                 double *s_wtot, int *s_out) {
+    const int tid = threadIdx.x, lane = lane_id(), w = tid >> 6, S = a.S;
+    const void *row = (const char *)a.target + g * a.row_stride * (a.dtype == DT_BF16 ? 2 : 4);
+    const float cexp = 1.4426950408889634f * inv_t;
+    // chunk c in lane c (S <= 64), every wave for itself
+    double mass = 0.0;
+    if (lane < S) {
+        const float2 p = a.part_ms[g * S + lane];
+        if (p.y > 0.f) mass = (double)p.y * (double)__builtin_amdgcn_exp2f((p.x - Mrow) * cexp);
+    }
+    double cum = mass;  // inclusive scan over the chunks
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double t = __shfl_up(cum, off, 64);
+        if (lane >= off) cum += t;
+    }
+    const double Z = __shfl(cum, 63, 64);
+    const double target_mass = (double)u * Z;
+    // first chunk whose cumulative mass passes the target; if rounding leaves none, the last with mass
+    const u64 passed = __ballot(cum > target_mass), massy = __ballot(mass > 0.0);
+    const int cstar = passed ? (int)__builtin_ctzll(passed) : massy ? 63 - (int)__builtin_clzll(massy) : 0;
+    const double before = __shfl(cum - mass, cstar, 64);
+    const int epl = a.chunk_elems / 256;
+    const int lo = cstar * a.chunk_elems, hi = min(a.V, lo + a.chunk_elems);
+    const int id0 = lo + tid * epl;
+    const bool vec_ok = ((uintptr_t)row & 15) == 0;  // id0 is a multiple of 8
+    double mine = 0.0;
+    for (int e0 = 0; e0 < epl; e0 += 8) {
+        float x[8];
+        load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mine += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
+    }
+    double incl = mine;  // inclusive scan over the lanes of the wave
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double t = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += t;
+    }
+    __syncthreads();  // s_wtot / *s_out may still be read from an earlier use
+    if (lane == 63) s_wtot[w] = incl;
+    if (tid == 0) *s_out = -1;
+    __syncthreads();
+    double run = before;
+    for (int q = 0; q < w; ++q) run += s_wtot[q];
+    const bool cross = run + incl > target_mass;
+    const u64 m = __ballot(cross);
+    // the first crossing thread of the first crossing wave
+    bool earlier = false;
+    {
+        double r2 = before;
+        for (int q = 0; q < w; ++q) {
+            r2 += s_wtot[q];
+            earlier = earlier || r2 > target_mass;
+        }
+    }
+    if (!earlier && m && lane == (int)__builtin_ctzll(m)) {
+        double cm = run + incl - mine;
+        int id = min(id0 + epl, hi) - 1;
+        bool done = false;
+        for (int e0 = 0; e0 < epl && !done; e0 += 8) {
+            float x[8];
+            load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                cm += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
+                if (!done && cm > target_mass) { id = id0 + e0 + e; done = true; }
+            }
+        }
+        *s_out = id;
+    }
+    __syncthreads();
+    if (tid == 0 && *s_out < 0) {
+        // the chunk's re-computed mass falls just short of the crossing (rounding), or the row
+        // carries no mass at all: last token of the chunk that carries mass, else token 0
+        int id = hi - 1;
+        while (id > lo && !(__builtin_amdgcn_exp2f((load_logit(row, a.dtype, id) - Mrow) * cexp) > 0.f)) --id;
+        *s_out = Z > 0.0 ? id : 0;
+    }
+    __syncthreads();
+}
+
+// Target-sampled verification: node i of sequence b draws the target's own next token from
+// softmax(row i / T) at the uniform of its depth.  One workgroup per (sequence, node).
+__global__ __launch_bounds__(256) void node_sample_kernel(AcceptArgs a) {
+    const int b = blockIdx.x / a.TT_cap, i = blockIdx.x % a.TT_cap, lane = lane_id();
+    const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
+    if (i >= N) return;
+    const int64_t g = (int64_t)b * a.TT_cap + i;
+    __shared__ double s_wtot[4];
+    __shared__ int s_out;
+    // the row maximum: the largest of the chunks' best keys
+    u64 key = lane < a.S ? a.part_keys[g * a.S + lane] : 0ull;
+    key = wave_max_u64(key);
+    const int dep = min(max(a.depth[g], 0), DT_D_MAX);
+    const float u = philox_uniform(a.seed, a.step, (u32)b, 0x80000000u + (u32)dep);
+    sample_row_block(a, g, key_val(key), u, 1.0f / a.temperature, s_wtot, &s_out);
+    if (threadIdx.x == 0) a.samples[g] = s_out;
+}
+
 __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     const int b = blockIdx.x, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
     const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
     const int64_t o = (int64_t)b * a.TT_cap;
     const bool stochastic = a.mode == DT_ACCEPT_STOCHASTIC;
+    const bool sampled = a.mode == DT_ACCEPT_SAMPLED;  // node_sample_kernel has drawn every node's token
     const float inv_t = stochastic ? 1.0f / a.temperature : 1.0f;
     const int S = a.S;
 
@@ -91,10 +199,11 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
                 }
             }
             if (part == 0 && i < N) {
-                s_amax[i] = (int)key_idx(best);
+                const int choice = sampled ? a.samples[o + i] : (int)key_idx(best);
+                s_amax[i] = choice;
                 s_rowmax[i] = key_val(best);
                 s_lse[i] = stochastic ? M * inv_t + __logf(Ssum) : 0.f;
-                if (a.node_argmax) a.node_argmax[o + i] = (int)key_idx(best);
+                if (a.node_argmax) a.node_argmax[o + i] = choice;
             }
         }
     }
@@ -160,90 +269,9 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
     if (!stochastic) {
         if (tid == 0) s_bonus = s_amax[best];
     } else {
-        // Inverse CDF of softmax(row/T) of node `best` at the bonus uniform.  The row kernel left
-        // (max, sum exp((x - max)/T)) of every chunk of the row: their masses relative to the row
-        // maximum, accumulated in double, locate the chunk that holds the crossing; only that chunk
-        // is read again (thread t owns `epl` consecutive ids), element masses in fp32, running sums
-        // in double.  The comparison is "cumulative mass > u * total", the un-normalised form of
-        // the cdf > u test; it differs from an all-double evaluation by ~1e-6 in probability.
-        const void *row = (const char *)a.target + (o + best) * a.row_stride * (a.dtype == DT_BF16 ? 2 : 4);
-        const float Mrow = s_rowmax[best];
-        const float cexp = 1.4426950408889634f * inv_t;
-        const int64_t g = o + best;
-        // chunk c in lane c (S <= 64), every wave for itself
-        double mass = 0.0;
-        if (lane < S) {
-            const float2 p = a.part_ms[g * S + lane];
-            if (p.y > 0.f) mass = (double)p.y * (double)__builtin_amdgcn_exp2f((p.x - Mrow) * cexp);
-        }
-        double cum = mass;  // inclusive scan over the chunks
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const double t = __shfl_up(cum, off, 64);
-            if (lane >= off) cum += t;
-        }
-        const double Z = __shfl(cum, 63, 64);
-        const double target_mass = (double)philox_uniform(a.seed, a.step, (u32)b, 0xFFFFFFFFu) * Z;
-        // first chunk whose cumulative mass passes the target; if rounding leaves none, the last with mass
-        const u64 passed = __ballot(cum > target_mass), massy = __ballot(mass > 0.0);
-        const int cstar = passed ? (int)__builtin_ctzll(passed) : massy ? 63 - (int)__builtin_clzll(massy) : 0;
-        const double before = __shfl(cum - mass, cstar, 64);
-        const int epl = a.chunk_elems / 256;
-        const int lo = cstar * a.chunk_elems, hi = min(a.V, lo + a.chunk_elems);
-        const int id0 = lo + tid * epl;
-        const bool vec_ok = ((uintptr_t)row & 15) == 0;  // id0 is a multiple of 8
-        double mine = 0.0;
-        for (int e0 = 0; e0 < epl; e0 += 8) {
-            float x[8];
-            load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) mine += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
-        }
-        double incl = mine;  // inclusive scan over the lanes of the wave
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const double t = __shfl_up(incl, off, 64);
-            if (lane >= off) incl += t;
-        }
-        if (lane == 63) s_wtot[w] = incl;
-        if (tid == 0) s_bonus = -1;
-        __syncthreads();
-        double run = before;
-        for (int q = 0; q < w; ++q) run += s_wtot[q];
-        const bool cross = run + incl > target_mass;
-        const u64 m = __ballot(cross);
-        // the first crossing thread of the first crossing wave
-        bool earlier = false;
-        {
-            double r2 = before;
-            for (int q = 0; q < w; ++q) {
-                r2 += s_wtot[q];
-                earlier = earlier || r2 > target_mass;
-            }
-        }
-        if (!earlier && m && lane == (int)__builtin_ctzll(m)) {
-            double cm = run + incl - mine;
-            int id = min(id0 + epl, hi) - 1;
-            bool done = false;
-            for (int e0 = 0; e0 < epl && !done; e0 += 8) {
-                float x[8];
-                load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    cm += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
-                    if (!done && cm > target_mass) { id = id0 + e0 + e; done = true; }
-                }
-            }
-            s_bonus = id;
-        }
-        __syncthreads();
-        if (tid == 0 && s_bonus < 0) {
-            // the chunk's re-computed mass falls just short of the crossing (rounding), or the row
-            // carries no mass at all: last token of the chunk that carries mass, else token 0
-            int id = hi - 1;
-            while (id > lo && !(__builtin_amdgcn_exp2f((load_logit(row, a.dtype, id) - Mrow) * cexp) > 0.f)) --id;
-            s_bonus = Z > 0.0 ? id : 0;
-        }
+        // inverse CDF of softmax(row best / T) at the bonus uniform
+        sample_row_block(a, o + best, s_rowmax[best], philox_uniform(a.seed, a.step, (u32)b, 0xFFFFFFFFu), inv_t,
+                         s_wtot, &s_bonus);
     }
     __syncthreads();
 
@@ -252,6 +280,11 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
 
 hipError_t accept_launch(const AcceptArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;
+    if (a.mode == DT_ACCEPT_SAMPLED) {
+        launch_kernel(KID_NODE_SAMPLE, st, node_sample_kernel, dim3(a.batch * a.TT_cap), dim3(256), 0, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     launch_kernel(KID_ACCEPT, st, accept_kernel, dim3(a.batch), dim3(256), 0, a);
     return hipGetLastError();
 }

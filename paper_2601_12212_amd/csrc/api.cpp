@@ -110,7 +110,7 @@ int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq,
     // build: lane maxima + (max, sum) partials + merged top-k (values, ids) + lse
     size_t build = topk_scratch(nullptr, total_rows, St).bytes + 2 * align_up((size_t)total_rows * DT_K_MAX * 4) +
                    align_up((size_t)total_rows * 4);
-    size_t accept = argmax_scratch(nullptr, (int64_t)batch * TT_cap, S).bytes;
+    size_t accept = argmax_scratch(nullptr, (int64_t)batch * TT_cap, S).bytes + align_up((size_t)batch * TT_cap * 4);
     size_t attn = dt::attn_workspace_bytes(batch, TT_cap, Hq, D);
     size_t m = build > accept ? build : accept;
     m = m > attn ? m : attn;
@@ -221,23 +221,25 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
               uint64_t philox_step, int32_t *accept_len, int32_t *best_node, int32_t *path_nodes,
               int32_t *out_tokens, int32_t *node_argmax, void *ws, size_t ws_bytes) {
     if (batch < 0 || bad_dtype(t)) return DT_ERR_INVALID_ARG;
-    if (mode != DT_ACCEPT_GREEDY && mode != DT_ACCEPT_STOCHASTIC) return DT_ERR_INVALID_ARG;
+    if (mode != DT_ACCEPT_GREEDY && mode != DT_ACCEPT_STOCHASTIC && mode != DT_ACCEPT_SAMPLED) return DT_ERR_INVALID_ARG;
     if (batch == 0) return DT_OK;
     if (!target_logits || !n_nodes || !tokens || !parents || !depth || !anc_mask || !accept_len || !best_node ||
         !path_nodes || !out_tokens || row_stride < V)
         return DT_ERR_INVALID_ARG;
-    if (mode == DT_ACCEPT_STOCHASTIC && (!logp || !(temperature > 0.0f))) return DT_ERR_INVALID_ARG;
+    if (mode == DT_ACCEPT_STOCHASTIC && !logp) return DT_ERR_INVALID_ARG;
+    if (mode != DT_ACCEPT_GREEDY && !(temperature > 0.0f)) return DT_ERR_INVALID_ARG;
     if (V < 1 || min_nl(V) == 0 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
     const int64_t rows = (int64_t)batch * TT_cap;
     const int nl = pick_nl(rows, V), S = dt::rows_chunks_per_row(V, nl);
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     ArgmaxScratch rs = argmax_scratch(ws, rows, S);
-    if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
+    int32_t *samples = (int32_t *)((char *)ws + rs.bytes);  // target-sampled mode: one token per node
+    if (rs.bytes + align_up((size_t)rows * 4) > ws_bytes) return DT_ERR_WORKSPACE;
 
     dt::RowArgs a = {};
     a.logits = target_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
     a.mode = dt::ROWS_TARGET; a.batch = batch; a.TT_cap = TT_cap; a.n_nodes = n_nodes;
-    a.want_lse = mode == DT_ACCEPT_STOCHASTIC; a.inv_t = mode == DT_ACCEPT_STOCHASTIC ? 1.0f / temperature : 1.0f;
+    a.want_lse = mode != DT_ACCEPT_GREEDY; a.inv_t = mode != DT_ACCEPT_GREEDY ? 1.0f / temperature : 1.0f;
     a.part_keys = rs.keys; a.part_ms = rs.ms;
     hipStream_t st = (hipStream_t)stream;
     (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
@@ -250,7 +252,7 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     aa.depth = depth; aa.logp = logp; aa.anc_mask = (const unsigned long long *)anc_mask; aa.TT_cap = TT_cap;
     aa.seed = philox_seed; aa.step = philox_step; aa.accept_len = accept_len; aa.best_node = best_node;
     aa.path_nodes = path_nodes; aa.out_tokens = out_tokens; aa.node_argmax = node_argmax;
-    aa.part_keys = rs.keys; aa.part_ms = rs.ms; aa.S = S; aa.chunk_elems = 256 * 8 * nl;
+    aa.part_keys = rs.keys; aa.part_ms = rs.ms; aa.S = S; aa.chunk_elems = 256 * 8 * nl; aa.samples = samples;
     e = dt::accept_launch(aa, st);
     if (e != hipSuccess) return hip_fail(e);
     return DT_OK;

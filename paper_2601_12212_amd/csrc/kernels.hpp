@@ -13,7 +13,7 @@ namespace dt {
 // of pre-created HIP events attached to its dispatch (hipExtLaunchKernelGGL), which record the
 // kernel's own begin and end; dt_profile_read sums the elapsed times per kernel id.
 enum KernelId { KID_ROWS_DRAFT = 0, KID_ROWS_MERGE, KID_TREE, KID_ATTN, KID_ATTN_COMBINE, KID_ROWS_TARGET,
-                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COMMIT, KID_POLICY_L1, KID_POLICY_HEAD, KID_COUNT };
+                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COMMIT, KID_POLICY_L1, KID_POLICY_HEAD, KID_NODE_SAMPLE, KID_COUNT };
 bool prof_next(int kid, hipEvent_t *start, hipEvent_t *stop);  // false when timing is off
 
 template <typename F, typename... Args>
@@ -117,6 +117,7 @@ struct AcceptArgs {
     const float2 *part_ms;
     int S;            // chunks per row
     int chunk_elems;  // vocabulary entries per chunk
+    int32_t *samples; // [batch*TT_cap] target-sampled mode: the token every node drew
 };
 hipError_t accept_launch(const AcceptArgs &a, hipStream_t st);
 

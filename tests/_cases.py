@@ -40,7 +40,7 @@ def oracle_case(ci, seed=0, cfg=None, philox_step=0, max_bumps=20):
             case.accepts.append(ref.accept(c.mode, case.targets[b], t["tokens"], t["parents"], t["depth"],
                                            logp=t["logp"], temperature=c.temperature, seed=c.philox_seed,
                                            step=philox_step, seq=b))
-        if c.mode == dt_synth.STOCHASTIC:
+        if c.mode != dt_synth.GREEDY:
             am = min(a["min_margin"] for a in case.accepts)
             if am < ACCEPT_MARGIN:
                 print("margin guard: %s seed %d accept margin %.3g -> seed %d" % (c.name, c.seed, am, c.seed + 1))
@@ -79,4 +79,6 @@ def assert_accept_equal(got, want, tag=""):
     assert got["best_node"] == want["best_node"], tag
     assert np.array_equal(got["path_nodes"], want["path_nodes"]), tag
     assert np.array_equal(got["out_tokens"], want["out_tokens"]), tag
-    assert np.array_equal(got["node_argmax"], want["node_argmax"]), tag
+    # per-node draws of the target-sampled mode are compared where their own margin allows it
+    sure = want["node_margin"] >= ACCEPT_MARGIN if "node_margin" in want else np.ones(len(want["node_argmax"]), bool)
+    assert np.array_equal(got["node_argmax"][sure], want["node_argmax"][sure]), tag

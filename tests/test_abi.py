@@ -87,7 +87,8 @@ def test_bad_arguments_are_rejected_before_any_launch():
     # accept: bad mode, stochastic without logp or with T <= 0
     acc = lambda **kw: [None, 1, kw.get("mode", 0), kw.get("T", 1.0), one, 1, 1024, 1024, one, one, one, one,
                         kw.get("logp", one), one, 8, 0, 0, one, one, one, one, None, ws, kw.get("wsb", 1 << 24)]
-    assert lib.dt_accept(*acc(mode=2)) == -1
+    assert lib.dt_accept(*acc(mode=3)) == -1
+    assert lib.dt_accept(*acc(mode=2, T=0.0)) == -1
     assert lib.dt_accept(*acc(mode=1, logp=None)) == -1
     assert lib.dt_accept(*acc(mode=1, T=0.0)) == -1
     assert lib.dt_accept(*acc(wsb=8)) == -3

@@ -222,6 +222,83 @@ def test_stochastic_small_and_many_steps():
     assert agree > 60
 
 
+def test_target_sampled_verification_small_and_llama_vocabulary():
+    # distribution-preserving mode: every node draws the target's own token; tokens, path and node samples exact
+    cfg = small_cfg([(40, 5, 4), (64, 6, 6), (1, 1, 1)], [100, 31, 7], V=3001, mode=dt_synth.SAMPLED)
+    cfg.temperature = 0.8
+    case = oracle_case(0, cfg=cfg)
+    st = check_case(case)
+    agree = 0
+    for step in range(1, 25):
+        st.accept(philox_step=step)
+        torch.cuda.synchronize()
+        for b in range(cfg.B):
+            t = case.trees[b]
+            want = ref.accept(cfg.mode, case.targets[b], t["tokens"], t["parents"], t["depth"],
+                              temperature=cfg.temperature, seed=cfg.philox_seed, step=step, seq=b)
+            if want["min_margin"] < 1e-5:
+                continue
+            got = st.accepted(b)
+            assert_accept_equal(got, want, "step %d seq %d" % (step, b))
+            agree += 1
+    assert agree > 50
+    big = small_cfg([(60, 6, 10), (33, 4, 8)], [64, 5], V=128256, Hq=8, Hkv=2, mode=dt_synth.SAMPLED)
+    check_case(oracle_case(0, cfg=big))
+
+
+def test_all_layers_attention_under_one_graph():
+    # verification touches every layer: the attention calls of several layers (own Q/K/V/prefix per layer,
+    # shared tree masks and lengths) captured as one HIP graph, replayed with the outputs wiped and eager
+    # work in between; every replay must reproduce every layer's oracle result.
+    import paper_2601_12212_amd as dt
+    cfg = small_cfg([(30, 4, 3), (64, 5, 5)], [300, 45], Hq=8, Hkv=2)
+    case = oracle_case(0, cfg=cfg)
+    st = make_step(case)
+    st.build_tree()
+    torch.cuda.synchronize()
+    n_layers, B, TC = 3, cfg.B, st.TT_cap
+    rng = np.random.default_rng(8)
+    bf = lambda sh: dt_synth.f32_to_bf16_bits(rng.standard_normal(sh).astype(np.float32))
+    dev = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    layers = []
+    for l in range(n_layers):
+        h = dict(q=bf((B, TC, cfg.Hq, cfg.D)), kt=bf((B, TC, cfg.Hkv, cfg.D)), vt=bf((B, TC, cfg.Hkv, cfg.D)),
+                 kp=[bf((max(L, 1), cfg.Hkv, cfg.D)) for L in cfg.prefix_len],
+                 vp=[bf((max(L, 1), cfg.Hkv, cfg.D)) for L in cfg.prefix_len])
+        d = dict(q=dev(h["q"]), kt=dev(h["kt"]), vt=dev(h["vt"]), kp=[dev(a) for a in h["kp"]], vp=[dev(a) for a in h["vp"]],
+                 out=torch.zeros((B, TC, cfg.Hq, cfg.D), dtype=torch.bfloat16, device="cuda"))
+        d["kpp"] = torch.tensor([t.data_ptr() for t in d["kp"]], dtype=torch.int64, device="cuda")
+        d["vpp"] = torch.tensor([t.data_ptr() for t in d["vp"]], dtype=torch.int64, device="cuda")
+        layers.append((h, d))
+
+    def run():
+        for h, d in layers:
+            dt.dt_tree_attention(d["q"], d["kt"], d["vt"], st.n_nodes, d["kpp"], d["vpp"], st.prefix_len,
+                                 max(cfg.prefix_len), cfg.Hkv * cfg.D, cfg.D, st.anc_mask, st.scale, d["out"], st.ws)
+
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        run()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            run()
+    for rep in range(3):
+        for h, d in layers:
+            d["out"].fill_(7.0)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for l, (h, d) in enumerate(layers):
+            for b in range(B):
+                N, L = case.trees[b]["n_nodes"], cfg.prefix_len[b]
+                want = ref.tree_attention(h["q"][b, :N], h["kt"][b, :N], h["vt"][b, :N], h["kp"][b][:L], h["vp"][b][:L],
+                                          case.trees[b]["anc_mask"], st.scale)
+                got = d["out"][b, :N].float().cpu().numpy()
+                assert np.abs(got - want).max() <= 2e-2, (rep, l, b)
+        (torch.ones(1000, device="cuda") * 3).sum().item()
+
+
 def test_masked_vocabulary_rows():
     """-inf logits (tokens that may never be proposed) and rows with fewer than k viable tokens."""
     cfg = small_cfg([(20, 3, 4)], [50], V=3000)
