@@ -48,7 +48,13 @@ __device__ __forceinline__ int wave_select_t(const float *score, int n, int keep
     Cut c;
     c.thr = 0xFFFFFFFFu;
     c.need_eq = 0;
-    if (keep > 0) {
+    bool decided = false;
+    if (keep > 0 && viable <= keep_max) {
+        // everything viable is kept (a level whose parents propose no more than k candidates in all)
+        c.thr = KEY_NEG_INF;
+        decided = true;
+    }
+    if (keep > 0 && !decided) {
         u32 t = 0;
         if (ITEMS <= 2) {
             // few registers per lane: two bits per step (three independent probe counts)

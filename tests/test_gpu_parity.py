@@ -299,6 +299,25 @@ def test_all_layers_attention_under_one_graph():
         (torch.ones(1000, device="cuda") * 3).sum().item()
 
 
+def test_exact_score_ties_across_rows_go_to_the_lowest_pool_index():
+    # identical draft rows: every candidate of a level has exactly the same score on both sides, so the
+    # level cuts and the rerank are decided by the tie-break alone (the margin guard would reject these
+    # inputs, so the oracle is called directly)
+    from paper_2601_12212_amd.step import Step
+    for V, TT, d, k, bf16 in [(8, 6, 3, 2, False), (8, 9, 3, 2, False), (1000, 60, 4, 10, True), (2048, 128, 8, 32, True),
+                              (700, 100, 5, 12, False)]:
+        rows = np.zeros((1 + (d - 1) * k, V), np.float32)
+        rows[:, V // 3] = 1.0                                # one clear winner per row, the rest tie
+        want = ref.build_tree(dt_synth.f32_to_bf16_bits(rows) if bf16 else rows, TT, d, k, 3)
+        assert want["min_margin"] == 0.0
+        st = Step([(TT, d, k)], [1], 4, 4, 64, V, dtype=torch.bfloat16 if bf16 else torch.float32, TT_cap=128)
+        st.set_draft(0, dt_synth.f32_to_bf16_bits(rows) if bf16 else rows)
+        st.set_root_token(0, 3)
+        st.build_tree()
+        torch.cuda.synchronize()
+        assert_tree_equal(st.tree(0), want, "ties V=%d TT=%d d=%d k=%d" % (V, TT, d, k))
+
+
 def test_masked_vocabulary_rows():
     """-inf logits (tokens that may never be proposed) and rows with fewer than k viable tokens."""
     cfg = small_cfg([(20, 3, 4)], [50], V=3000)
