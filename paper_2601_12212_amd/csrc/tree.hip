@@ -1,227 +1,266 @@
 // Tree kernel: layer-wise expansion, rerank, and emission of the node arrays and the
-// ancestor bitsets.  One workgroup per sequence; the whole candidate pool (at most
+// ancestor bitsets.  One workgroup of eight waves per sequence; the whole candidate pool (at most
 // k + (d-1)k^2 = 7200 scores) lives in LDS.
 //
-// Selections ("the n best by (score desc, pool index asc)") are done without sorting:
-// a bitwise bisection over the order-preserving integer image of the score finds the n-th
-// largest score, then one pass in pool-index order takes everything above it and the first
-// few equal to it.  For up to 1024 candidates one wave does this from registers with
-// ballots only (no barrier inside the 32 steps).
+// Selections ("the n best by (score desc, pool index asc)") never sort.
+//  * A level of up to 256 candidates is ranked by counting: every candidate counts the candidates with
+//    a larger key, the work split over the waves by (64 candidates) x (a slice of the others), the
+//    others read as LDS broadcasts.  Every wave then forms the chosen set by itself from the partial
+//    counts, so the next level's scores follow without another barrier.
+//  * Everything else (larger levels, the rerank over the pool, exact ties that straddle a cut) takes a
+//    radix selection over the order-preserving integer image of the score: four 8-bit digits, one LDS
+//    histogram and one barrier per digit, every wave scanning the 256 bins by itself; then one
+//    workgroup-wide prefix count hands out positions in pool-index order (of equal keys the lowest
+//    indices first).
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace dt {
 
 #ifdef DT_TIMESTAMPS
+// debug builds only: clock readings of thread 0 of workgroup 0, parked in LDS (a global store in front
+// of a barrier would make the wave wait for the store) and copied out when the kernel ends
 __device__ unsigned long long dt_dbg_stamps[64];
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) dt_dbg_stamps[i] = __builtin_amdgcn_s_memtime(); } while (0)
+__shared__ unsigned long long dt_lds_stamps[64];
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) dt_lds_stamps[i] = __builtin_amdgcn_s_memtime(); } while (0)
+#define STAMP_FLUSH() do { if (threadIdx.x < 64 && blockIdx.x == 0) dt_dbg_stamps[threadIdx.x] = dt_lds_stamps[threadIdx.x]; } while (0)
 #else
 #define STAMP(i) do {} while (0)
+#define STAMP_FLUSH() do {} while (0)
 #endif
 
 #define DT_P_MAX (DT_K_MAX + (DT_D_MAX - 1) * DT_K_MAX * DT_K_MAX)
-
-struct Cut {
-    u32 thr;      // key of the n-th best candidate
-    int need_eq;  // how many candidates with key == thr are taken (lowest pool indices first)
-};
+#ifndef TREE_NT
+#define TREE_NT 512               // threads of the workgroup
+#endif
+#define TREE_NW (TREE_NT / 64)    // its waves
+#define COUNT_MAX 256             // largest level ranked by counting
 
 __device__ __forceinline__ u32 score_key(float s) { return ord32(s); }
-#define KEY_NEG_INF 0x007FFFFFu
+#define KEY_NEG_INF 0x007FFFFFu   // key of -inf: a candidate that does not exist
 
-// Selection of the `keep_max` best of score[0..n) (n <= 64*ITEMS) by one full wave, entirely from
-// registers: count the viable ones, find the keep-th largest key by bisection two bits at a time
-// (three independent probe counts per step, all on ballots), then visit the winners in ascending
-// index: f(index, position).  Absent items hold key 0, which no probe (>= 1) ever counts.
-template <int ITEMS, typename F>
-__device__ __forceinline__ int wave_select_t(const float *score, int n, int keep_max, Cut *cut_out, u32 *scratch, F f) {
-    const int lane = lane_id();
-    u32 it[ITEMS];
-    int viable = 0;
-#pragma unroll
-    for (int j = 0; j < ITEMS; ++j) {
-        const int i = j * 64 + lane;
-        it[j] = i < n ? score_key(score[i]) : 0u;
-        viable += __popcll(__ballot(it[j] > KEY_NEG_INF));
-    }
-    const int keep = min(keep_max, viable);
-    Cut c;
-    c.thr = 0xFFFFFFFFu;
-    c.need_eq = 0;
-    bool decided = false;
-    if (keep > 0 && viable <= keep_max) {
-        // everything viable is kept (a level whose parents propose no more than k candidates in all)
-        c.thr = KEY_NEG_INF;
-        decided = true;
-    }
-    if (keep > 0 && !decided) {
-        u32 t = 0;
-        if (ITEMS <= 2) {
-            // few registers per lane: two bits per step (three independent probe counts)
-#pragma unroll 1
-            for (int bit = 30; bit >= 0; bit -= 2) {
-                const u32 c1 = t | (1u << bit), c2 = t | (2u << bit), c3 = t | (3u << bit);
-                int n1 = 0, n2 = 0, n3 = 0;
-#pragma unroll
-                for (int j = 0; j < ITEMS; ++j) {
-                    n1 += __popcll(__ballot(it[j] >= c1));
-                    n2 += __popcll(__ballot(it[j] >= c2));
-                    n3 += __popcll(__ballot(it[j] >= c3));
-                }
-                t = n3 >= keep ? c3 : n2 >= keep ? c2 : n1 >= keep ? c1 : t;
-            }
-        } else {
-            // many registers per lane: settle the upper 16 key bits on all of them, then only the
-            // handful of keys that share that prefix (compacted to one per lane) decide the rest
-#pragma unroll 1
-            for (int bit = 31; bit >= 16; --bit) {
-                const u32 c1 = t | (1u << bit);
-                int n1 = 0;
-#pragma unroll
-                for (int j = 0; j < ITEMS; ++j) n1 += __popcll(__ballot(it[j] >= c1));
-                t = n1 >= keep ? c1 : t;
-            }
-            int above = 0, nb = 0;
-            u32 bk = 0u;  // boundary key of this lane
-            bool one_per_lane = true;
-#pragma unroll
-            for (int j = 0; j < ITEMS; ++j) {
-                above += __popcll(__ballot((it[j] >> 16) > (t >> 16)));
-                const bool bnd = (it[j] >> 16) == (t >> 16);
-                const u64 m = __ballot(bnd);
-                // lane q takes the q-th boundary key: hand it over through LDS-free readlane
-                // is not possible for a variable source, so stage through the scratch list
-                if (bnd) {
-                    const int slot = nb + (int)lanes_below(m);
-                    if (slot < 64) scratch[slot] = it[j];
-                }
-                nb += __popcll(m);
-            }
-            one_per_lane = nb <= 64;
-            const int need = keep - above;
-            if (one_per_lane) {
-                bk = lane < nb ? scratch[lane] : 0u;
-#pragma unroll 1
-                for (int bit = 15; bit >= 0; --bit) {
-                    const u32 c1 = t | (1u << bit);
-                    t = __popcll(__ballot(bk >= c1)) >= need ? c1 : t;
-                }
-            } else {
-#pragma unroll 1
-                for (int bit = 15; bit >= 0; --bit) {
-                    const u32 c1 = t | (1u << bit);
-                    int n1 = 0;
-#pragma unroll
-                    for (int j = 0; j < ITEMS; ++j) n1 += __popcll(__ballot(it[j] >= c1));
-                    t = n1 >= keep ? c1 : t;
-                }
-            }
-        }
-        int gt = 0;
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) gt += __popcll(__ballot(it[j] > t));
-        c.thr = t;
-        c.need_eq = keep - gt;
-    }
-    if (cut_out) *cut_out = c;
-    int pos = 0, eq_seen = 0;
-    if (keep > 0) {
-#pragma unroll
-        for (int j = 0; j < ITEMS; ++j) {
-            const int i = j * 64 + lane;
-            const bool eq = it[j] == c.thr;
-            const u64 meq = __ballot(eq);
-            const bool take = it[j] > c.thr || (eq && eq_seen + (int)lanes_below(meq) < c.need_eq);
-            const u64 m = __ballot(take);
-            if (take) f(i, pos + (int)lanes_below(m));
-            pos += __popcll(m);
-            eq_seen += __popcll(meq);
-        }
-    }
-    return pos;
-}
-// scratch: 64 LDS words private to the calling wave
-template <typename F>
-__device__ __forceinline__ int wave_select(const float *score, int n, int keep_max, Cut *cut_out, u32 *scratch, F f) {
-    if (n <= 64) return wave_select_t<1>(score, n, keep_max, cut_out, scratch, f);
-    if (n <= 128) return wave_select_t<2>(score, n, keep_max, cut_out, scratch, f);
-    if (n <= 256) return wave_select_t<4>(score, n, keep_max, cut_out, scratch, f);
-    if (n <= 512) return wave_select_t<8>(score, n, keep_max, cut_out, scratch, f);
-    return wave_select_t<16>(score, n, keep_max, cut_out, scratch, f);
-}
-
-__device__ __forceinline__ int block_sum_256(int v, int *s_red) {
-    const int lane = lane_id(), w = threadIdx.x >> 6;
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    __syncthreads();
-    if (lane == 0) s_red[w] = v;
-    __syncthreads();
-    return s_red[0] + s_red[1] + s_red[2] + s_red[3];
-}
-
-// Same cut for any n, by the whole workgroup (barriers inside every step).
-__device__ __forceinline__ Cut block_cut(const float *score, int n, int keep, int *s_red) {
-    u32 t = 0;
-    for (int bit = 31; bit >= 0; --bit) {
-        const u32 cand = t | (1u << bit);
-        int cnt = 0;
-        for (int i = threadIdx.x; i < n; i += 256) cnt += score_key(score[i]) >= cand ? 1 : 0;
-        if (block_sum_256(cnt, s_red) >= keep) t = cand;
-    }
-    int gt = 0;
-    for (int i = threadIdx.x; i < n; i += 256) gt += score_key(score[i]) > t ? 1 : 0;
-    Cut c;
-    c.thr = t;
-    c.need_eq = keep - block_sum_256(gt, s_red);
-    return c;
-}
-
-__device__ __forceinline__ int count_viable_wave(const float *score, int n) {
-    int cnt = 0;
-    for (int base = 0; base < n; base += 64) {
-        int i = base + lane_id();
-        cnt += __popcll(__ballot(i < n && score[i] > -INFINITY));
-    }
-    return cnt;
-}
-
-// Visit the selected candidates of score[0..n) in ascending index; f(i, position).  One wave.
-template <typename F>
-__device__ __forceinline__ int wave_enumerate(const float *score, int n, Cut c, F f) {
-    int pos = 0, eq_seen = 0;
-    for (int base = 0; base < n; base += 64) {
-        const int i = base + lane_id();
-        const u32 key = i < n ? score_key(score[i]) : 0u;
-        const bool eq = i < n && key == c.thr;
-        const u64 meq = __ballot(eq);
-        const bool take = (i < n && key > c.thr) || (eq && eq_seen + (int)lanes_below(meq) < c.need_eq);
-        const u64 m = __ballot(take);
-        if (take) f(i, pos + (int)lanes_below(m));
-        pos += __popcll(m);
-        eq_seen += __popcll(meq);
-    }
-    return pos;
-}
+// x / dv for 0 <= x < 8192 and 1 <= dv <= 1024 with inv = 1.0f / dv (any rounding within two ulp):
+// (x + 0.5) / dv is at least 0.5 / dv away from every integer, far more than the product's error.
+__device__ __forceinline__ int fdiv(int x, float inv) { return (int)(((float)x + 0.5f) * inv); }
 
 struct Decoded {
     int level, slot, rank, row;
 };
-__device__ __forceinline__ Decoded decode(int p, int k) {
+struct PoolShape {
+    int k, kk;
+    float inv_k, inv_kk;
+};
+__device__ __forceinline__ PoolShape pool_shape(int k) {
+    PoolShape s;
+    s.k = k; s.kk = k * k;
+    s.inv_k = 1.0f / (float)k; s.inv_kk = 1.0f / (float)(k * k);
+    return s;
+}
+// pool index -> (level, slot of the parent in its level's expanded set, rank in the parent's row, draft row)
+__device__ __forceinline__ Decoded decode(int p, const PoolShape &s) {
     Decoded d;
-    if (p < k) {
+    if (p < s.k) {
         d.level = 1; d.slot = 0; d.rank = p; d.row = 0;
     } else {
-        int q = p - k, kk = k * k;
-        int l2 = q / kk, rem = q - l2 * kk;
-        d.level = l2 + 2; d.slot = rem / k; d.rank = rem - d.slot * k;
-        d.row = 1 + l2 * k + d.slot;
+        const int q = p - s.k;
+        const int l2 = fdiv(q, s.inv_kk), rem = q - l2 * s.kk;
+        d.level = l2 + 2; d.slot = fdiv(rem, s.inv_k); d.rank = rem - d.slot * s.k;
+        d.row = 1 + l2 * s.k + d.slot;
     }
     return d;
 }
 
-__global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
-    const int b = blockIdx.x, tid = threadIdx.x, w = tid >> 6;
+// inclusive prefix sum over the lanes of a wave (row shifts, then the two row broadcasts)
+__device__ __forceinline__ int wave_scan_incl(int v) {
+    DT_DPP_REDUCE(v, 0, i_add, id_i, id_i)
+    return v;
+}
+
+struct TreeLds {
+    float score[DT_P_MAX];         // lp of a candidate, then its cumulative score
+    int16_t node[DT_P_MAX];        // node number after the rerank, -1: not kept
+    int8_t slot[DT_P_MAX];         // slot in its level's expanded set, -1: not expanded
+    int exp[DT_D_MAX][DT_K_MAX];   // pool index of slot s of level l
+    u32 key[2][COUNT_MAX];         // keys of the level being ranked by counting (levels alternate)
+    int rank[2][COUNT_MAX];        // how many keys of the level lie above each (summed by LDS adds)
+    u32 hist[4][256];              // one histogram per radix digit
+    int wtot[TREE_NW];             // per-wave totals of the position scan
+};
+
+// ---- radix selection ---------------------------------------------------------------------------------
+// Key of the keep-th best of score[0..n), keep = min(keep_max, #viable): returns keep (uniform), thr and
+// need_eq = how many candidates with key == thr belong to the chosen set.  Whole workgroup; ends
+// with every thread past the last barrier it contains.
+__device__ __forceinline__ int block_radix_cut(const float *score, int n, int keep_max, TreeLds &S, u32 &thr,
+                                               int &need_eq) {
+    const int tid = threadIdx.x, lane = lane_id();
+    for (int i = tid; i < 4 * 256; i += TREE_NT) (&S.hist[0][0])[i] = 0u;
+    __syncthreads();
+    u32 prefix = 0;
+    int above = 0, keep = 0;
+    thr = 0xFFFFFFFFu;
+    need_eq = 0;
+#pragma unroll 1
+    for (int p = 0; p < 4; ++p) {
+        const int shift = 24 - 8 * p;
+        for (int i = tid; i < n; i += TREE_NT) {
+            const u32 key = score_key(score[i]);
+            const bool in = key > KEY_NEG_INF && (p == 0 || (key >> (shift + 8)) == (prefix >> (shift + 8)));
+            if (in) atomicAdd(&S.hist[p][(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        STAMP(14 + p);
+        // every wave: lane L holds bins 4(63-L) .. 4(63-L)+3, so an ascending lane scan walks the bins downwards
+        const uint4 h = *(const uint4 *)&S.hist[p][4 * (63 - lane)];
+        const int c = (int)(h.x + h.y + h.z + h.w);
+        const int incl = wave_scan_incl(c);
+        if (p == 0) {
+            keep = min(keep_max, __builtin_amdgcn_readlane(incl, 63));
+            if (keep <= 0) return 0;
+        }
+        const int need = keep - above;  // rank of the wanted key among those sharing the digits found so far
+        const u64 m = __ballot(incl >= need);
+        const int ls = __ffsll((long long)m) - 1;
+        int acc = __builtin_amdgcn_readlane(incl - c, ls);
+        const int h3 = __builtin_amdgcn_readlane((int)h.w, ls), h2 = __builtin_amdgcn_readlane((int)h.z, ls),
+                  h1 = __builtin_amdgcn_readlane((int)h.y, ls);
+        int dg;
+        if (acc + h3 >= need) dg = 3;
+        else {
+            acc += h3;
+            if (acc + h2 >= need) dg = 2;
+            else {
+                acc += h2;
+                if (acc + h1 >= need) dg = 1;
+                else { acc += h1; dg = 0; }
+            }
+        }
+        above += acc;
+        prefix |= (u32)(4 * (63 - ls) + dg) << shift;
+        const int hd = dg == 3 ? h3 : dg == 2 ? h2 : dg == 1 ? h1 : __builtin_amdgcn_readlane((int)h.x, ls);
+        if (keep - above == hd && p < 3 && prefix != 0u) {
+            // every key that shares these digits belongs to the set: cut just below the smallest of them
+            thr = prefix - 1u;
+            need_eq = 0;
+            return keep;
+        }
+    }
+    thr = prefix;
+    need_eq = keep - above;
+    return keep;
+}
+
+// Positions in ascending index of the chosen candidates of score[0..n): those above thr and the first
+// need_eq of those equal to it; f(index, position).  Returns how many were chosen (uniform).  Whole
+// workgroup; one barrier inside, none after the calls of f.
+template <typename F>
+__device__ __forceinline__ int block_enumerate(const float *score, int n, u32 thr, int need_eq, TreeLds &S, F f) {
+    const int tid = threadIdx.x, lane = lane_id(), w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int C = (n + TREE_NT - 1) / TREE_NT;  // consecutive candidates per thread
+    const int i0 = tid * C;
+    int own = 0;  // low half: keys above thr, high half: keys equal to thr
+    for (int c = 0; c < C; ++c) {
+        const int i = i0 + c;
+        const u32 kv = score_key(score[min(i, n - 1)]);
+        const u32 key = i < n ? kv : 0u;
+        own += (key > thr ? 1 : 0) + (key == thr ? 0x10000 : 0);
+    }
+    const int incl = wave_scan_incl(own);
+    if (lane == 63) S.wtot[w] = incl;
+    __syncthreads();
+    int base = 0, total = 0;
+#pragma unroll
+    for (int v = 0; v < TREE_NW; ++v) {
+        const int t = S.wtot[v];
+        base += v < w ? t : 0;
+        total += t;
+    }
+    int before = base + incl - own;
+    for (int c = 0; c < C; ++c) {
+        const int i = i0 + c;
+        const u32 kv = score_key(score[min(i, n - 1)]);
+        const u32 key = i < n ? kv : 0u;
+        const int gt = before & 0xFFFF, eq = before >> 16;
+        if (key > thr || (key == thr && eq < need_eq)) f(i, gt + min(eq, need_eq));
+        before += (key > thr ? 1 : 0) + (key == thr ? 0x10000 : 0);
+    }
+    return (total & 0xFFFF) + min(total >> 16, need_eq);
+}
+
+// The keep_max best of score[0..n) (fewer if fewer are viable), visited in ascending index.  Whole
+// workgroup; the calls of f are followed by a barrier.
+template <typename F>
+__device__ __forceinline__ int block_select(const float *score, int n, int keep_max, TreeLds &S, F f) {
+    u32 thr;
+    int need_eq;
+    const int keep = block_radix_cut(score, n, keep_max, S, thr, need_eq);
+    STAMP(18);
+    if (keep <= 0) return 0;
+    const int taken = block_enumerate(score, n, thr, need_eq, S, f);
+    STAMP(19);
+    __syncthreads();
+    return taken;
+}
+
+// ---- ranking a level by counting ---------------------------------------------------------------------
+// key[0 .. 64 G) holds the keys of the level's n candidates (zero beyond n), G = ceil(n / 64) <= 4, and
+// rank[0 .. 64 G) is zero.  Wave w counts, for the 64 candidates of group w % G, the keys above
+// theirs within slice w / G of the level, and adds that to their rank.  Ties are counted as "not above",
+// so candidates of equal key share a rank; the caller detects a tie that straddles the cut by the size
+// of the chosen set.
+template <int G>
+__device__ __forceinline__ void level_count(const u32 *key, int *rank) {
+    constexpr int H = G == 1 ? TREE_NW : G == 2 ? TREE_NW / 2 : TREE_NW / 4;  // slices
+    constexpr int PER = 64 * G / H;                                           // keys per slice (padding included)
+    const int lane = lane_id(), w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (w < G * H) {
+        const int g = w % G, h = w / G;
+        const u32 mine = key[g * 64 + lane];
+        const uint4 *other = (const uint4 *)&key[h * PER];
+        int cnt = 0;
+#pragma unroll
+        for (int j = 0; j < PER / 4; ++j) {
+            const uint4 o = other[j];
+            cnt += (o.x > mine ? 1 : 0) + (o.y > mine ? 1 : 0) + (o.z > mine ? 1 : 0) + (o.w > mine ? 1 : 0);
+        }
+        atomicAdd(&rank[g * 64 + lane], cnt);
+    }
+}
+// Every wave by itself, after the barrier that follows level_count: the chosen set of the level (rank
+// below k among the viable candidates; all of them when n <= k, rank then is not read), positions in
+// ascending index.  Returns the size of the set, or -1 when equal keys straddle the cut (nothing has
+// been written then).  f(index, position) is called by every wave for every chosen candidate.
+template <int G, typename F>
+__device__ __forceinline__ int level_choose(const u32 *key, const int *rank, int n, int k, F f) {
+    const int lane = lane_id();
+    u64 m[G];
+    int chosen = 0, viable = 0;
+    u32 ky[G];
+    int rk[G];
+#pragma unroll
+    for (int q = 0; q < G; ++q) {  // all loads first
+        ky[q] = key[q * 64 + lane];
+        rk[q] = n <= k ? 0 : rank[q * 64 + lane];
+    }
+#pragma unroll
+    for (int q = 0; q < G; ++q) {
+        const bool ok = ky[q] > KEY_NEG_INF;
+        m[q] = __builtin_amdgcn_ballot_w64(ok && rk[q] < k);
+        viable += __popcll(__builtin_amdgcn_ballot_w64(ok));
+        chosen += __popcll(m[q]);
+    }
+    if (chosen != min(k, viable)) return -1;
+    int before = 0;
+#pragma unroll
+    for (int q = 0; q < G; ++q) {
+        if ((m[q] >> lane) & 1ull) f(q * 64 + lane, before + (int)lanes_below(m[q]));
+        before += __popcll(m[q]);
+    }
+    return chosen;
+}
+
+__global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
+    const int b = blockIdx.x, tid = threadIdx.x;
     const dt_params prm = a.params[b];
     const int TT = min(max(prm.TT, 1), a.TT_cap), d = min(max(prm.d, 1), DT_D_MAX);
     const int k = min(max(prm.k, 1), min(DT_K_MAX, a.V));
@@ -231,15 +270,10 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     const int32_t *ti = a.top_id + r0 * DT_K_MAX;
     const float *lse = a.lse + r0;
     const int64_t o = (int64_t)b * a.TT_cap;
+    const PoolShape ps = pool_shape(k);
+    const int kk = k * k;
 
-    __shared__ float s_score[DT_P_MAX];
-    __shared__ int16_t s_node[DT_P_MAX];
-    __shared__ int8_t s_slot[DT_P_MAX];
-    __shared__ int s_exp[DT_D_MAX][DT_K_MAX];
-    __shared__ int s_nexp;
-    __shared__ int s_red[4];
-    __shared__ Cut s_cut;
-    __shared__ u32 s_scratch[64];
+    __shared__ __align__(16) TreeLds S;
 
     STAMP(0);
     if (xl > 0 && (TT == 1 || xl >= d)) {  // nothing is drafted below level d
@@ -262,17 +296,21 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     }
     // candidates through level d, or through level xl when only that level's choice is wanted (the
     // rows of deeper levels do not exist yet)
-    const int P = xl > 0 ? k + (xl - 1) * k * k : k + (d - 1) * k * k;
+    const int P = xl > 0 ? k + (xl - 1) * kk : k + (d - 1) * kk;
     // Every candidate's own log-probability is known up front: the draft row that would
     // produce pool index p is fixed by p alone (only its parent is decided later).  Park
-    // lp in s_score; the level loop turns it into the cumulative score in place.
-    for (int p = tid; p < P; p += 256) {
-        const Decoded dc = decode(p, k);
+    // lp in the score array; the level loop turns it into the cumulative score in place.
+    for (int p = tid; p < P; p += TREE_NT) {
+        const Decoded dc = decode(p, ps);
         const float v = tv[dc.row * DT_K_MAX + dc.rank];
-        s_score[p] = v > -INFINITY ? v - lse[dc.row] : -INFINITY;
-        s_node[p] = -1;
-        s_slot[p] = -1;
+        const float lp = v > -INFINITY ? v - lse[dc.row] : -INFINITY;
+        S.score[p] = lp;
+        S.node[p] = -1;
+        S.slot[p] = -1;
+        if (p < 64) S.key[1][p] = p < k ? score_key(lp) : 0u;  // level 1 is chosen first
     }
+    if (P < 64) for (int p = P + tid; p < 64; p += TREE_NT) S.key[1][p] = 0u;
+    for (int t = tid; t < COUNT_MAX; t += TREE_NT) S.rank[0][t] = 0;
     __syncthreads();
     STAMP(1);
 
@@ -280,24 +318,40 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
     int p_end = k;  // pool indices below p_end hold real scores (levels computed so far)
     const int l_end = xl > 0 ? xl + 1 : d;
     for (int l = 1; l < l_end; ++l) {
-        const int lo = l == 1 ? 0 : k + (l - 2) * k * k;
-        const int n = l == 1 ? k : k * k;
-        if (w == 0) {
-            int *exp_l = s_exp[l];
-            const int n_exp = wave_select(s_score + lo, n, k, nullptr, s_scratch, [&](int i, int pos) {
-                exp_l[pos] = lo + i;
-                s_slot[lo + i] = (int8_t)pos;
-            });
-            if (lane_id() == 0) s_nexp = n_exp;
+        const int lo = l == 1 ? 0 : k + (l - 2) * kk;
+        const int n = l == 1 ? k : kk;
+        int *exp_l = S.exp[l];
+        auto put = [&](int i, int pos) {
+            exp_l[pos] = lo + i;
+            S.slot[lo + i] = (int8_t)pos;
+        };
+        int n_exp = -1;
+        if (n <= COUNT_MAX) {
+            // (after the barrier that published the keys) count, publish the ranks, choose in every wave
+            const u32 *key = S.key[l & 1];
+            int *rank = S.rank[l & 1];
+            const int G = (n + 63) >> 6;
+            if (n > k) {  // otherwise every viable candidate is chosen
+                if (G == 1) level_count<1>(key, rank);
+                else if (G == 2) level_count<2>(key, rank);
+                else if (G == 3) level_count<3>(key, rank);
+                else level_count<4>(key, rank);
+                STAMP(24 + 4 * l);
+                __syncthreads();
+                STAMP(25 + 4 * l);
+            }
+            if (G == 1) n_exp = level_choose<1>(key, rank, n, k, put);
+            else if (G == 2) n_exp = level_choose<2>(key, rank, n, k, put);
+            else if (G == 3) n_exp = level_choose<3>(key, rank, n, k, put);
+            else n_exp = level_choose<4>(key, rank, n, k, put);
         }
+        if (n_exp < 0) n_exp = block_select(S.score + lo, n, k, S, put);
         STAMP(2 + 2 * l);
-        __syncthreads();
-        const int n_exp = s_nexp;
         if (l == xl) {
             // ---- what the draft model is handed for its next pass: node s of the chosen set ----------
             if (tid < n_exp) {
-                const int pi = s_exp[l][tid];
-                const Decoded dc = decode(pi, k);
+                const int pi = exp_l[tid];
+                const Decoded dc = decode(pi, ps);
                 const int64_t e = (int64_t)b * DT_K_MAX + tid;
                 a.exp_token[e] = ti[dc.row * DT_K_MAX + dc.rank];
                 a.exp_parent_slot[e] = l == 1 ? -1 : dc.slot;
@@ -313,11 +367,13 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
                     m2 |= wd == 2 ? bit : 0ull; m3 |= wd == 3 ? bit : 0ull;
                 };
                 set(own);
-                int pp = l == 1 ? -1 : s_exp[l - 1][dc.slot];
-                for (int guard = 0; guard < DT_D_MAX && pp >= 0; ++guard) {
-                    const Decoded dp = decode(pp, k);
-                    set(1 + (dp.level - 1) * k + s_slot[pp]);
-                    pp = dp.level == 1 ? -1 : s_exp[dp.level - 1][dp.slot];
+                // the slot of an expanded candidate is read from S.exp, which every wave wrote for itself
+                int lv = l, sl = dc.slot;  // level of the current node, slot of its parent
+                for (int guard = 0; guard < DT_D_MAX && lv > 1; ++guard) {
+                    set(1 + (lv - 2) * k + sl);
+                    const Decoded dp = decode(S.exp[lv - 1][sl], ps);
+                    --lv;
+                    sl = dp.slot;
                 }
                 a.exp_mask[e * 4] = m0; a.exp_mask[e * 4 + 1] = m1;
                 a.exp_mask[e * 4 + 2] = m2; a.exp_mask[e * 4 + 3] = m3;
@@ -326,13 +382,23 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
             return;
         }
         if (n_exp == 0) break;
-        const int nlo = k + (l - 1) * k * k;
-        for (int t = tid; t < k * k; t += 256) {
-            const int s = t / k;
+        // next level: score = score[parent] + lp, and the keys for its ranking.  exp_l is read by the
+        // wave that wrote it (every wave writes the whole set) or after block_select's barrier.
+        const int nlo = k + (l - 1) * kk;
+        const int npad = kk <= COUNT_MAX ? ((kk + 63) & ~63) : kk;
+        for (int t = tid; t < npad; t += TREE_NT) {
+            const int tc = min(t, kk - 1);
+            const int s = fdiv(tc, ps.inv_k);
             // slots beyond the expanded set own no node: their candidates do not exist
-            s_score[nlo + t] = s < n_exp ? s_score[s_exp[l][s]] + s_score[nlo + t] : -INFINITY;
+            const float par = S.score[exp_l[min(s, n_exp - 1)]], own = S.score[nlo + tc];
+            const float sc = s < n_exp ? par + own : -INFINITY;
+            if (t < kk) S.score[nlo + t] = sc;
+            if (kk <= COUNT_MAX) {  // the other pair of arrays: slower waves may still be choosing from this level's
+                S.key[(l + 1) & 1][t] = t < kk ? score_key(sc) : 0u;
+                S.rank[(l + 1) & 1][t] = 0;
+            }
         }
-        p_end = nlo + k * k;
+        p_end = nlo + kk;
         __syncthreads();
         STAMP(3 + 2 * l);
     }
@@ -341,62 +407,41 @@ __global__ __launch_bounds__(256) void tree_kernel(TreeArgs a) {
         if (tid == 0) { a.n_expand[b] = 0; a.state_n_exp[b] = 0; }
         return;
     }
-    __syncthreads();  // every wave has read s_nexp before it is reused below
+    __syncthreads();  // the level loop may have been left right after a wave-local choice
 
     // ---- rerank: the TT-1 best of the whole pool ----------------------------------------------
-    Cut cut;
-    int keep;
-    if (p_end <= 1024) {
-        if (w == 0) {
-            const int kp = wave_select(s_score, p_end, TT - 1, nullptr, s_scratch,
-                                       [&](int i, int pos) { s_node[i] = (int16_t)(pos + 1); });
-            if (lane_id() == 0) s_nexp = kp;
-        }
-        __syncthreads();
-        keep = s_nexp;
-    } else {
-        int v = 0;
-        for (int i = tid; i < p_end; i += 256) v += s_score[i] > -INFINITY ? 1 : 0;
-        keep = min(TT - 1, block_sum_256(v, s_red));
-        cut.thr = 0xFFFFFFFFu;
-        cut.need_eq = 0;
-        if (keep > 0) cut = block_cut(s_score, p_end, keep, s_red);
-    }
+    const int keep = block_select(S.score, p_end, TT - 1, S, [&](int i, int pos) { S.node[i] = (int16_t)(pos + 1); });
     STAMP(20);
-    if (p_end > 1024) {
-        if (w == 0 && keep > 0)
-            wave_enumerate(s_score, p_end, cut, [&](int i, int pos) { s_node[i] = (int16_t)(pos + 1); });
-        __syncthreads();
-    }
     if (tid == 0) a.n_nodes[b] = keep + 1;
     STAMP(21);
 
     // ---- emission -------------------------------------------------------------------------------
-    for (int p = tid; p < p_end; p += 256) {
-        const int n = s_node[p];
+    for (int p = tid; p < p_end; p += TREE_NT) {
+        const int n = S.node[p];
         if (n < 0) continue;
-        const Decoded dc = decode(p, k);
+        const Decoded dc = decode(p, ps);
         const float v = tv[dc.row * DT_K_MAX + dc.rank];
-        int par_pool = dc.level == 1 ? -1 : s_exp[dc.level - 1][dc.slot];
+        int par_pool = dc.level == 1 ? -1 : S.exp[dc.level - 1][dc.slot];
         a.tokens[o + n] = ti[dc.row * DT_K_MAX + dc.rank];
-        a.parents[o + n] = par_pool < 0 ? 0 : max((int)s_node[par_pool], 0);
+        a.parents[o + n] = par_pool < 0 ? 0 : max((int)S.node[par_pool], 0);
         a.depth[o + n] = dc.level;
-        a.score[o + n] = s_score[p];
+        a.score[o + n] = S.score[p];
         a.logp[o + n] = v - lse[dc.row];
-        a.src_row[o + n] = s_slot[p] >= 0 ? 1 + (dc.level - 1) * k + s_slot[p] : -1;
+        a.src_row[o + n] = S.slot[p] >= 0 ? 1 + (dc.level - 1) * k + S.slot[p] : -1;
         u64 m0 = 1ull, m1 = 0ull;  // the root
         int nn = n, pp = par_pool;
         for (int guard = 0; guard <= DT_D_MAX; ++guard) {
             if (nn < 64) m0 |= 1ull << nn; else m1 |= 1ull << (nn - 64);
             if (pp < 0) break;
-            nn = max((int)s_node[pp], 0);
-            const Decoded dp = decode(pp, k);
-            pp = dp.level == 1 ? -1 : s_exp[dp.level - 1][dp.slot];
+            nn = max((int)S.node[pp], 0);
+            const Decoded dp = decode(pp, ps);
+            pp = dp.level == 1 ? -1 : S.exp[dp.level - 1][dp.slot];
         }
         a.anc_mask[(o + n) * DT_MASK_WORDS] = m0;
         a.anc_mask[(o + n) * DT_MASK_WORDS + 1] = m1;
     }
     STAMP(22);
+    STAMP_FLUSH();
 }
 
 #ifdef DT_TIMESTAMPS
@@ -407,7 +452,7 @@ extern "C" int dt_debug_stamps(unsigned long long *out) {
 
 hipError_t tree_launch(const TreeArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;
-    launch_kernel(KID_TREE, st, tree_kernel, dim3(a.batch), dim3(256), 0, a);
+    launch_kernel(KID_TREE, st, tree_kernel, dim3(a.batch), dim3(TREE_NT), 0, a);
     return hipGetLastError();
 }
 
