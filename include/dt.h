@@ -93,7 +93,8 @@ int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, i
  * and uses the first 1 + (d-1)*k of them: local row 0 is the next-token row of the root;
  * local row 1 + (l-1)*k + s is the next-token row of the s-th expanded node of level l
  * (l = 1..d-1), expanded nodes of a level being numbered in ascending pool index.
- * total_rows = row_off[batch] as a host value (sizes the launch).
+ * total_rows = row_off[batch] as a host value (sizes the launch; draft_logits holds that many rows,
+ * all of which may be read, also those a sequence does not use).
  *
  * Method.  Level-l candidates are the top-k tokens of every expanded level-(l-1) node;
  * score = score[parent] + (logit - lse of its row), one float add per level.  The k best
@@ -145,7 +146,8 @@ int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int 
 /*
  * Acceptance and longest accepted walk (paper Section 3.2 "Acceptance Criterion";
  * Section 3.1 greedy decoding).  target_logits row (b, i) = the target's next-token
- * logits after node i, at target_logits + (b*TT_cap + i)*row_stride.
+ * logits after node i, at target_logits + (b*TT_cap + i)*row_stride.  The buffer holds all
+ * batch*TT_cap rows: rows at and past n_nodes[b] never reach a result, but a small launch may read them.
  *   greedy     : node i > 0 accepted iff tokens[i] == argmax(row of its parent), ties -> lowest id
  *   stochastic : accepted iff u_i < min(1, P_T(tokens[i]) / P_d(tokens[i])), P_T = softmax(row of
  *                parent / temperature), P_d = exp(logp[i]); u_i is the first word of
@@ -190,7 +192,8 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
  * dt_expand_level, level l: level_logits holds the rows of this pass, sequence b's row s at
  * level_logits + (b*R + s)*row_stride with R = 1 for level 1 (the root's next-token row) and
  * R = rows_per_seq (>= every k, <= DT_K_MAX) otherwise; row s belongs to the s-th node that the
- * previous call reported for sequence b (rows at and past that call's n_expand[b] are ignored).
+ * previous call reported for sequence b (rows at and past that call's n_expand[b] are ignored, but
+ * belong to the buffer, which holds batch*R rows: a small launch may read them).
  * The call scores the candidates of level l and reports the nodes of level l that are expanded
  * next, in slot order (= ascending pool index):
  *   n_expand        [batch]            how many (0 when l >= d, TT == 1, or nothing is viable)

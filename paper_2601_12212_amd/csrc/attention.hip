@@ -539,15 +539,19 @@ template <int D, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, SplitBuf sb) {
     static_assert(D == 128 && (NW == 4 || NW == 8), "shape");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
+    ASTAMP(62);
     const int G = a.Hq / a.Hkv;
     // blockIdx.x = kv head: workgroups are dealt to the 8 XCDs round-robin by linear id, so every
     // row block and split of one kv head lands on one XCD and shares its L2 copy of that head's K/V
     const int b = blockIdx.z / KS, ks = blockIdx.z % KS, h = blockIdx.x;
-    const int N = min(max(a.n_nodes[b], 1), a.TT_cap);
+    // the four per-sequence words, asked for together: one trip to memory instead of up to three
+    const int n_raw = a.n_nodes[b], l_raw = a.prefix_len[b];
+    const void *kp_raw = a.k_prefix[b], *vp_raw = a.v_prefix[b];
+    const int N = min(max(n_raw, 1), a.TT_cap);
     const int M = N * G;
     const int m0 = blockIdx.y * 32;
     if (m0 >= M) return;
-    const int L = max(a.prefix_len[b], 0);
+    const int L = max(l_raw, 0);
     const int Tk = L + N;
     const int nb = (Tk + ATT_KB - 1) / ATT_KB;
 
@@ -583,8 +587,8 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
     float m_run = -INFINITY, l_run = 0.f;
     const float c = a.scale * 1.4426950408889634f;
 
-    const gbf16p kpre = (gbf16p)a.k_prefix[b] + (int64_t)h * a.kv_stride_head;
-    const gbf16p vpre = (gbf16p)a.v_prefix[b] + (int64_t)h * a.kv_stride_head;
+    const gbf16p kpre = (gbf16p)kp_raw + (int64_t)h * a.kv_stride_head;
+    const gbf16p vpre = (gbf16p)vp_raw + (int64_t)h * a.kv_stride_head;
     const gbf16p ktree = (gbf16p)a.k_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
     const gbf16p vtree = (gbf16p)a.v_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
     const int64_t stok = a.kv_stride_tok, stree = (int64_t)a.Hkv * D;
@@ -797,6 +801,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
 #pragma unroll
         for (int q = 0; q < 4; ++q) pw[q * 64 + lane] = make_float4(res[4 * q], res[4 * q + 1], res[4 * q + 2], res[4 * q + 3]);
         if (w == 0 && half == 0) sb.ml[(unit * KS + ks) * 32 + col] = make_float2(Mx, Lsum);
+        ASTAMP(63);
         return;
     }
     if (!qvalid) return;

@@ -81,6 +81,11 @@ __device__ __forceinline__ int wave_sum_i32(int v) {
     DT_DPP_REDUCE(v, 0, i_add, id_i, id_i)
     return __builtin_amdgcn_readlane(v, 63);
 }
+// inclusive prefix sum over the lanes of a wave (the same row shifts and row broadcasts)
+__device__ __forceinline__ int wave_scan_incl_i32(int v) {
+    DT_DPP_REDUCE(v, 0, i_add, id_i, id_i)
+    return v;
+}
 // 64-bit maximum: the high words first, then the low words of the lanes that hold that high word.
 __device__ __forceinline__ u64 wave_max_u64(u64 v) {
     const u32 hi = wave_max_u32((u32)(v >> 32));

@@ -47,6 +47,9 @@ struct RowArgs {
     // ROWS_LEVEL: rows of one level of every sequence, results scattered into the build state
     int level, rows_per_seq, state_rows;
     const int32_t *n_exp_prev;  // [batch] nodes expanded one level up
+    // set by the launch functions: read a row's chunk before the row is known to be live (the loads then
+    // overlap the reads that decide it; the row is inside the caller's buffer either way)
+    int early_load;
 };
 
 int rows_chunks_per_row(int V, int nl);

@@ -13,6 +13,17 @@
 
 namespace dt {
 
+#ifdef DT_TIMESTAMPS
+// debug builds only: clock readings of thread 0 of workgroup 0 of the selection kernel
+__device__ unsigned long long dt_dbg_stamps_rows[64];
+__shared__ unsigned long long dt_lds_stamps_rows[64];
+#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) dt_lds_stamps_rows[i] = __builtin_amdgcn_s_memtime(); } while (0)
+#define STAMP_FLUSH() do { __syncthreads(); if (threadIdx.x < 64 && blockIdx.x == 0) dt_dbg_stamps_rows[threadIdx.x] = dt_lds_stamps_rows[threadIdx.x]; } while (0)
+#else
+#define STAMP(i) do {} while (0)
+#define STAMP_FLUSH() do {} while (0)
+#endif
+
 // ---------------------------------------------------------------- row -> (valid, k) ----
 struct RowMeta {
     bool valid;
@@ -148,12 +159,13 @@ __global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
     constexpr int E = 8 * NL;
     const int64_t g = blockIdx.y;
     const int c = blockIdx.x;
-    const RowMeta meta = row_meta(a, g);
-    if (!meta.valid) return;
     const int lane = lane_id(), w = threadIdx.x >> 6;
     const int base = c * (256 * E) + w * (64 * E) + lane * 8;
     float x[E];
-    load_chunk<NL, BF16, VEC>(a, g, base, x);
+    if (a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
+    const RowMeta meta = row_meta(a, g);
+    if (!meta.valid) return;
+    if (!a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
     float mx = x[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
@@ -183,15 +195,25 @@ __device__ __forceinline__ float load_elem(const RowArgs &a, int64_t g, int id) 
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int S, float *top_val, int32_t *top_id,
-                                                         float *lse, int out_stride) {
+__global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int S, int vec, float *top_val,
+                                                         int32_t *top_id, float *lse, int out_stride) {
     const int64_t g = blockIdx.x;
-    const RowMeta meta = row_meta(a, g);
-    if (!meta.valid) return;
-    const int k = meta.k, tid = threadIdx.x, lane = lane_id(), w = tid >> 6;
+    const int tid = threadIdx.x, lane = lane_id(), w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int V = a.V, E = 8 * nl;
     const int n_lanes = S * 256;
     const float *lm = a.lane_max + g * n_lanes;
+    STAMP(0);
+    // the lane maxima do not depend on the row's metadata (two dependent global reads): ask for them
+    // first.  Rows that turn out to be dead have their slots in the workspace all the same.
+    float it[16];
+    if (S <= 16) {
+#pragma unroll
+        for (int j = 0; j < 16; ++j) it[j] = lm[min(j, S - 1) * 256 + tid];
+    }
+    const RowMeta meta = row_meta(a, g);
+    if (!meta.valid) return;
+    STAMP(1);
+    const int k = meta.k;
 
     __shared__ float s_T[4];
     __shared__ float s_c1v[4][64];
@@ -215,18 +237,19 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     };
 
     // ---- 1. thread maxima, per-wave k-th largest, T0 ------------------------------------------
-    float it[16];
     float tmax = -INFINITY;
     if (S <= 16) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            it[j] = j < S ? lm[j * 256 + tid] : -INFINITY;
+            it[j] = j < S ? it[j] : -INFINITY;
             tmax = fmaxf(tmax, it[j]);
         }
     } else {
         for (int j = 0; j < S; ++j) tmax = fmaxf(tmax, lm[j * 256 + tid]);
     }
+    STAMP(2);
     const float Tw = unord32(wave_kth_largest<BF16 ? 16 : 0>(ord32(tmax), k));
+    STAMP(3);
     if (lane == 0) s_T[w] = Tw;
     if (tid == 0) s_n2 = 0;
     __syncthreads();
@@ -234,24 +257,38 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
 
     // ---- 2. lane maxima >= T0, compacted per wave ---------------------------------------------
     int cnt = 0;
-    auto push = [&](float v, int j) {
-        const bool hit = v >= T0;
-        const u64 m = __ballot(hit);
-        if (m) {
-            const int slot = cnt + (int)lanes_below(m);
-            if (hit && slot < 64) { s_c1v[w][slot] = v; s_c1l[w][slot] = j * 256 + tid; }
-            cnt += __popcll(m);
-        }
-    };
     if (S <= 16) {
+        // hits are rare (a few dozen of S*256): count them per thread, place them with one wave scan
+        int mine = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
-            if (j < S) push(it[j], j);
+        for (int j = 0; j < 16; ++j) mine += it[j] >= T0 ? 1 : 0;
+        int at = wave_scan_incl_i32(mine);
+        cnt = __builtin_amdgcn_readlane(at, 63);
+        at -= mine;
+        if (mine > 0) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                if (it[j] >= T0) {
+                    if (at < 64) { s_c1v[w][at] = it[j]; s_c1l[w][at] = j * 256 + tid; }
+                    ++at;
+                }
+            }
+        }
     } else {
-        for (int j = 0; j < S; ++j) push(lm[j * 256 + tid], j);
+        for (int j = 0; j < S; ++j) {
+            const float v = lm[j * 256 + tid];
+            const bool hit = v >= T0;
+            const u64 m = __ballot(hit);
+            if (m) {
+                const int slot = cnt + (int)lanes_below(m);
+                if (hit && slot < 64) { s_c1v[w][slot] = v; s_c1l[w][slot] = j * 256 + tid; }
+                cnt += __popcll(m);
+            }
+        }
     }
     if (lane == 0) s_c1n[w] = cnt;
     __syncthreads();
+    STAMP(5);
     const int c0 = s_c1n[0], c1 = s_c1n[1], c2 = s_c1n[2], c3 = s_c1n[3];
     const int n1 = c0 + c1 + c2 + c3;
     bool slow = n1 > 64;  // uniform over the workgroup
@@ -290,7 +327,9 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
             if (hot) s_hot[lanes_below(m)] = gl;
             if (lane == 0) { s_h = __popcll(m); s_Trow = T; }
         }
+        STAMP(6);
         __syncthreads();
+        STAMP(7);
         const int h = s_h;
         const float T = s_Trow;
         // ---- 3. re-read the hot lanes: (hot lane, load n) pairs spread over the threads ----
@@ -298,19 +337,43 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
             const int gl = s_hot[q / nl], n = q % nl;
             const int c = gl >> 8, ww = (gl >> 6) & 3, l = gl & 63;
             const int id0 = c * (256 * E) + ww * (64 * E) + l * 8 + n * 512;
-            for (int e = 0; e < 8; ++e) {
-                const int id = id0 + e;
-                const float xv = id < V ? load_elem(a, g, id) : -INFINITY;
-                if (xv >= T) {
-                    const int slot = atomicAdd(&s_n2, 1);
-                    if (slot < 64) s_fin[slot] = make_key(xv, (u32)id);
+            float xv[8];
+            if (BF16 && vec && id0 + 8 <= V) {
+                const uint4 r = *(const uint4 *)((const uint16_t *)a.logits + g * a.row_stride + id0);
+                const u32 rr[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    xv[2 * p] = __uint_as_float(rr[p] << 16);
+                    xv[2 * p + 1] = __uint_as_float(rr[p] & 0xFFFF0000u);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xv[e] = load_elem(a, g, min(id0 + e, V - 1));
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xv[e] = id0 + e < V ? xv[e] : -INFINITY;
+            }
+            int hits = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) hits += xv[e] >= T ? 1 : 0;
+            if (hits > 0) {
+                int slot = atomicAdd(&s_n2, hits);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    if (xv[e] >= T) {
+                        if (slot < 64) s_fin[slot] = make_key(xv[e], (u32)(id0 + e));
+                        ++slot;
+                    }
                 }
             }
         }
+        STAMP(8);
         __syncthreads();
+        STAMP(9);
         const int n2 = s_n2;
         if (n2 <= 64) {
             if (w == 0) rank_emit_lanes(lane < n2 ? s_fin[lane] : 0ull, n2, k, emit);
+            STAMP(10);
+            STAMP_FLUSH();
             return;
         }
         slow = true;
@@ -347,15 +410,16 @@ __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
     constexpr int E = 8 * NL;
     const int64_t g = blockIdx.y;
     const int c = blockIdx.x;
-    const RowMeta meta = row_meta(a, g);
-    if (!meta.valid) return;
     const int lane = lane_id(), w = threadIdx.x >> 6;
     __shared__ u64 s_wout[4];
     __shared__ float s_m[4], s_s[4];
 
     const int base = c * (256 * E) + w * (64 * E) + lane * 8;
     float x[E];
-    load_chunk<NL, BF16, VEC>(a, g, base, x);
+    if (a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
+    const RowMeta meta = row_meta(a, g);
+    if (!meta.valid) return;
+    if (!a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
     float mx = x[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
@@ -396,6 +460,12 @@ __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
 }
 
 // ------------------------------------------------------------------------ launchers ------
+#ifdef DT_TIMESTAMPS
+extern "C" int dt_debug_stamps_rows(unsigned long long *out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_stamps_rows), sizeof(unsigned long long) * 64);
+}
+#endif
+
 int rows_chunks_per_row(int V, int nl) { return (V + 256 * 8 * nl - 1) / (256 * 8 * nl); }
 
 // Chunk multiplier for the top-k rows: the smallest that keeps a row within 16 chunks (so that
@@ -420,9 +490,9 @@ static bool rows_vec_ok(const RowArgs &a) {
     return ((uintptr_t)a.logits % 16 == 0) && ((a.row_stride * esz) % 16 == 0);
 }
 
-#define DT_ROWS_DISPATCH(KID, KERNEL, NLV)                                                                \
+#define DT_ROWS_DISPATCH(KID, KERNEL, NLV, GRID)                                                          \
     do {                                                                                                  \
-        dim3 grid(rows_chunks_per_row(a.V, NLV), (unsigned)n_rows);                                       \
+        dim3 grid = GRID;                                                                                 \
         if (a.dtype == DT_BF16) {                                                                         \
             if (vec) launch_kernel(KID, st, KERNEL<NLV, true, true>, grid, dim3(256), 0, a);              \
             else launch_kernel(KID, st, KERNEL<NLV, true, false>, grid, dim3(256), 0, a);                 \
@@ -433,15 +503,24 @@ static bool rows_vec_ok(const RowArgs &a) {
     } while (0)
 
 // top-k rows, pass 1: lane maxima and (max, sum) partials
-hipError_t rows_launch_stream(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st) {
+// Launches of at most this many workgroups are latency bound: their rows are read before they are known
+// to be live.  Larger ones are bandwidth bound, and the bytes of a dead row would cost time.
+static const int64_t EARLY_LOAD_WGS = 2048;
+
+hipError_t rows_launch_stream(const RowArgs &a_in, int64_t n_rows, int nl, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
+    RowArgs a = a_in;
+    // every row of a draft or uniform launch is live unless the caller's row_off leaves gaps
+    a.early_load = a.mode == ROWS_DRAFT || a.mode == ROWS_UNIFORM || n_rows * rows_chunks_per_row(a.V, nl) <= EARLY_LOAD_WGS;
     const bool vec = rows_vec_ok(a);
     const int kid = a.mode == ROWS_DRAFT ? KID_ROWS_DRAFT : KID_ROWS_UNIFORM;
+#define STREAM_GRID(NLV) dim3(rows_chunks_per_row(a.V, NLV), (unsigned)n_rows)
     switch (nl) {
-        case 4: DT_ROWS_DISPATCH(kid, row_stream_kernel, 4); break;
-        case 2: DT_ROWS_DISPATCH(kid, row_stream_kernel, 2); break;
-        default: DT_ROWS_DISPATCH(kid, row_stream_kernel, 1); break;
+        case 4: DT_ROWS_DISPATCH(kid, row_stream_kernel, 4, STREAM_GRID(4)); break;
+        case 2: DT_ROWS_DISPATCH(kid, row_stream_kernel, 2, STREAM_GRID(2)); break;
+        default: DT_ROWS_DISPATCH(kid, row_stream_kernel, 1, STREAM_GRID(1)); break;
     }
+#undef STREAM_GRID
     return hipGetLastError();
 }
 
@@ -450,24 +529,29 @@ hipError_t rows_launch_select(const RowArgs &a, int64_t n_rows, int nl, float *t
                               int out_stride, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
     const int S = rows_chunks_per_row(a.V, nl);
+    const int vec = rows_vec_ok(a) ? 1 : 0;
     if (a.dtype == DT_BF16)
         launch_kernel(KID_ROWS_MERGE, st, row_select_kernel<true>, dim3((unsigned)n_rows), dim3(256), 0, a, nl, S,
-                      top_val, top_id, lse, out_stride);
+                      vec, top_val, top_id, lse, out_stride);
     else
         launch_kernel(KID_ROWS_MERGE, st, row_select_kernel<false>, dim3((unsigned)n_rows), dim3(256), 0, a, nl, S,
-                      top_val, top_id, lse, out_stride);
+                      vec, top_val, top_id, lse, out_stride);
     return hipGetLastError();
 }
 
 // arg max rows (target logits)
-hipError_t rows_launch_argmax(const RowArgs &a, int64_t n_rows, int nl, hipStream_t st) {
+hipError_t rows_launch_argmax(const RowArgs &a_in, int64_t n_rows, int nl, hipStream_t st) {
     if (n_rows <= 0) return hipSuccess;
+    RowArgs a = a_in;
+    a.early_load = n_rows * rows_chunks_per_row(a.V, nl) <= EARLY_LOAD_WGS;
     const bool vec = rows_vec_ok(a);
+#define STREAM_GRID(NLV) dim3(rows_chunks_per_row(a.V, NLV), (unsigned)n_rows)
     switch (nl) {
-        case 4: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 4); break;
-        case 2: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 2); break;
-        default: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 1); break;
+        case 4: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 4, STREAM_GRID(4)); break;
+        case 2: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 2, STREAM_GRID(2)); break;
+        default: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 1, STREAM_GRID(1)); break;
     }
+#undef STREAM_GRID
     return hipGetLastError();
 }
 

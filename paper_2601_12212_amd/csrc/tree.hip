@@ -70,12 +70,6 @@ __device__ __forceinline__ Decoded decode(int p, const PoolShape &s) {
     return d;
 }
 
-// inclusive prefix sum over the lanes of a wave (row shifts, then the two row broadcasts)
-__device__ __forceinline__ int wave_scan_incl(int v) {
-    DT_DPP_REDUCE(v, 0, i_add, id_i, id_i)
-    return v;
-}
-
 struct TreeLds {
     float score[DT_P_MAX];         // lp of a candidate, then its cumulative score
     int16_t node[DT_P_MAX];        // node number after the rerank, -1: not kept
@@ -113,7 +107,7 @@ __device__ __forceinline__ int block_radix_cut(const float *score, int n, int ke
         // every wave: lane L holds bins 4(63-L) .. 4(63-L)+3, so an ascending lane scan walks the bins downwards
         const uint4 h = *(const uint4 *)&S.hist[p][4 * (63 - lane)];
         const int c = (int)(h.x + h.y + h.z + h.w);
-        const int incl = wave_scan_incl(c);
+        const int incl = wave_scan_incl_i32(c);
         if (p == 0) {
             keep = min(keep_max, __builtin_amdgcn_readlane(incl, 63));
             if (keep <= 0) return 0;
@@ -165,7 +159,7 @@ __device__ __forceinline__ int block_enumerate(const float *score, int n, u32 th
         const u32 key = i < n ? kv : 0u;
         own += (key > thr ? 1 : 0) + (key == thr ? 0x10000 : 0);
     }
-    const int incl = wave_scan_incl(own);
+    const int incl = wave_scan_incl_i32(own);
     if (lane == 63) S.wtot[w] = incl;
     __syncthreads();
     int base = 0, total = 0;
