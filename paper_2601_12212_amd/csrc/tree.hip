@@ -35,6 +35,7 @@ __shared__ unsigned long long dt_lds_stamps[64];
 #endif
 #define TREE_NW (TREE_NT / 64)    // its waves
 #define COUNT_MAX 256             // largest level ranked by counting
+#define BUCKET_CAP 64             // most candidates of one score bucket that are ranked one against the other
 
 __device__ __forceinline__ u32 score_key(float s) { return ord32(s); }
 #define KEY_NEG_INF 0x007FFFFFu   // key of -inf: a candidate that does not exist
@@ -79,6 +80,8 @@ struct TreeLds {
     int rank[2][COUNT_MAX];        // how many keys of the level lie above each (summed by LDS adds)
     u32 hist[4][256];              // one histogram per radix digit
     int wtot[TREE_NW];             // per-wave totals of the position scan
+    u64 mem[BUCKET_CAP];           // (key, index) of the candidates in the bucket that holds the cut
+    int memn;
 };
 
 // ---- radix selection ---------------------------------------------------------------------------------
@@ -181,19 +184,182 @@ __device__ __forceinline__ int block_enumerate(const float *score, int n, u32 th
     return (total & 0xFFFF) + min(total >> 16, need_eq);
 }
 
+// Positions of flagged candidates: thread t owns candidates [t C, t C + C) and their flags (bit c of
+// `flags`); f(index, position) for every flagged one, positions counted in ascending index.  Returns
+// the number of flagged candidates (uniform).  Whole workgroup; one barrier inside.
+template <typename F>
+__device__ __forceinline__ int block_positions(int C, u32 flags, TreeLds &S, F f) {
+    const int tid = threadIdx.x, lane = lane_id(), w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int own = __popc(flags);
+    const int incl = wave_scan_incl_i32(own);
+    if (lane == 63) S.wtot[w] = incl;
+    __syncthreads();
+    int base = 0, total = 0;
+#pragma unroll
+    for (int v = 0; v < TREE_NW; ++v) {
+        const int t = S.wtot[v];
+        base += v < w ? t : 0;
+        total += t;
+    }
+    int pos = base + incl - own;
+    for (int c = 0; c < C; ++c)
+        if ((flags >> c) & 1u) f(tid * C + c, pos++);
+    return total;
+}
+
 // The keep_max best of score[0..n) (fewer if fewer are viable), visited in ascending index.  Whole
 // workgroup; the calls of f are followed by a barrier.
-template <typename F>
-__device__ __forceinline__ int block_select(const float *score, int n, int keep_max, TreeLds &S, F f) {
-    u32 thr;
-    int need_eq;
-    const int keep = block_radix_cut(score, n, keep_max, S, thr, need_eq);
-    STAMP(18);
+//
+// Scores are log-probabilities, so floor(-8 score), capped at 255, spreads them over buckets that are
+// ordered like the scores.  One histogram and one scan name the bucket that holds the cut; the few
+// candidates inside it are ranked one against the other by (key desc, index asc), everything in a better
+// bucket is taken.  A bucket with more than BUCKET_CAP candidates (many equal scores, or scores below
+// -32) goes through the radix selection instead.  CT: candidates per thread when known at compile time
+// (their scores then stay in registers), 0: any number up to 32.
+__device__ __forceinline__ int score_bucket(float sc) { return min(max((int)(sc * -8.0f), 0), 255); }
+__device__ __forceinline__ u64 member_key(u32 key, int i) { return ((u64)key << 32) | (u32)(0x7FFFFFFF - i); }
+
+template <int CT, typename F>
+__device__ __forceinline__ int block_select_t(const float *score, int n, int keep_max, TreeLds &S, F f) {
+    const int tid = threadIdx.x, lane = lane_id();
+    const int C = CT > 0 ? CT : (n + TREE_NT - 1) / TREE_NT;  // consecutive candidates per thread
+    constexpr int CR = CT > 0 ? CT : 1;
+    float sc[CR];
+    if (tid < 256) S.hist[0][tid] = 0u;
+    if (tid < BUCKET_CAP) S.mem[tid] = 0ull;
+    if (tid == 0) S.memn = 0;
+    __syncthreads();
+    if (CT > 0) {
+#pragma unroll
+        for (int c = 0; c < CR; ++c) sc[c] = score[min(tid * CT + c, n - 1)];
+#pragma unroll
+        for (int c = 0; c < CR; ++c) {
+            if (tid * CT + c >= n) sc[c] = -INFINITY;
+            if (sc[c] > -INFINITY) atomicAdd(&S.hist[0][score_bucket(sc[c])], 1u);
+        }
+    } else {
+        for (int c = 0; c < C; ++c) {
+            const int i = tid * C + c;
+            const float v = score[min(i, n - 1)];
+            if (i < n && v > -INFINITY) atomicAdd(&S.hist[0][score_bucket(v)], 1u);
+        }
+    }
+    __syncthreads();
+    // every wave: lane L holds buckets 4L .. 4L+3, best scores first
+    const uint4 h = *(const uint4 *)&S.hist[0][4 * lane];
+    const int c4 = (int)(h.x + h.y + h.z + h.w);
+    const int incl = wave_scan_incl_i32(c4);
+    const int keep = min(keep_max, __builtin_amdgcn_readlane(incl, 63));
     if (keep <= 0) return 0;
-    const int taken = block_enumerate(score, n, thr, need_eq, S, f);
-    STAMP(19);
+    const int ls = __ffsll((long long)__builtin_amdgcn_ballot_w64(incl >= keep)) - 1;
+    int above = __builtin_amdgcn_readlane(incl - c4, ls);
+    const int h0 = __builtin_amdgcn_readlane((int)h.x, ls), h1 = __builtin_amdgcn_readlane((int)h.y, ls),
+              h2 = __builtin_amdgcn_readlane((int)h.z, ls), h3 = __builtin_amdgcn_readlane((int)h.w, ls);
+    int dg, hB;
+    if (above + h0 >= keep) { dg = 0; hB = h0; }
+    else {
+        above += h0;
+        if (above + h1 >= keep) { dg = 1; hB = h1; }
+        else {
+            above += h1;
+            if (above + h2 >= keep) { dg = 2; hB = h2; }
+            else { above += h2; dg = 3; hB = h3; }
+        }
+    }
+    const int B = 4 * ls + dg;
+    const int need = keep - above;  // how many of bucket B belong to the set: 1 .. hB
+    if (hB > BUCKET_CAP) {
+        u32 thr;
+        int need_eq;
+        if (block_radix_cut(score, n, keep_max, S, thr, need_eq) <= 0) return 0;
+        const int taken = block_enumerate(score, n, thr, need_eq, S, f);
+        __syncthreads();
+        return taken;
+    }
+    // flags of the candidates in better buckets, and of those in bucket B
+    u32 sure = 0u, inb = 0u;
+    if (CT > 0) {
+#pragma unroll
+        for (int c = 0; c < CR; ++c) {
+            const int bk = score_bucket(sc[c]);
+            const bool ok = sc[c] > -INFINITY;
+            sure |= (ok && bk < B ? 1u : 0u) << c;
+            inb |= (ok && bk == B ? 1u : 0u) << c;
+        }
+    } else {
+        for (int c = 0; c < C; ++c) {
+            const int i = tid * C + c;
+            const float v = score[min(i, n - 1)];
+            const int bk = score_bucket(v);
+            const bool ok = i < n && v > -INFINITY;
+            sure |= (ok && bk < B ? 1u : 0u) << c;
+            inb |= (ok && bk == B ? 1u : 0u) << c;
+        }
+    }
+    if (need < hB) {  // the cut runs through bucket B: its members rank themselves
+        auto key_of = [&](int c) { return member_key(score_key(CT > 0 ? sc[CT > 0 ? c : 0] : score[tid * C + c]), tid * C + c); };
+        if (CT > 0) {
+#pragma unroll
+            for (int c = 0; c < CR; ++c)
+                if ((inb >> c) & 1u) S.mem[atomicAdd(&S.memn, 1)] = key_of(c);
+        } else {
+            for (int c = 0; c < C; ++c)
+                if ((inb >> c) & 1u) S.mem[atomicAdd(&S.memn, 1)] = key_of(c);
+        }
+        __syncthreads();
+        if (inb) {
+            // entries past the hB members are zero and rank below every member
+            auto rank_of = [&](u64 mine) {
+                int rank = 0;
+                for (int j0 = 0; j0 < hB; j0 += 8) {
+                    u64 o[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] = S.mem[j0 + j];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) rank += o[j] > mine ? 1 : 0;
+                }
+                return rank;
+            };
+            if (CT > 0) {
+#pragma unroll
+                for (int c = 0; c < CR; ++c)
+                    if (((inb >> c) & 1u) && rank_of(key_of(c)) < need) sure |= 1u << c;
+            } else {
+                for (int c = 0; c < C; ++c)
+                    if (((inb >> c) & 1u) && rank_of(key_of(c)) < need) sure |= 1u << c;
+            }
+        }
+    } else {
+        sure |= inb;
+    }
+    const int taken = block_positions(C, sure, S, f);
     __syncthreads();
     return taken;
+}
+template <typename F>
+__device__ __forceinline__ int block_select(const float *score, int n, int keep_max, TreeLds &S, F f) {
+    if (n <= TREE_NT) return block_select_t<1>(score, n, keep_max, S, f);
+    if (n <= 2 * TREE_NT) return block_select_t<2>(score, n, keep_max, S, f);
+    return block_select_t<0>(score, n, keep_max, S, f);
+}
+
+// c_i += (o_i > mine) for the four keys of o.  Written out so that the four compares go to four scalar
+// register pairs and the four adds-with-carry follow them: no result is needed by the next instruction,
+// where the compiler's own sequence (compare into VCC, add from VCC) waits on every pair.
+__device__ __forceinline__ void count_above4(const uint4 o, u32 mine, int &c0, int &c1, int &c2, int &c3) {
+    u64 m0, m1, m2, m3;
+    asm(
+        "v_cmp_gt_u32_e64 %[m0], %[ox], %[mine]\n\t"
+        "v_cmp_gt_u32_e64 %[m1], %[oy], %[mine]\n\t"
+        "v_cmp_gt_u32_e64 %[m2], %[oz], %[mine]\n\t"
+        "v_cmp_gt_u32_e64 %[m3], %[ow], %[mine]\n\t"
+        "v_addc_co_u32_e64 %[c0], %[m0], 0, %[c0], %[m0]\n\t"
+        "v_addc_co_u32_e64 %[c1], %[m1], 0, %[c1], %[m1]\n\t"
+        "v_addc_co_u32_e64 %[c2], %[m2], 0, %[c2], %[m2]\n\t"
+        "v_addc_co_u32_e64 %[c3], %[m3], 0, %[c3], %[m3]\n\t"
+        : [c0] "+v"(c0), [c1] "+v"(c1), [c2] "+v"(c2), [c3] "+v"(c3), [m0] "=&s"(m0), [m1] "=&s"(m1),
+          [m2] "=&s"(m2), [m3] "=&s"(m3)
+        : [ox] "v"(o.x), [oy] "v"(o.y), [oz] "v"(o.z), [ow] "v"(o.w), [mine] "v"(mine));
 }
 
 // ---- ranking a level by counting ---------------------------------------------------------------------
@@ -211,13 +377,10 @@ __device__ __forceinline__ void level_count(const u32 *key, int *rank) {
         const int g = w % G, h = w / G;
         const u32 mine = key[g * 64 + lane];
         const uint4 *other = (const uint4 *)&key[h * PER];
-        int cnt = 0;
+        int c0 = 0, c1 = 0, c2 = 0, c3 = 0;
 #pragma unroll
-        for (int j = 0; j < PER / 4; ++j) {
-            const uint4 o = other[j];
-            cnt += (o.x > mine ? 1 : 0) + (o.y > mine ? 1 : 0) + (o.z > mine ? 1 : 0) + (o.w > mine ? 1 : 0);
-        }
-        atomicAdd(&rank[g * 64 + lane], cnt);
+        for (int j = 0; j < PER / 4; ++j) count_above4(other[j], mine, c0, c1, c2, c3);
+        atomicAdd(&rank[g * 64 + lane], (c0 + c1) + (c2 + c3));
     }
 }
 // Every wave by itself, after the barrier that follows level_count: the chosen set of the level (rank
