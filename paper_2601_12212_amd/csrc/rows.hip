@@ -216,8 +216,8 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     const int k = meta.k;
 
     __shared__ float s_T[4];
-    __shared__ float s_c1v[4][64];
-    __shared__ int s_c1l[4][64];
+    __shared__ float s_c1v[4][128];  // 64 list slots, then one spare word per lane
+    __shared__ int s_c1l[4][128];
     __shared__ int s_c1n[4];
     __shared__ int s_hot[64];
     __shared__ int s_h;
@@ -266,12 +266,14 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
         cnt = __builtin_amdgcn_readlane(at, 63);
         at -= mine;
         if (mine > 0) {
+            // no branch per value: a miss (or a slot past the list) goes to this lane's own spare word
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
-                if (it[j] >= T0) {
-                    if (at < 64) { s_c1v[w][at] = it[j]; s_c1l[w][at] = j * 256 + tid; }
-                    ++at;
-                }
+                const bool hit = it[j] >= T0;
+                const int dst = hit && at < 64 ? at : 64 + lane;
+                s_c1v[w][dst] = it[j];
+                s_c1l[w][dst] = j * 256 + tid;
+                at += hit ? 1 : 0;
             }
         }
     } else {
@@ -332,9 +334,10 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
         STAMP(7);
         const int h = s_h;
         const float T = s_Trow;
+        const int nl_log2 = nl == 4 ? 2 : nl == 2 ? 1 : 0;  // chunk multipliers are 1, 2 or 4
         // ---- 3. re-read the hot lanes: (hot lane, load n) pairs spread over the threads ----
         for (int q = tid; q < h * nl; q += 256) {
-            const int gl = s_hot[q / nl], n = q % nl;
+            const int gl = s_hot[q >> nl_log2], n = q & (nl - 1);
             const int c = gl >> 8, ww = (gl >> 6) & 3, l = gl & 63;
             const int id0 = c * (256 * E) + ww * (64 * E) + l * 8 + n * 512;
             float xv[8];
@@ -371,7 +374,21 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
         STAMP(9);
         const int n2 = s_n2;
         if (n2 <= 64) {
-            if (w == 0) rank_emit_lanes(lane < n2 ? s_fin[lane] : 0ull, n2, k, emit);
+            if (w == 0) {
+                const u64 mine = lane < n2 ? s_fin[lane] : 0ull;
+                int r0 = 0, r1 = 0;
+                for (int j0 = 0; j0 < n2; j0 += 8) {  // eight broadcast reads in flight, then the compares
+                    u64 o[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) o[j] = s_fin[j0 + j];
+#pragma unroll
+                    for (int j = 0; j < 8; j += 2) {  // s_fin[n2 .. 63] may hold anything: masked
+                        r0 += j0 + j < n2 && o[j] > mine ? 1 : 0;
+                        r1 += j0 + j + 1 < n2 && o[j + 1] > mine ? 1 : 0;
+                    }
+                }
+                if (lane < n2 && r0 + r1 < k) emit(r0 + r1, mine);
+            }
             STAMP(10);
             STAMP_FLUSH();
             return;
