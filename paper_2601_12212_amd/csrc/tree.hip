@@ -73,6 +73,8 @@ __device__ __forceinline__ Decoded decode(int p, const PoolShape &s) {
 
 struct TreeLds {
     float score[DT_P_MAX];         // lp of a candidate, then its cumulative score
+    float lp[DT_P_MAX];            // its own log-probability and token, kept for the emission: the
+    int tok[DT_P_MAX];             // kernel then ends without another trip to memory
     int16_t node[DT_P_MAX];        // node number after the rerank, -1: not kept
     int8_t slot[DT_P_MAX];         // slot in its level's expanded set, -1: not expanded
     int exp[DT_D_MAX][DT_K_MAX];   // pool index of slot s of level l
@@ -430,7 +432,8 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
     const PoolShape ps = pool_shape(k);
     const int kk = k * k;
 
-    __shared__ __align__(16) TreeLds S;
+    extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];  // 116 KB: more than a static array may hold
+    TreeLds &S = *reinterpret_cast<TreeLds *>(s_dyn);
 
     STAMP(0);
     if (xl > 0 && (TT == 1 || xl >= d)) {  // nothing is drafted below level d
@@ -460,8 +463,12 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
     for (int p = tid; p < P; p += TREE_NT) {
         const Decoded dc = decode(p, ps);
         const float v = tv[dc.row * DT_K_MAX + dc.rank];
-        const float lp = v > -INFINITY ? v - lse[dc.row] : -INFINITY;
+        const int token = ti[dc.row * DT_K_MAX + dc.rank];
+        const float own = v - lse[dc.row];
+        const float lp = v > -INFINITY ? own : -INFINITY;
         S.score[p] = lp;
+        S.lp[p] = own;
+        S.tok[p] = token;
         S.node[p] = -1;
         S.slot[p] = -1;
         if (p < 64) S.key[1][p] = p < k ? score_key(lp) : 0u;  // level 1 is chosen first
@@ -510,7 +517,7 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
                 const int pi = exp_l[tid];
                 const Decoded dc = decode(pi, ps);
                 const int64_t e = (int64_t)b * DT_K_MAX + tid;
-                a.exp_token[e] = ti[dc.row * DT_K_MAX + dc.rank];
+                a.exp_token[e] = S.tok[pi];
                 a.exp_parent_slot[e] = l == 1 ? -1 : dc.slot;
                 const int own = 1 + (l - 1) * k + tid;
                 a.exp_row[e] = own;
@@ -577,13 +584,12 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
         const int n = S.node[p];
         if (n < 0) continue;
         const Decoded dc = decode(p, ps);
-        const float v = tv[dc.row * DT_K_MAX + dc.rank];
         int par_pool = dc.level == 1 ? -1 : S.exp[dc.level - 1][dc.slot];
-        a.tokens[o + n] = ti[dc.row * DT_K_MAX + dc.rank];
+        a.tokens[o + n] = S.tok[p];
         a.parents[o + n] = par_pool < 0 ? 0 : max((int)S.node[par_pool], 0);
         a.depth[o + n] = dc.level;
         a.score[o + n] = S.score[p];
-        a.logp[o + n] = v - lse[dc.row];
+        a.logp[o + n] = S.lp[p];
         a.src_row[o + n] = S.slot[p] >= 0 ? 1 + (dc.level - 1) * k + S.slot[p] : -1;
         u64 m0 = 1ull, m1 = 0ull;  // the root
         int nn = n, pp = par_pool;
@@ -609,7 +615,14 @@ extern "C" int dt_debug_stamps(unsigned long long *out) {
 
 hipError_t tree_launch(const TreeArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;
-    launch_kernel(KID_TREE, st, tree_kernel, dim3(a.batch), dim3(TREE_NT), 0, a);
+    static bool lds_opt_in = false;  // LDS beyond 64 KB has to be asked for once
+    if (!lds_opt_in) {
+        const hipError_t e = hipFuncSetAttribute((const void *)tree_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 (int)sizeof(TreeLds));
+        if (e != hipSuccess) return e;
+        lds_opt_in = true;
+    }
+    launch_kernel(KID_TREE, st, tree_kernel, dim3(a.batch), dim3(TREE_NT), sizeof(TreeLds), a);
     return hipGetLastError();
 }
 
