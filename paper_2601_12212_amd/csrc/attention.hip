@@ -61,6 +61,7 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const __bf16 *p) {
 #define V_PITCH (128 + 32)
 #define VT_PITCH 40         // bf16 elements per V^T row in LDS (80 B)
 #define ATT_MAX_SPLITS 16
+#define LAZY_LOG2 8.0f        // how far (in powers of two) a probability may exceed 1 before the reference maximum moves
 
 // position of key kk (0..31) inside a V^T row: 16-byte unit (step, lane half) then index,
 // mirroring which accumulator registers of S^T a lane holds (rows 8*(i/4) + 4*half + i%4).
@@ -257,9 +258,15 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, sacc[j][i]);
             mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-            const float m_new = fmaxf(m_run, mloc);
+            // m_run is a reference, not the exact running maximum: it moves only when a block's maximum
+            // lies more than LAZY_LOG2 binary orders above it.  Until then probabilities may reach
+            // 2^LAZY_LOG2 instead of 1 (harmless in fp32 sums and in bf16's relative precision) and the 64
+            // multiplies that rescale the output accumulators are not spent: with unit-variance keys the
+            // reference settles on the first block.  (-inf - -inf is NaN: a fully hidden block moves nothing.)
+            const bool move = (mloc - m_run) * c > LAZY_LOG2;
+            const float m_new = move ? mloc : m_run;
             const float m_use = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c);  // m_run = -inf -> 0
+            const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_use) * c) : 1.0f;  // m_run = -inf -> 0
             const float nmc = -m_use * c;
             float psum = 0.f;
             bf16x8 pb[2][2];
@@ -674,9 +681,11 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
 #pragma unroll
         for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, sacc[i]);
         mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
-        const float m_new = fmaxf(m_run, mloc);
+        // lazily moved reference maximum, as in the large-batch kernel
+        const bool move = (mloc - m_run) * c > LAZY_LOG2;
+        const float m_new = move ? mloc : m_run;
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * c);
+        const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_use) * c) : 1.0f;
         const float nmc = -m_use * c;
         float psum = 0.f;
         bf16x8 pb[2];
