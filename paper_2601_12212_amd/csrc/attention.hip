@@ -229,16 +229,35 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
         if (active) {
             const unsigned char *kt = s_dyn + cur * STAGE_BYTES, *vt = kt + TILE_BYTES;
             // ---- S^T: 64 keys x 32 queries as two 32x32 blocks -----------------------------------
+            // The two 32-key halves advance together, their K operands requested two k-steps ahead: an
+            // LDS read needs about two MFMA times to come back, and two chains never wait on each other.
             f32x16 sacc[2];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[j][i] = 0.f;
+            bf16x8 ka[3][2];
 #pragma unroll
-                for (int s = 0; s < KSTEPS; ++s) {
-                    const bf16x8 ka = *(const bf16x8 *)(kt + j * 32 * 256 + koff[s]);
-                    sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc[j], 0, 0, 0);
+            for (int s = 0; s < 2; ++s)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) ka[s][j] = *(const bf16x8 *)(kt + j * 32 * 256 + koff[s]);
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                if (s + 2 < KSTEPS) {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) ka[(s + 2) % 3][j] = *(const bf16x8 *)(kt + j * 32 * 256 + koff[s + 2]);
                 }
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s % 3][j], qreg[s], sacc[j], 0, 0, 0);
+            }
+            // keep that order: four reads ahead, then {two reads, two MFMAs} per k-step (left to itself the
+            // scheduler reuses one operand register set and waits for every read right after issuing it)
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+                if (s + 2 < KSTEPS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             }
             ASTAMP(3 + (kb - kb0) * 6);
             const int tbase = kb * TILE_KEYS;
