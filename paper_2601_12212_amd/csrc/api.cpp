@@ -108,8 +108,9 @@ int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq,
     const int S = max_chunks(V);
     const int St = dt::rows_chunks_per_row(V, dt::rows_topk_nl(V));
     // build: lane maxima + (max, sum) partials + merged top-k (values, ids) + lse
-    size_t build = topk_scratch(nullptr, total_rows, St).bytes + 2 * align_up((size_t)total_rows * DT_K_MAX * 4) +
-                   align_up((size_t)total_rows * 4);
+    const size_t state_rows = (size_t)batch * DT_STATE_ROWS;  // merged results: one block of rows per sequence
+    size_t build = topk_scratch(nullptr, total_rows, St).bytes + 2 * align_up(state_rows * DT_K_MAX * 4) +
+                   align_up(state_rows * 4);
     size_t accept = argmax_scratch(nullptr, (int64_t)batch * TT_cap, S).bytes + align_up((size_t)batch * TT_cap * 4);
     size_t attn = dt::attn_workspace_bytes(batch, TT_cap, Hq, D);
     size_t m = build > accept ? build : accept;
@@ -158,9 +159,11 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     char *wsd = (char *)ws;
     TopkScratch rs = topk_scratch(wsd, total_rows, S);
     size_t off = rs.bytes;
-    float *top_val = (float *)(wsd + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
-    int32_t *top_id = (int32_t *)(wsd + off); off += align_up((size_t)total_rows * DT_K_MAX * 4);
-    float *lse = (float *)(wsd + off); off += align_up((size_t)total_rows * 4);
+    // merged row results: sequence b's row r at row b * DT_STATE_ROWS + r, the layout the tree kernel reads
+    const size_t state_rows = (size_t)batch * DT_STATE_ROWS;
+    float *top_val = (float *)(wsd + off); off += align_up(state_rows * DT_K_MAX * 4);
+    int32_t *top_id = (int32_t *)(wsd + off); off += align_up(state_rows * DT_K_MAX * 4);
+    float *lse = (float *)(wsd + off); off += align_up(state_rows * 4);
     if (off > ws_bytes) return DT_ERR_WORKSPACE;
 
     dt::RowArgs a = {};
@@ -176,7 +179,7 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     if (e != hipSuccess) return hip_fail(e);
 
     dt::TreeArgs ta = {};
-    ta.batch = batch; ta.params = params; ta.V = V; ta.row_off = row_off; ta.root_token = root_token;
+    ta.batch = batch; ta.params = params; ta.V = V; ta.seq_rows = DT_STATE_ROWS; ta.root_token = root_token;
     ta.TT_cap = TT_cap; ta.top_val = top_val; ta.top_id = top_id; ta.lse = lse;
     ta.n_nodes = n_nodes; ta.tokens = tokens; ta.parents = parents; ta.depth = depth; ta.src_row = src_row;
     ta.score = score; ta.logp = logp; ta.anc_mask = (unsigned long long *)anc_mask;
@@ -297,7 +300,7 @@ int dt_expand_level(void *stream, int batch, int level, const dt_params *params,
     if (e != hipSuccess) return hip_fail(e);
 
     dt::TreeArgs ta = {};
-    ta.batch = batch; ta.params = params; ta.V = V; ta.row_off = nullptr; ta.seq_rows = DT_STATE_ROWS;
+    ta.batch = batch; ta.params = params; ta.V = V; ta.seq_rows = DT_STATE_ROWS;
     ta.TT_cap = TT_cap; ta.top_val = ls.top_val; ta.top_id = ls.top_id; ta.lse = ls.lse;
     ta.expand_level = level; ta.prefix_len = prefix_len; ta.n_expand = n_expand; ta.state_n_exp = ls.n_exp;
     ta.exp_token = exp_token; ta.exp_parent_slot = exp_parent_slot; ta.exp_row = exp_row; ta.exp_pos = exp_pos;
@@ -318,7 +321,7 @@ int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, cons
     if (V < 1 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
     LevelState ls = level_state((void *)state, batch);
     dt::TreeArgs ta = {};
-    ta.batch = batch; ta.params = params; ta.V = V; ta.row_off = nullptr; ta.seq_rows = DT_STATE_ROWS;
+    ta.batch = batch; ta.params = params; ta.V = V; ta.seq_rows = DT_STATE_ROWS;
     ta.root_token = root_token; ta.TT_cap = TT_cap; ta.top_val = ls.top_val; ta.top_id = ls.top_id; ta.lse = ls.lse;
     ta.n_nodes = n_nodes; ta.tokens = tokens; ta.parents = parents; ta.depth = depth; ta.src_row = src_row;
     ta.score = score; ta.logp = logp; ta.anc_mask = (unsigned long long *)anc_mask;

@@ -65,17 +65,16 @@ struct TreeArgs {
     int batch;
     const dt_params *params;
     int V;
-    const int64_t *row_off;
     const int32_t *root_token;
     int TT_cap;
-    const float *top_val;  // [total_rows, DT_K_MAX]
+    const float *top_val;  // [batch, seq_rows, DT_K_MAX]: row results of sequence b start at row b * seq_rows
     const int32_t *top_id;
     const float *lse;      // [total_rows]
     int32_t *n_nodes, *tokens, *parents, *depth, *src_row;
     float *score, *logp;
     unsigned long long *anc_mask;
-    // level-at-a-time build.  row_off == nullptr: sequence b's row results start at b * seq_rows.
     int64_t seq_rows;
+    // level-at-a-time build
     int expand_level;       // 0: whole tree; l > 0: only the set of level-l nodes to expand
     const int32_t *prefix_len;  // may be null (positions then count from 0)
     int32_t *n_expand, *state_n_exp, *exp_token, *exp_parent_slot, *exp_row, *exp_pos;  // [batch(, DT_K_MAX)]

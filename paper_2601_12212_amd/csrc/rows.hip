@@ -60,6 +60,7 @@ __device__ __forceinline__ RowMeta row_meta(const RowArgs &a, int64_t g) {
         int k = min(max(p.k, 1), min(DT_K_MAX, a.V));
         m.k = k;
         m.valid = (TT > 1) && (r < 1 + (d - 1) * k) && (g < a.row_off[lo + 1]);
+        m.out = (int64_t)lo * DT_STATE_ROWS + r;  // results in the sequence's own block of rows
     } else if (a.mode == ROWS_TARGET) {
         int b = (int)(g / a.TT_cap), i = (int)(g % a.TT_cap);
         m.k = 1;

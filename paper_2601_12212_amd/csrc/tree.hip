@@ -420,14 +420,27 @@ __device__ __forceinline__ int level_choose(const u32 *key, const int *rank, int
 
 __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
     const int b = blockIdx.x, tid = threadIdx.x;
-    const dt_params prm = a.params[b];
-    const int TT = min(max(prm.TT, 1), a.TT_cap), d = min(max(prm.d, 1), DT_D_MAX);
-    const int k = min(max(prm.k, 1), min(DT_K_MAX, a.V));
-    const int64_t r0 = a.row_off ? a.row_off[b] : (int64_t)b * a.seq_rows;
-    const int xl = a.expand_level;  // > 0: only the nodes of level xl that are expanded next
+    // Row results of sequence b: rows b * seq_rows .. (the same block layout for the one-shot build and
+    // the level-at-a-time state), so nothing about them depends on the sequence's parameters.  The first
+    // 64 rows are requested before the parameters have arrived: one trip to memory instead of two.
+    const int64_t r0 = (int64_t)b * a.seq_rows;
     const float *tv = a.top_val + r0 * DT_K_MAX;
     const int32_t *ti = a.top_id + r0 * DT_K_MAX;
     const float *lse = a.lse + r0;
+    constexpr int EARLY = 4;  // entries per thread read ahead: rows 0 .. EARLY * TREE_NT / DT_K_MAX - 1
+    float ev[EARLY], el[EARLY];
+    int et[EARLY];
+#pragma unroll
+    for (int j = 0; j < EARLY; ++j) {
+        const int e = tid + j * TREE_NT;  // entry (row e / 32, rank e % 32)
+        ev[j] = tv[e];
+        et[j] = ti[e];
+        el[j] = lse[e / DT_K_MAX];
+    }
+    const dt_params prm = a.params[b];
+    const int TT = min(max(prm.TT, 1), a.TT_cap), d = min(max(prm.d, 1), DT_D_MAX);
+    const int k = min(max(prm.k, 1), min(DT_K_MAX, a.V));
+    const int xl = a.expand_level;  // > 0: only the nodes of level xl that are expanded next
     const int64_t o = (int64_t)b * a.TT_cap;
     const PoolShape ps = pool_shape(k);
     const int kk = k * k;
@@ -454,26 +467,30 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
         if (tid == 0) a.n_nodes[b] = 1;
         return;
     }
-    // candidates through level d, or through level xl when only that level's choice is wanted (the
-    // rows of deeper levels do not exist yet)
-    const int P = xl > 0 ? k + (xl - 1) * kk : k + (d - 1) * kk;
-    // Every candidate's own log-probability is known up front: the draft row that would
+    // Candidates through level d, or through level xl when only that level's choice is wanted (the
+    // rows of deeper levels do not exist yet).  Every candidate's own log-probability is known up front: the draft row that would
     // produce pool index p is fixed by p alone (only its parent is decided later).  Park
     // lp in the score array; the level loop turns it into the cumulative score in place.
-    for (int p = tid; p < P; p += TREE_NT) {
-        const Decoded dc = decode(p, ps);
-        const float v = tv[dc.row * DT_K_MAX + dc.rank];
-        const int token = ti[dc.row * DT_K_MAX + dc.rank];
-        const float own = v - lse[dc.row];
-        const float lp = v > -INFINITY ? own : -INFINITY;
-        S.score[p] = lp;
-        S.lp[p] = own;
-        S.tok[p] = token;
-        S.node[p] = -1;
-        S.slot[p] = -1;
-        if (p < 64) S.key[1][p] = p < k ? score_key(lp) : 0u;  // level 1 is chosen first
-    }
-    if (P < 64) for (int p = P + tid; p < 64; p += TREE_NT) S.key[1][p] = 0u;
+    // Entry (row, rank) with rank < k is candidate p = rank (row 0) or k + (row - 1) k + rank.
+    const int R = xl > 0 ? 1 + (xl - 1) * k : 1 + (d - 1) * k;  // rows that hold candidates
+    auto place = [&](int e, float v, int token, float row_lse) {
+        const int row = e / DT_K_MAX, rank = e % DT_K_MAX;
+        if (row < R && rank < k) {
+            const int p = row == 0 ? rank : k + (row - 1) * k + rank;
+            const float own = v - row_lse;
+            const float lp = v > -INFINITY ? own : -INFINITY;
+            S.score[p] = lp;
+            S.lp[p] = own;
+            S.tok[p] = token;
+            S.node[p] = -1;
+            S.slot[p] = -1;
+            if (row == 0) S.key[1][p] = score_key(lp);  // level 1 is chosen first
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < EARLY; ++j) place(tid + j * TREE_NT, ev[j], et[j], el[j]);
+    for (int e = tid + EARLY * TREE_NT; e < R * DT_K_MAX; e += TREE_NT) place(e, tv[e], ti[e], lse[e / DT_K_MAX]);
+    if (tid < 64 && tid >= k) S.key[1][tid] = 0u;
     for (int t = tid; t < COUNT_MAX; t += TREE_NT) S.rank[0][t] = 0;
     __syncthreads();
     STAMP(1);
