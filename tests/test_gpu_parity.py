@@ -318,6 +318,31 @@ def test_exact_score_ties_across_rows_go_to_the_lowest_pool_index():
         assert_tree_equal(st.tree(0), want, "ties V=%d TT=%d d=%d k=%d" % (V, TT, d, k))
 
 
+@pytest.mark.parametrize("V,sigma,TT,d,k", [(2000, 0.02, 100, 4, 12),      # 144 level-2 scores inside one bucket
+                                             (128256, 0.02, 40, 8, 3),     # the cut among 54 scores below -32
+                                             (128256, 0.02, 60, 8, 4),     # 96 scores below -32
+                                             (3000, 0.3, 128, 8, 16)])     # pool of 1808, crowded deep levels
+def test_nearly_flat_rows_crowd_the_score_buckets(V, sigma, TT, d, k):
+    """Draft rows that are almost flat give every candidate of a level nearly the same score: the rerank then
+    finds its cut inside one crowded score bucket (or among the scores below the bucket range) and has to
+    order distinct, close keys exactly."""
+    from paper_2601_12212_amd.step import Step
+    R = 1 + (d - 1) * k
+    for seed in range(20):
+        rows = (np.random.default_rng(seed).standard_normal((R, V)) * sigma).astype(np.float32)
+        want = ref.build_tree(rows, TT, d, k, 7)
+        if want["min_margin"] >= 1e-4:
+            break
+    else:
+        pytest.fail("margin guard: no acceptable seed")
+    st = Step([(TT, d, k)], [1], 4, 4, 64, V, dtype=torch.float32, TT_cap=128)
+    st.set_draft(0, rows)
+    st.set_root_token(0, 7)
+    st.build_tree()
+    torch.cuda.synchronize()
+    assert_tree_equal(st.tree(0), want, "flat rows V=%d TT=%d d=%d k=%d seed=%d" % (V, TT, d, k, seed))
+
+
 def test_masked_vocabulary_rows():
     """-inf logits (tokens that may never be proposed) and rows with fewer than k viable tokens."""
     cfg = small_cfg([(20, 3, 4)], [50], V=3000)
