@@ -61,6 +61,8 @@ def main():
                     help="also time the level-at-a-time build of the same tree (0: skip)")
     ap.add_argument("--commit-layers", type=int, default=32,
                     help="layers of the separately timed input update (0: skip it)")
+    ap.add_argument("--read-ceiling-mb", type=int, default=2048,
+                    help="size of the read-only pass that measures what a plain stream reaches here (0: skip)")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="also run a plain device copy of this many MB (a kernel of known traffic, for scaling "
                          "rocprofv3 --pmc FETCH_SIZE/WRITE_SIZE readings)")
@@ -215,6 +217,28 @@ def main():
                           % (P, R))
     roofline["traffic_source"] = os.path.relpath(pmc_path, ROOT) if traffic else None
     roofline_all = [roof(n) for n in sorted(with_bytes, key=lambda n: -kbytes[n])]
+
+    # ---- what a plain read-only pass reaches on this machine (context for the fractions of the 8 TB/s
+    #      peak): torch's row-wise maximum of a [4096, n] fp32 matrix of 2 GiB, far more than the 256 MB
+    #      last-level cache (the fastest of torch's plain reductions here; its sum reaches 4.0 TB/s) ------
+    ceiling = None
+    if args.read_ceiling_mb > 0:
+        probe = torch.ones((4096, args.read_ceiling_mb * (1 << 20) // 4 // 4096), dtype=torch.float32, device="cuda")
+        best = None
+        for _ in range(6):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            probe.amax(dim=1)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None or ms < best else best
+        ceiling = {"gbps": round(probe.numel() * 4 / (best * 1e-3) / 1e9, 1), "bytes": probe.numel() * 4,
+                   "how": "torch.amax(dim=1) over a [4096, n] fp32 matrix, best of 6, torch events"}
+        del probe
+        log("  read-only pass over %d MiB: %.0f GB/s" % (args.read_ceiling_mb, ceiling["gbps"]))
+        for r in [roofline] + roofline_all:
+            r["frac_of_read_ceiling"] = round(r["achieved"] / ceiling["gbps"], 4)
 
     # ---- the input update that follows the step (not part of the timed step): all layers' K/V rows of
     #      the accepted paths appended to the caches; timed on its own with dispatch-attached events ----
@@ -438,6 +462,7 @@ def main():
         "attention_layers_graph": layers_graph,
         "roofline": roofline,
         "roofline_all_streams": roofline_all,
+        "hbm_read_ceiling": ceiling,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
