@@ -7,11 +7,13 @@
 //    a larger key, the work split over the waves by (64 candidates) x (a slice of the others), the
 //    others read as LDS broadcasts.  Every wave then forms the chosen set by itself from the partial
 //    counts, so the next level's scores follow without another barrier.
-//  * Everything else (larger levels, the rerank over the pool, exact ties that straddle a cut) takes a
-//    radix selection over the order-preserving integer image of the score: four 8-bit digits, one LDS
-//    histogram and one barrier per digit, every wave scanning the 256 bins by itself; then one
-//    workgroup-wide prefix count hands out positions in pool-index order (of equal keys the lowest
-//    indices first).
+//  * Everything else (larger levels, the rerank over the pool, exact ties that straddle a cut) is cut by
+//    score buckets: one LDS histogram over floor(-8 score) and one scan name the bucket that holds the
+//    cut, the few candidates inside it rank themselves one against the other, everything in a better
+//    bucket is taken; one workgroup-wide prefix count hands out positions in pool-index order (of equal
+//    keys the lowest indices first).  A bucket too crowded for that goes through a radix selection over
+//    the order-preserving integer image of the score (four 8-bit digits, one histogram and one barrier
+//    per digit, every wave scanning the 256 bins by itself).
 #include "common.hpp"
 #include "kernels.hpp"
 
