@@ -299,6 +299,46 @@ def test_all_layers_attention_under_one_graph():
         (torch.ones(1000, device="cuda") * 3).sum().item()
 
 
+@pytest.mark.parametrize("ci,samples", [(2, 200), (4, 24)])
+def test_whole_step_replayed_from_a_graph_matches_the_oracle(ci, samples):
+    # the launch configuration bench.py times: the three calls of the step captured once as a HIP graph and
+    # replayed, at the full size of the configuration; every replay (outputs wiped before it, eager work
+    # after it) must give the oracle's tree, acceptance and (sampled) attention
+    case = oracle_case(ci)
+    c = case.cfg
+    st = make_step(case).prepare()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        st.run_prepared(side.cuda_stream)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            st.run_prepared(side.cuda_stream)
+    for rep in range(3):
+        for t in (st.n_nodes, st.tokens, st.parents, st.depth, st.src_row, st.accept_len, st.best_node, st.path_nodes,
+                  st.out_tokens):
+            t.fill_(-7)
+        st.out.fill_(3.0)
+        st.anc_mask.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(rep)
+        for b in range(c.B):
+            tag = "%s seq %d replay %d" % (c.name, b, rep)
+            got = st.tree(b)
+            assert_tree_equal(got, case.trees[b], tag)
+            assert_accept_equal(st.accepted(b), case.accepts[b], tag)
+            q, kt, vt, kp, vp = dt_synth.qkv(c, b)
+            N = got["n_nodes"]
+            pick = np.stack([rng.integers(0, N, samples), rng.integers(0, c.Hq, samples)], 1)
+            want = ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, case.trees[b]["anc_mask"], st.scale, samples=pick)
+            out = st.attention_out(b)
+            err = max(np.abs(out[i, h] - want[r]).max() for r, (i, h) in enumerate(pick))
+            assert err <= 2e-2, (tag, "attention max-abs", err)
+        (torch.ones(1000, device="cuda") * 3).sum().item()
+
+
 def test_exact_score_ties_across_rows_go_to_the_lowest_pool_index():
     # identical draft rows: every candidate of a level has exactly the same score on both sides, so the
     # level cuts and the rerank are decided by the tie-break alone (the margin guard would reject these
