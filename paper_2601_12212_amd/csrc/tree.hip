@@ -220,7 +220,8 @@ __device__ __forceinline__ int block_positions(int C, u32 flags, TreeLds &S, F f
 // bucket is taken.  A bucket with more than BUCKET_CAP candidates (many equal scores, or scores below
 // -32) goes through the radix selection instead.  CT: candidates per thread when known at compile time
 // (their scores then stay in registers), 0: any number up to 32.
-__device__ __forceinline__ int score_bucket(float sc) { return min(max((int)(sc * -8.0f), 0), 255); }
+// (clamped as a float first: converting a float beyond the int range would be undefined)
+__device__ __forceinline__ int score_bucket(float sc) { return max((int)fminf(sc * -8.0f, 255.0f), 0); }
 __device__ __forceinline__ u64 member_key(u32 key, int i) { return ((u64)key << 32) | (u32)(0x7FFFFFFF - i); }
 
 template <int CT, typename F>
