@@ -521,19 +521,31 @@ __global__ __launch_bounds__(256) void attn_gang_combine_kernel(AttnArgs a, int 
         const int64_t slot = (int64_t)h * P + base + j * cls + tile;
         return (slot * 2 + (csb < j * Tc ? 0 : 1)) * ATT_MTILE + rit;
     };
-    float M = -INFINITY;
-    for (int j = jf; j <= jl; ++j) M = fmaxf(M, part.ml[prow(j)].x);
-    const float Mu = M == -INFINITY ? 0.f : M;
+    // Four partials at a time, every load asked for before any is used (a load that waited for the
+    // previous partial's weight would make the kernel one memory round trip per partial long); the
+    // running maximum moves as in the attention kernel itself.
+    float M = -INFINITY, l = 0.f;
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    float l = 0.f;
-    for (int j = jf; j <= jl; ++j) {
-        const int64_t pr = prow(j);
-        const float2 ml = part.ml[pr];
-        if (ml.y <= 0.f) continue;
-        const float wgt = __builtin_amdgcn_exp2f((ml.x - Mu) * c);
-        const float4 o = *(const float4 *)(part.o + pr * D + c4 * 4);
-        acc.x += o.x * wgt; acc.y += o.y * wgt; acc.z += o.z * wgt; acc.w += o.w * wgt;
-        l += ml.y * wgt;
+    for (int j0 = jf; j0 <= jl; j0 += 4) {
+        float2 ml[4];
+        float4 o[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int64_t pr = prow(min(j0 + u, jl));
+            ml[u] = part.ml[pr];
+            o[u] = *(const float4 *)(part.o + pr * D + c4 * 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (j0 + u > jl || !(ml[u].y > 0.f)) continue;  // a range whose keys were all hidden weighs nothing
+            const float M2 = fmaxf(M, ml[u].x);
+            const float keep = __builtin_amdgcn_exp2f((M - M2) * c);  // first partial: exp2(-inf) = 0
+            const float wgt = __builtin_amdgcn_exp2f((ml[u].x - M2) * c);
+            acc.x = acc.x * keep + o[u].x * wgt; acc.y = acc.y * keep + o[u].y * wgt;
+            acc.z = acc.z * keep + o[u].z * wgt; acc.w = acc.w * keep + o[u].w * wgt;
+            l = l * keep + ml[u].y * wgt;
+            M = M2;
+        }
     }
     const float inv = l > 0.f ? 1.0f / l : 0.f;
     bf16x4 o4;
