@@ -32,7 +32,7 @@ __device__ __forceinline__ void load_logits8(const void *row, int dtype, int id,
 // Inverse-CDF sample of softmax(row g / T) at the uniform u, by the whole workgroup (256 threads; contains
 // barriers).  The row kernel left (max, sum exp((x - max)/T)) of every chunk of the row: their masses
 // relative to the row maximum Mrow, accumulated in double, locate the chunk that holds the crossing; only
-// that chunk is read again (thread t owns `epl` consecutive ids), element masses in fp32, running sums in
+// that chunk is read again (thread t owns `epl` <= 32 consecutive ids), element masses in fp32, running sums in
 // double.  The comparison is "cumulative mass > u * total", the un-normalised form of the cdf > u test;
 // it differs from an all-double evaluation by ~1e-6 in probability.  The result is left in *s_out.
 __device__ __forceinline__ void sample_row_block(const AcceptArgs &a, int64_t g, float Mrow, float u, float inv_t,
@@ -62,13 +62,16 @@ __device__ __forceinline__ void sample_row_block(const AcceptArgs &a, int64_t g,
     const int lo = cstar * a.chunk_elems, hi = min(a.V, lo + a.chunk_elems);
     const int id0 = lo + tid * epl;
     const bool vec_ok = ((uintptr_t)row & 15) == 0;  // id0 is a multiple of 8
-    double mine = 0.0;
-    for (int e0 = 0; e0 < epl; e0 += 8) {
-        float x[8];
-        load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
+    // a thread owns at most 32 entries (four octets): all asked for at once and kept, the thread that
+    // holds the crossing walks its registers and nothing is read twice
+    float x[4][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) mine += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
-    }
+    for (int j = 0; j < 4; ++j) load_logits8(row, a.dtype, id0 + 8 * j, 8 * j < epl ? hi : 0, vec_ok, x[j]);
+    double mine = 0.0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mine += (double)__builtin_amdgcn_exp2f((x[j][e] - Mrow) * cexp);  // past epl: + 0
     double incl = mine;  // inclusive scan over the lanes of the wave
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
@@ -96,15 +99,13 @@ __device__ __forceinline__ void sample_row_block(const AcceptArgs &a, int64_t g,
         double cm = run + incl - mine;
         int id = min(id0 + epl, hi) - 1;
         bool done = false;
-        for (int e0 = 0; e0 < epl && !done; e0 += 8) {
-            float x[8];
-            load_logits8(row, a.dtype, id0 + e0, hi, vec_ok, x);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                cm += (double)__builtin_amdgcn_exp2f((x[e] - Mrow) * cexp);
-                if (!done && cm > target_mass) { id = id0 + e0 + e; done = true; }
+                cm += (double)__builtin_amdgcn_exp2f((x[j][e] - Mrow) * cexp);
+                if (!done && cm > target_mass) { id = id0 + 8 * j + e; done = true; }
             }
-        }
         *s_out = id;
     }
     __syncthreads();
@@ -175,15 +176,26 @@ __global__ __launch_bounds__(256) void accept_kernel(AcceptArgs a) {
             const int64_t g = o + min(i, N - 1);
             u64 best = 0ull;
             float M = -INFINITY, Ssum = 0.f;
-            for (int c = part; c < S; c += 4) {
-                const u64 key = a.part_keys[g * S + c];
-                best = key > best ? key : best;
-                if (stochastic) {
-                    const float2 p = a.part_ms[g * S + c];
-                    const float M2 = fmaxf(M, p.x);
-                    if (M2 != -INFINITY)
-                        Ssum = Ssum * __builtin_amdgcn_exp2f((M - M2) * cexp) + p.y * __builtin_amdgcn_exp2f((p.x - M2) * cexp);
-                    M = M2;
+            for (int c0 = part; c0 < S; c0 += 16) {  // four chunks per trip to memory
+                u64 key[4];
+                float2 p[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = min(c0 + 4 * u, S - 1);  // past the end: the last chunk again, ignored below
+                    key[u] = a.part_keys[g * S + c];
+                    if (stochastic) p[u] = a.part_ms[g * S + c];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (c0 + 4 * u >= S) continue;
+                    best = key[u] > best ? key[u] : best;
+                    if (stochastic) {
+                        const float M2 = fmaxf(M, p[u].x);
+                        if (M2 != -INFINITY)
+                            Ssum = Ssum * __builtin_amdgcn_exp2f((M - M2) * cexp) +
+                                   p[u].y * __builtin_amdgcn_exp2f((p[u].x - M2) * cexp);
+                        M = M2;
+                    }
                 }
             }
 #pragma unroll
