@@ -25,8 +25,15 @@ __device__ unsigned long long dt_dbg_attn[64];
 extern "C" int dt_debug_attn_stamps(unsigned long long *out) {
     return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_attn), sizeof(unsigned long long) * 64);
 }
+// life of every workgroup of the balanced large-batch kernel: (start, end) on the 100 MHz counter, hardware id
+__device__ unsigned long long dt_dbg_wg[4096][3];
+extern "C" int dt_debug_attn_wgs(unsigned long long *out) {
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_wg), sizeof(unsigned long long) * 4096 * 3);
+}
+#define WGSTAMP(k) do { if (threadIdx.x == 0) { const int wg_ = blockIdx.y * gridDim.x + blockIdx.x; if (wg_ < 4096) { dt_dbg_wg[wg_][k] = __builtin_amdgcn_s_memrealtime(); if (k) dt_dbg_wg[wg_][2] = ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) << 32) | __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11)); } } } while (0)
 #else
 #define ASTAMP(i) do {} while (0)
+#define WGSTAMP(k) do {} while (0)
 #endif
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -445,6 +452,7 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void attn_gang_kernel(AttnArgs a, int P, int mt_max, GangPartial part) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
     const int h = blockIdx.x, y = blockIdx.y, lane = threadIdx.x & 63;
+    WGSTAMP(0);
     const GangPlan p = gang_plan(a, P, mt_max, lane);
     // class, gang and row tile of slot y
     int base = 0, cls = 0;
@@ -497,6 +505,7 @@ __global__ __launch_bounds__(256, 2) void attn_gang_kernel(AttnArgs a, int P, in
         dst.ml = part.ml + (slot * 2 + which) * ATT_MTILE;
         tile_segment<D>(a, s_dyn, h, b, tile * ATT_MTILE, kb0, kb1, dst);
     }
+    WGSTAMP(1);
 }
 
 // Merge of the partials of the balanced schedule: one thread per (row, 4 output columns) of
