@@ -29,30 +29,46 @@ __global__ __launch_bounds__(256) void policy_layer1_kernel(PolicyArgs a) {
     __shared__ float s_x[POLICY_BCH][POLICY_KS];
     __shared__ float s_acc[POLICY_BCH][128];
     __shared__ int s_need[POLICY_BCH];
+    // This thread's weights do not depend on the batch: asked for first, so that the one trip to memory
+    // they cost overlaps the cache flags and the inputs (rows past F: the last row again, zeroed at use).
+    float wreg[POLICY_KS / 2];
+#pragma unroll
+    for (int i = 0; i < POLICY_KS / 2; ++i) wreg[i] = a.W1[(int64_t)min(k0 + part * half + i, a.F - 1) * H + o];
     for (int b0 = 0; b0 < a.batch; b0 += POLICY_BCH) {
         const int nb = min(POLICY_BCH, a.batch - b0);
+        // the inputs are read before the flags that say which sequences need them are back
+        float xv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = tid + u * (int)blockDim.x;
+            xv[u] = 0.f;
+            if (i < nb * POLICY_KS) {
+                const int64_t idx = (int64_t)(b0 + i / POLICY_KS) * a.feat_stride + min(k0 + i % POLICY_KS, a.F - 1);
+                xv[u] = a.feat_dtype == DT_BF16 ? bf16_bits_to_float(((const uint16_t *)a.feat)[idx])
+                                                : ((const float *)a.feat)[idx];
+            }
+        }
         if (tid < POLICY_BCH) s_need[tid] = tid < nb && policy_needed(a, b0 + tid);
         __syncthreads();
         bool any = false;
         for (int j = 0; j < nb; ++j) any = any || s_need[j];
         if (any) {
-            for (int i = tid; i < nb * POLICY_KS; i += blockDim.x) {
-                const int j = i / POLICY_KS, kk = i % POLICY_KS, k = k0 + kk;
-                float v = 0.f;
-                if (s_need[j] && k < a.F) {
-                    const int64_t idx = (int64_t)(b0 + j) * a.feat_stride + k;
-                    v = a.feat_dtype == DT_BF16 ? bf16_bits_to_float(((const uint16_t *)a.feat)[idx])
-                                                : ((const float *)a.feat)[idx];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = tid + u * (int)blockDim.x;
+                if (i < nb * POLICY_KS) {
+                    const int j = i / POLICY_KS, kk = i % POLICY_KS;
+                    s_x[j][kk] = (s_need[j] && k0 + kk < a.F) ? xv[u] : 0.f;
                 }
-                s_x[j][kk] = v;
             }
             __syncthreads();
             float acc[POLICY_BCH];
 #pragma unroll
             for (int j = 0; j < POLICY_BCH; ++j) acc[j] = 0.f;
-            for (int kk = part * half; kk < (part + 1) * half; ++kk) {
-                const int k = k0 + kk;
-                const float w = k < a.F ? a.W1[(int64_t)k * H + o] : 0.f;
+#pragma unroll
+            for (int i = 0; i < POLICY_KS / 2; ++i) {
+                const int kk = part * half + i;
+                const float w = k0 + kk < a.F ? wreg[i] : 0.f;
 #pragma unroll
                 for (int j = 0; j < POLICY_BCH; ++j) acc[j] = fmaf(w, s_x[j][kk], acc[j]);
             }
@@ -68,15 +84,15 @@ __global__ __launch_bounds__(256) void policy_layer1_kernel(PolicyArgs a) {
     }
 }
 
-// s + sum_i x[i] * w[i * stride], i = 0 .. n-1 in order, n a multiple of 16: the sixteen weights of a
-// batch are requested together, so their latencies overlap.
+// s + sum_i x[i] * w[i * stride], i = 0 .. n-1 in order, n a multiple of 64: the sixty-four weights of a
+// batch are requested together, so a layer of 128 inputs costs two trips to memory and not one per few terms.
 __device__ __forceinline__ float dot_strided(float s, const float *x, const float *w, int n, int stride) {
-    for (int i0 = 0; i0 < n; i0 += 16) {
-        float wv[16];
+    for (int i0 = 0; i0 < n; i0 += 64) {
+        float wv[64];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) wv[i] = w[(int64_t)(i0 + i) * stride];
+        for (int i = 0; i < 64; ++i) wv[i] = w[(int64_t)(i0 + i) * stride];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s = fmaf(x[i0 + i], wv[i], s);
+        for (int i = 0; i < 64; ++i) s = fmaf(x[i0 + i], wv[i], s);
     }
     return s;
 }
@@ -93,17 +109,17 @@ __global__ __launch_bounds__(256) void policy_head_kernel(PolicyArgs a) {
     if (need) {
         {
             // the slices' partial sums, in a fixed order: 256 / H threads per output take consecutive runs
-            // of slices (eight requests in flight each), the runs are added up in order
+            // of slices (thirty-two requests in flight each), the runs are added up in order
             const int o = tid % H, r = tid / H, R = 256 / H;
             const int per = (a.S + R - 1) / R, s0 = r * per, s1 = min(a.S, s0 + per);
             float s = 0.f;
-            for (int sl = s0; sl < s1; sl += 8) {
-                float v[8];
+            for (int sl = s0; sl < s1; sl += 32) {
+                float v[32];
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    v[i] = sl + i < s1 ? a.partial[((int64_t)(sl + i) * a.batch + b) * H + o] : 0.f;
+                for (int i = 0; i < 32; ++i)
+                    v[i] = a.partial[((int64_t)min(sl + i, s1 - 1) * a.batch + b) * H + o];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) s += v[i];
+                for (int i = 0; i < 32; ++i) s += sl + i < s1 ? v[i] : 0.f;
             }
             s_run[r][o] = s;
         }
