@@ -16,14 +16,15 @@ def toy_logits(seed, string, V, sigma=2.0):
 
 
 def brute_tree(draft_fn, V, TT, d, k):
-    """Returns (kept strings in level-major order of their discovery, score dict)."""
+    """Returns (set of kept strings, cumulative score of every candidate string, own log-probability
+    of every candidate string = its logit minus the log-sum-exp of the row that proposed it)."""
     def topk(string):
         x = draft_fn(string).astype(np.float64)
         lse = logsumexp(x)
         order = sorted(range(V), key=lambda t: (-x[t], t))[:k]
         return [(t, x[t] - lse) for t in order if x[t] > -np.inf]
 
-    score = {}
+    score, own = {}, {}
     levels = []
     frontier = [()]          # strings to expand at this level
     for level in range(1, d + 1):
@@ -32,6 +33,7 @@ def brute_tree(draft_fn, V, TT, d, k):
             for t, lp in topk(s):
                 c = s + (t,)
                 score[c] = (score[s] if s else 0.0) + lp
+                own[c] = lp
                 cands.append(c)
         levels.append(cands)
         if not cands:
@@ -41,7 +43,7 @@ def brute_tree(draft_fn, V, TT, d, k):
     everyone = [c for lv in levels for c in lv]
     ranked = sorted(everyone, key=lambda c: -score[c])
     kept = set(ranked[:max(TT - 1, 0)])
-    return kept, score
+    return kept, score, own
 
 
 def brute_frontiers(draft_fn, V, d, k):
@@ -90,3 +92,40 @@ def brute_greedy_accept(strings, target_fn):
             if len(s) > len(best):
                 best = s
     return best, amax(best)
+
+
+def brute_min_margin(draft_fn, V, TT, d, k):
+    """Smallest score gap between a chosen and a passed-over candidate that were proposed by different
+    token strings (different draft rows), over every cut of the build: the choice of the k strings to expand
+    at levels 1..d-1 and the final cut to TT-1.  float64 scores on token strings; inf if no such pair."""
+    def topk(string):
+        x = draft_fn(string).astype(np.float64)
+        lse = logsumexp(x)
+        order = sorted(range(V), key=lambda t: (-x[t], t))[:k]
+        return [(t, x[t] - lse) for t in order if x[t] > -np.inf]
+
+    def gap(chosen, passed):
+        g = [score[a] - score[b] for a in chosen for b in passed if a[:-1] != b[:-1]]
+        return min(g) if g else np.inf
+
+    score = {(): 0.0}
+    margin = np.inf
+    everyone = []
+    frontier = [()]
+    for level in range(1, d + 1):
+        cands = [s + (t,) for s in frontier for t, _ in topk(s)]
+        for s in frontier:
+            for t, lp in topk(s):
+                score[s + (t,)] = score[s] + lp
+        everyone += cands
+        if level == d or TT == 1:
+            break
+        ranked = sorted(cands, key=lambda c: -score[c])
+        margin = min(margin, gap(ranked[:k], ranked[k:]))
+        frontier = ranked[:k]
+        if not frontier:
+            break
+    if TT > 1:
+        ranked = sorted(everyone, key=lambda c: -score[c])
+        margin = min(margin, gap(ranked[:TT - 1], ranked[TT - 1:]))
+    return margin

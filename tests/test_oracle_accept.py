@@ -324,3 +324,90 @@ def test_sampled_verification_with_a_one_hot_target_is_greedy():
         s = ref.accept(ref.SAMPLED, target, t["tokens"], t["parents"], t["depth"], temperature=1.0, seed=1, step=step)
         assert s["accept_len"] == g["accept_len"] and np.array_equal(s["out_tokens"], g["out_tokens"])
         assert np.array_equal(s["node_argmax"], g["node_argmax"])
+
+
+# ---------------------------------------------- the decision margins the parity tests rely on
+
+def _small_tree_and_target(seed, V=9, TT=14, d=3, k=3):
+    t, strs, target, _ = tree_and_target(seed, V, TT, d, k)
+    return t, target
+
+
+def test_stochastic_min_margin_is_recomputed_in_float64():
+    """min over nodes with alpha < 1 of |u - alpha|, and the distance of the bonus uniform to the edges of its
+    CDF bin (lower edge only when the bonus is not token 0): numpy/scipy float64 from the same uniforms."""
+    seen_alpha, seen_bonus = 0, 0
+    for seed in range(30):
+        t, target = _small_tree_and_target(seed)
+        T = float(np.float32([0.7, 1.0, 1.9][seed % 3]))     # the temperature crosses the C interface as a float
+        a = ref.accept(ref.STOCHASTIC, target, t["tokens"], t["parents"], t["depth"], logp=t["logp"], temperature=T,
+                       seed=11, step=seed, seq=2)
+        lpT = log_softmax(target.astype(np.float64) / T, axis=1)
+        m_alpha = np.inf
+        acc = [True]
+        for i in range(1, t["n_nodes"]):
+            alpha = min(1.0, float(np.exp(lpT[t["parents"][i], t["tokens"][i]] - np.float64(t["logp"][i]))))
+            u = ref.uniform(11, seed, 2, i)
+            acc.append(u < alpha)
+            if alpha < 1.0:
+                m_alpha = min(m_alpha, abs(u - alpha))
+        assert a["accepted"].tolist() == acc
+        cdf = np.cumsum(np.exp(lpT[a["best_node"]]))
+        u = ref.uniform(11, seed, 2, 0xFFFFFFFF)
+        bonus = int(np.searchsorted(cdf, u, side="right"))
+        assert a["out_tokens"][a["accept_len"]] == bonus
+        m_bonus = cdf[bonus] - u
+        if bonus > 0:
+            m_bonus = min(m_bonus, u - cdf[bonus - 1])
+        want = min(m_alpha, m_bonus)
+        assert abs(a["min_margin"] - want) <= 1e-6 * want + 1e-12, (seed, a["min_margin"], want)
+        seen_alpha += m_alpha < m_bonus
+        seen_bonus += m_bonus < m_alpha
+    assert seen_alpha > 3 and seen_bonus > 3          # both terms decide the minimum in some case
+
+
+def test_sampled_node_margins_and_min_margin_are_recomputed_in_float64():
+    for seed in range(30):
+        t, target = _small_tree_and_target(seed)
+        T = float(np.float32([0.7, 1.0, 1.9][seed % 3]))
+        a = ref.accept(ref.SAMPLED, target, t["tokens"], t["parents"], t["depth"], temperature=T, seed=12, step=seed, seq=1)
+        p = np.exp(log_softmax(target.astype(np.float64) / T, axis=1))
+        want_node, draw = [], []
+        for i in range(t["n_nodes"]):
+            cdf = np.cumsum(p[i])
+            u = ref.uniform(12, seed, 1, 0x80000000 + int(t["depth"][i]))
+            y = int(np.searchsorted(cdf, u, side="right"))
+            draw.append(y)
+            m = cdf[y] - u
+            if y > 0:
+                m = min(m, u - cdf[y - 1])
+            want_node.append(m)
+        assert a["node_argmax"].tolist() == draw
+        assert np.allclose(a["node_margin"], want_node, rtol=1e-6, atol=1e-12)
+        # the sequence's margin: the nodes whose draw decides the output (all ancestors accepted)
+        ok = [True]
+        for i in range(1, t["n_nodes"]):
+            ok.append(ok[t["parents"][i]] and t["tokens"][i] == draw[t["parents"][i]])
+        want = min(m for m, o in zip(want_node, ok) if o)
+        assert abs(a["min_margin"] - want) <= 1e-6 * want + 1e-12
+        assert want >= min(want_node)
+
+
+def test_a_uniform_of_exactly_zero_skips_tokens_without_mass():
+    """u = 0 is reachable (probability 2^-24 per draw).  The inverse CDF is "first id with cdf > u", so tokens of
+    zero probability in front of the first token with mass are never drawn (a ">=" test would draw token 0)."""
+    BONUS_STEP, DEPTH0_STEP = 657078, 2169497        # found by search; the asserts below re-check them
+    assert ref.uniform(0, BONUS_STEP, 0, 0xFFFFFFFF) == 0.0
+    assert philox_py([0xFFFFFFFF, 0, BONUS_STEP, 0], [0, 0])[0] >> 8 == 0
+    assert ref.uniform(0, DEPTH0_STEP, 0, 0x80000000) == 0.0
+    assert philox_py([0x80000000, 0, DEPTH0_STEP, 0], [0, 0])[0] >> 8 == 0
+    V = 6
+    target = np.array([[-np.inf, -np.inf, 0.5, 1.0, -np.inf, 0.0]], np.float32)
+    one = (np.array([0], np.int32), np.array([-1], np.int32), np.array([0], np.int32))
+    a = ref.accept(ref.STOCHASTIC, target, *one, logp=np.zeros(1, np.float32), seed=0, step=BONUS_STEP, seq=0)
+    assert a["out_tokens"][0] == 2
+    a = ref.accept(ref.SAMPLED, target, *one, seed=0, step=DEPTH0_STEP, seq=0)
+    assert a["out_tokens"][0] == 2 and a["node_argmax"][0] == 2
+    target[0, 0] = -3.0                               # token 0 with mass: u = 0 draws it
+    a = ref.accept(ref.STOCHASTIC, target, *one, logp=np.zeros(1, np.float32), seed=0, step=BONUS_STEP, seq=0)
+    assert a["out_tokens"][0] == 0

@@ -7,7 +7,7 @@ import pytest
 
 import dt_synth
 from oracle import ref
-from tests._brute import brute_frontiers, brute_tree, toy_logits
+from tests._brute import brute_frontiers, brute_min_margin, brute_tree, toy_logits
 from tests._drive import node_strings, rows_from_fn
 
 
@@ -64,13 +64,18 @@ def test_tree_matches_brute_force_on_strings(V, TT, d, k):
         fn = lambda s: toy_logits(seed * 1000 + V, s, V)
         rows = rows_from_fn(ref.build_tree, fn, V, d, k)
         t = ref.build_tree(rows, TT, d, k, 5)
-        kept, score = brute_tree(fn, V, TT, d, k)
+        kept, score, own = brute_tree(fn, V, TT, d, k)
         strs = node_strings(t)
-        assert strs[0] == () and t["tokens"][0] == 5
+        assert strs[0] == () and t["tokens"][0] == 5 and t["logp"][0] == 0.0 and t["score"][0] == 0.0
         assert set(strs[1:]) == kept
         assert len(strs) == len(set(strs))
         for i in range(1, t["n_nodes"]):
             assert abs(t["score"][i] - score[strs[i]]) < 1e-5
+            # the node's own log-probability (the P_d of the acceptance ratio): the brute force's logit minus
+            # the float64 log-sum-exp of the row of the node's string prefix, and the one float add per level
+            assert abs(t["logp"][i] - own[strs[i]]) < 2e-6 * max(1.0, abs(own[strs[i]]))
+            par = t["parents"][i]
+            assert t["score"][i] == np.float32(t["score"][par] + t["logp"][i])
             assert strs[t["parents"][i]] == strs[i][:-1]         # parent = string prefix
             assert t["depth"][i] == len(strs[i])
         check_invariants(t, TT, d, k)
@@ -231,3 +236,41 @@ def test_level_outputs_survive_a_rerank_that_drops_expanded_nodes_and_stop_witho
     rows2[1:1 + k] = -np.inf                                         # level-1 nodes propose nothing
     t = ref.build_tree(rows2, 40, d, k, with_levels=True)
     assert len(t["levels"][1]["tokens"]) == k and len(t["levels"][2]["tokens"]) == 0 and len(t["levels"][3]["tokens"]) == 0
+
+
+@pytest.mark.parametrize("V,TT,d,k", [(8, 4, 2, 2), (8, 7, 3, 2), (8, 12, 3, 3), (6, 5, 3, 3), (8, 30, 3, 3), (8, 3, 1, 3)])
+def test_min_margin_is_the_smallest_cross_row_gap_of_any_cut(V, TT, d, k):
+    """The decision margin the parity tests rely on: recomputed on token strings in float64 (every chosen /
+    passed-over pair of every cut, pairs proposed by the same string left out)."""
+    finite = 0
+    for seed in range(12):
+        fn = lambda s: toy_logits(300 + seed, s, V)
+        rows = rows_from_fn(ref.build_tree, fn, V, d, k)
+        got = ref.build_tree(rows, TT, d, k, 0)["min_margin"]
+        want = brute_min_margin(fn, V, TT, d, k)
+        if np.isinf(want):
+            assert np.isinf(got)
+        else:
+            assert abs(got - want) < 1e-5, (seed, got, want)
+            finite += 1
+    assert finite > 0 or d == 1            # d = 1: one row only, nothing crosses rows
+
+
+def test_min_margin_of_a_constructed_gap():
+    # two level-1 nodes, both expanded; their rows put exactly one known gap across the final cut
+    V, d, k = 4, 2, 2
+    rows = np.full((3, V), -30.0, np.float32)
+    rows[0, [0, 1]] = [0.0, 0.0]                 # children a=(0), b=(1): lp = -log 2 each (others negligible)
+    rows[1, [2, 3]] = [0.0, -1.0]                # under a: lp ~ -0.3133, -1.3133
+    rows[2, [2, 3]] = [0.0, -0.75]               # under b: lp ~ -0.3869, -1.1369
+    # pool scores: a, b = -0.693; (a,2) -1.006, (b,2) -1.080, (b,3) -1.830, (a,3) -2.006
+    t = ref.build_tree(rows, 5, d, k, 0)         # keeps a, b, (a,2), (b,2); passes over (b,3), (a,3)
+    assert sorted(node_strings(t)) == [(), (0,), (0, 2), (1,), (1, 2)]
+    from scipy.special import logsumexp
+    l0, l1, l2 = (logsumexp(rows[i].astype(np.float64)) for i in range(3))
+    kept = {"a2": -l0 + 0.0 - l1, "b2": -l0 + 0.0 - l2}
+    gone = {"a3": -l0 - 1.0 - l1, "b3": -l0 - 0.75 - l2}
+    # cross-row pairs only: (a2, b3), (b2, a3) -- and a/b (root row) against both
+    want = min(kept["a2"] - gone["b3"], kept["b2"] - gone["a3"], -l0 - gone["a3"], -l0 - gone["b3"])
+    assert abs(t["min_margin"] - want) < 1e-6
+    assert abs(want - (kept["b2"] - gone["b3"])) > 1e-3     # the same-row pair (b2, b3) would have been smaller: it is not counted
