@@ -9,7 +9,12 @@
  *
  * Conventions for every entry point
  *   - Returns DT_OK or a negative dt_status.  Never throws, aborts, allocates, frees or
- *     synchronises.  Arguments are validated on the host before anything is launched.
+ *     synchronises.  Arguments are validated on the host before anything is launched; that
+ *     includes the launch grids (see the limits below): a call that would need a grid the
+ *     hardware cannot take returns DT_ERR_LIMIT and launches nothing.
+ *   - One-time set-up per device: see dt_init().  Apart from that the library keeps no state
+ *     (the optional dt_profile_* timing aside) and its entry points may be called from several
+ *     threads, on different streams, as long as calls that share a workspace are ordered.
  *   - All tensor pointers are DEVICE pointers owned by the caller.  Scalars are host values.
  *   - `stream` is the caller's hipStream_t (as void*; NULL = the default stream).  Work is
  *     enqueued on it and the call returns immediately; outputs are valid once the stream
@@ -59,6 +64,18 @@ typedef enum {
     DT_ERR_HIP = -5          /* a HIP call failed; see dt_last_hip_error() */
 } dt_status;
 
+/*
+ * One-time set-up for the CURRENT device: asks the runtime for the device's number of compute
+ * units (launch shapes depend on it) and gives the kernels that use more than 64 KB of LDS
+ * leave to do so (hipFuncSetAttribute).  No allocation, no launch, no stream operation.
+ * Thread-safe and idempotent; every launching entry point does the same on its first call on a
+ * device, so calling dt_init() is optional -- but a caller that records its first call into a
+ * HIP graph, or calls from several threads at once at start-up, may prefer to have it done
+ * beforehand.  (The set-up calls are legal while a stream is being captured: they enqueue
+ * nothing.)  At most 64 devices per process.  Returns DT_OK or DT_ERR_HIP.
+ */
+int dt_init(void);
+
 const char *dt_status_string(int status);
 /* hipError_t of the last failing HIP call made by this library on this thread (0 if none). */
 int dt_last_hip_error(void);
@@ -80,7 +97,8 @@ int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq,
  *   top_id   [n_rows, k] int32 : their token ids; equal logits are ordered by ascending id
  *   lse      [n_rows]   float  : log sum_v exp(logits[r, v])
  * Slots beyond the number of finite entries of a row hold (-inf, -1).
- * Errors: k < 1 or k > min(DT_K_MAX, V) -> DT_ERR_LIMIT.
+ * Errors: k < 1 or k > min(DT_K_MAX, V) -> DT_ERR_LIMIT; V beyond 524,288 or more than 2^31 - 1
+ * (row, 8192-entry chunk) pairs in one call -> DT_ERR_LIMIT.
  */
 int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, int V, int64_t row_stride,
                  int k, float *top_val, int32_t *top_id, float *lse, void *ws, size_t ws_bytes);
@@ -94,7 +112,9 @@ int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, i
  * local row 1 + (l-1)*k + s is the next-token row of the s-th expanded node of level l
  * (l = 1..d-1), expanded nodes of a level being numbered in ascending pool index.
  * total_rows = row_off[batch] as a host value (sizes the launch; draft_logits holds that many rows,
- * all of which may be read, also those a sequence does not use).
+ * all of which may be read, also those a sequence does not use).  A sequence that owns fewer than
+ * 1 + (d-1)*k rows is built as if the missing rows held no viable token (all -inf): the nodes that
+ * would have been handed those rows get no children.
  *
  * Method.  Level-l candidates are the top-k tokens of every expanded level-(l-1) node;
  * score = score[parent] + (logit - lse of its row), one float add per level.  The k best
@@ -133,9 +153,11 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
  *   k_prefix[b], v_prefix[b] : device arrays (length batch) of device pointers; element
  *       (token, kv head, c) at token*kv_stride_tok + head*kv_stride_head + c (strides in elements)
  *   max_prefix_len : host upper bound of prefix_len[] (sizes the launch)
- * Arithmetic: bf16 inputs, fp32 accumulation (MFMA), fp32 softmax, output rounded to bf16;
- * fp32 inputs are handled entirely in fp32.
- * Errors: Hq % Hkv != 0, D not in {64, 128} for bf16 or D > 128 / D % 4 != 0 for fp32 -> DT_ERR_DTYPE/LIMIT.
+ * Arithmetic: bf16 inputs, fp32 accumulation, fp32 softmax, output rounded to bf16; fp32 inputs are
+ * handled entirely in fp32.  bf16 with D == 128 and both strides multiples of 8 elements runs on the
+ * matrix cores; every other combination with D <= 128 runs on a plain vector-ALU kernel (correct, slow).
+ * Errors: Hq % Hkv != 0, scale <= 0, negative strides, q / k_tree / v_tree / out not 16-byte aligned
+ * -> DT_ERR_INVALID_ARG; D > 128, batch > 8191 or Hq > 65535 -> DT_ERR_LIMIT.
  */
 int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int D, float scale,
                       const void *q, const void *k_tree, const void *v_tree, const int32_t *n_nodes,
@@ -170,7 +192,8 @@ int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int 
  *                                    row best; stochastic: inverse-CDF sample of softmax(row best /
  *                                    temperature) at the uniform with node index 0xFFFFFFFF), then -1
  *   node_argmax[batch, TT_cap]       argmax of every node row (may be NULL)
- * Errors: stochastic / sampled with temperature <= 0, stochastic with logp NULL -> DT_ERR_INVALID_ARG.
+ * Errors: stochastic / sampled with temperature <= 0, stochastic with logp NULL -> DT_ERR_INVALID_ARG;
+ * more than 2^31 - 1 (row, chunk) pairs over the batch*TT_cap rows -> DT_ERR_LIMIT.
  */
 int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, const void *target_logits,
               dt_dtype t, int V, int64_t row_stride, const int32_t *n_nodes, const int32_t *tokens,

@@ -62,7 +62,8 @@ def load_library():
         lib.dt_profile_read.restype = i32
         lib.dt_profile_kernel_name.argtypes = [i32]
         lib.dt_profile_kernel_name.restype = C.c_char_p
-        for fn in ("dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept", "dt_commit",
+        lib.dt_init.argtypes = []
+        for fn in ("dt_init", "dt_workspace_bytes", "dt_topk_rows", "dt_build_tree", "dt_tree_attention", "dt_accept", "dt_commit",
                    "dt_level_state_bytes", "dt_expand_level", "dt_finish_tree", "dt_action_table",
                    "dt_policy_workspace_bytes", "dt_policy_step"):
             getattr(lib, fn).restype = i32
@@ -72,6 +73,12 @@ def load_library():
 
 def dt_status_string(status):
     return load_library().dt_status_string(status).decode()
+
+
+def dt_init():
+    rc = load_library().dt_init()
+    if rc:
+        raise DtError("dt_init", rc)
 
 
 def _ptr(t):

@@ -2,14 +2,66 @@
 // No allocation, no synchronisation, no exceptions.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdint>
-#include <cstdlib>
+#include <mutex>
 
 #include "kernels.hpp"
 
 namespace {
 
 thread_local int g_last_hip = 0;
+
+// ---- one-time set-up per device (dt_init) ---------------------------------------------------------
+// Kernels that use more than 64 KB of LDS have to be given leave once per device, and the launch
+// shapes depend on the device's number of compute units.  Both are settled here, under a lock, by
+// dt_init() or by the first launching call on a device; afterwards the launch path only reads.
+constexpr int MAX_DEVICES = 64;
+struct DeviceState {
+    std::atomic<int> ready{0};
+    int n_cu = 0;
+};
+DeviceState g_dev[MAX_DEVICES];
+std::mutex g_init_mu;
+
+// status; *n_cu = compute units of the current device
+int ensure_init(int *n_cu) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); return DT_ERR_HIP; }
+    if (dev < 0 || dev >= MAX_DEVICES) return DT_ERR_LIMIT;
+    DeviceState &d = g_dev[dev];
+    if (!d.ready.load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(g_init_mu);
+        if (!d.ready.load(std::memory_order_relaxed)) {
+            int n = 0;
+            e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+            if (e == hipSuccess) e = dt::tree_init();
+            if (e == hipSuccess) e = dt::attn_init();
+            if (e != hipSuccess || n < 1) { g_last_hip = (int)e; (void)hipGetLastError(); return DT_ERR_HIP; }
+            d.n_cu = n;
+            d.ready.store(1, std::memory_order_release);
+        }
+    }
+    if (n_cu) *n_cu = d.n_cu;
+    return DT_OK;
+}
+
+// compute units for sizing a workspace: of the current device if there is one, else of an MI355X
+// (the size is then an upper bound for any smaller part)
+int cu_count_for_sizing() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < MAX_DEVICES) {
+        if (g_dev[dev].ready.load(std::memory_order_acquire)) return g_dev[dev].n_cu;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) return n;
+    }
+    (void)hipGetLastError();
+    return 256;
+}
+
+// launch grids: x up to 2^31 - 1 workgroups, y and z up to 65535
+constexpr int64_t GRID_X_MAX = 2147483647ll;
+constexpr int GRID_YZ_MAX = 65535;
 
 inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -23,9 +75,6 @@ inline int min_nl(int V) {
 }
 inline int pick_nl(int64_t n_rows, int V) {
     int a = dt::rows_pick_nl(n_rows, V), b = min_nl(V);
-#ifdef DT_TIMESTAMPS
-    if (const char *e = getenv("DT_NL")) a = atoi(e);
-#endif
     return a > b ? a : b;
 }
 inline int max_chunks(int V) { return dt::rows_chunks_per_row(V, min_nl(V)); }
@@ -99,6 +148,8 @@ const char *dt_status_string(int s) {
     }
 }
 
+int dt_init(void) { return ensure_init(nullptr); }
+
 int dt_last_hip_error(void) { return g_last_hip; }
 const char *dt_hip_error_string(int code) { return hipGetErrorString((hipError_t)code); }
 
@@ -112,7 +163,7 @@ int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq,
     size_t build = topk_scratch(nullptr, total_rows, St).bytes + 2 * align_up(state_rows * DT_K_MAX * 4) +
                    align_up(state_rows * 4);
     size_t accept = argmax_scratch(nullptr, (int64_t)batch * TT_cap, S).bytes + align_up((size_t)batch * TT_cap * 4);
-    size_t attn = dt::attn_workspace_bytes(batch, TT_cap, Hq, D);
+    size_t attn = dt::attn_workspace_bytes(batch, TT_cap, Hq, D, cu_count_for_sizing());
     size_t m = build > accept ? build : accept;
     m = m > attn ? m : attn;
     *bytes = m + 256;
@@ -126,9 +177,11 @@ int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, i
     if (!topk_v_ok(V) || k < 1 || k > DT_K_MAX || k > V) return DT_ERR_LIMIT;
     if (n_rows == 0) return DT_OK;
     const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
+    if (n_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     TopkScratch rs = topk_scratch(ws, n_rows, S);
     if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
+    if (int rc = ensure_init(nullptr)) return rc;
     dt::RowArgs a = {};
     a.logits = logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
     a.mode = dt::ROWS_UNIFORM; a.k_uniform = k;
@@ -155,6 +208,7 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     if (!topk_v_ok(V) || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
     if (total_rows < batch) return DT_ERR_INVALID_ARG;  // every sequence owns at least its root row
     const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
+    if (total_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     char *wsd = (char *)ws;
     TopkScratch rs = topk_scratch(wsd, total_rows, S);
@@ -165,6 +219,7 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     int32_t *top_id = (int32_t *)(wsd + off); off += align_up(state_rows * DT_K_MAX * 4);
     float *lse = (float *)(wsd + off); off += align_up(state_rows * 4);
     if (off > ws_bytes) return DT_ERR_WORKSPACE;
+    if (int rc = ensure_init(nullptr)) return rc;
 
     dt::RowArgs a = {};
     a.logits = draft_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
@@ -180,7 +235,7 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
 
     dt::TreeArgs ta = {};
     ta.batch = batch; ta.params = params; ta.V = V; ta.seq_rows = DT_STATE_ROWS; ta.root_token = root_token;
-    ta.TT_cap = TT_cap; ta.top_val = top_val; ta.top_id = top_id; ta.lse = lse;
+    ta.TT_cap = TT_cap; ta.top_val = top_val; ta.top_id = top_id; ta.lse = lse; ta.row_off = row_off;
     ta.n_nodes = n_nodes; ta.tokens = tokens; ta.parents = parents; ta.depth = depth; ta.src_row = src_row;
     ta.score = score; ta.logp = logp; ta.anc_mask = (unsigned long long *)anc_mask;
     e = dt::tree_launch(ta, st);
@@ -200,11 +255,14 @@ int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int 
     if (Hq < 1 || Hkv < 1 || Hq % Hkv || D < 1 || max_prefix_len < 0 || !(scale > 0.0f) || kv_stride_tok < 0 ||
         kv_stride_head < 0)
         return DT_ERR_INVALID_ARG;
-    if (TT_cap < 1 || TT_cap > DT_TT_MAX || D > 128) return DT_ERR_LIMIT;
+    if (TT_cap < 1 || TT_cap > DT_TT_MAX || D > 128 || batch > GRID_YZ_MAX / 8 || Hq > GRID_YZ_MAX) return DT_ERR_LIMIT;
     if ((uintptr_t)q % 16 || (uintptr_t)k_tree % 16 || (uintptr_t)v_tree % 16 || (uintptr_t)out % 16)
         return DT_ERR_INVALID_ARG;
     if (ws && (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
+    int n_cu = 0;
+    if (int rc = ensure_init(&n_cu)) return rc;
     dt::AttnArgs a = {};
+    a.n_cu = n_cu;
     a.batch = batch; a.dtype = t; a.Hq = Hq; a.Hkv = Hkv; a.D = D; a.scale = scale;
     a.q = q; a.k_tree = k_tree; a.v_tree = v_tree; a.n_nodes = n_nodes;
     a.k_prefix = k_prefix; a.v_prefix = v_prefix; a.prefix_len = prefix_len; a.max_prefix_len = max_prefix_len;
@@ -234,10 +292,12 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     if (V < 1 || min_nl(V) == 0 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
     const int64_t rows = (int64_t)batch * TT_cap;
     const int nl = pick_nl(rows, V), S = dt::rows_chunks_per_row(V, nl);
+    if (rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     ArgmaxScratch rs = argmax_scratch(ws, rows, S);
     int32_t *samples = (int32_t *)((char *)ws + rs.bytes);  // target-sampled mode: one token per node
     if (rs.bytes + align_up((size_t)rows * 4) > ws_bytes) return DT_ERR_WORKSPACE;
+    if (int rc = ensure_init(nullptr)) return rc;
 
     dt::RowArgs a = {};
     a.logits = target_logits; a.dtype = t; a.V = V; a.row_stride = row_stride;
@@ -284,6 +344,8 @@ int dt_expand_level(void *stream, int batch, int level, const dt_params *params,
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     TopkScratch rs = topk_scratch(ws, total_rows, S);
     if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
+    if (total_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
+    if (int rc = ensure_init(nullptr)) return rc;
     LevelState ls = level_state(state, batch);
 
     dt::RowArgs a = {};
@@ -319,6 +381,7 @@ int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, cons
         !anc_mask || (uintptr_t)state % 256)
         return DT_ERR_INVALID_ARG;
     if (V < 1 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
+    if (int rc = ensure_init(nullptr)) return rc;
     LevelState ls = level_state((void *)state, batch);
     dt::TreeArgs ta = {};
     ta.batch = batch; ta.params = params; ta.V = V; ta.seq_rows = DT_STATE_ROWS;

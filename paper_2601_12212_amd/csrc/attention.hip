@@ -12,29 +12,12 @@
 //
 // fp32 path: plain ALU kernel, one wave per (node, head); a correctness path for small
 // problems and for head sizes the MFMA path does not cover.
-#include <cstdlib>
 
 #include "common.hpp"
 #include "kernels.hpp"
 
 namespace dt {
 
-#ifdef DT_TIMESTAMPS
-__device__ unsigned long long dt_dbg_attn[64];
-#define ASTAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && (i) < 64) dt_dbg_attn[i] = __builtin_amdgcn_s_memtime(); } while (0)
-extern "C" int dt_debug_attn_stamps(unsigned long long *out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_attn), sizeof(unsigned long long) * 64);
-}
-// life of every workgroup of the balanced large-batch kernel: (start, end) on the 100 MHz counter, hardware id
-__device__ unsigned long long dt_dbg_wg[4096][3];
-extern "C" int dt_debug_attn_wgs(unsigned long long *out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_wg), sizeof(unsigned long long) * 4096 * 3);
-}
-#define WGSTAMP(k) do { if (threadIdx.x == 0) { const int wg_ = blockIdx.y * gridDim.x + blockIdx.x; if (wg_ < 4096) { dt_dbg_wg[wg_][k] = __builtin_amdgcn_s_memrealtime(); if (k) dt_dbg_wg[wg_][2] = ((unsigned long long)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) << 32) | __builtin_amdgcn_s_getreg(4 | (0 << 6) | (31 << 11)); } } } while (0)
-#else
-#define ASTAMP(i) do {} while (0)
-#define WGSTAMP(k) do {} while (0)
-#endif
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -224,15 +207,12 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
             voff[db][hi] = (u32)((8 * hi + 4 * half + r0) * 256 +
                                  (((4 * db + 2 * grp + (q4 >> 1)) ^ (4 * r0 + 2 * hi + half)) << 4) + 8 * (q4 & 1));
 
-    ASTAMP(0);
     fetch(kb0, 0);
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of the block is in LDS
     __syncthreads();
     for (int kb = kb0; kb < kb1; ++kb) {
         const int cur = (kb - kb0) & 1;
-        ASTAMP(1 + (kb - kb0) * 6);
         if (kb + 1 < kb1) fetch(kb + 1, cur ^ 1);  // the other stage was last read before the previous barrier
-        ASTAMP(2 + (kb - kb0) * 6);
         if (active) {
             const unsigned char *kt = s_dyn + cur * STAGE_BYTES, *vt = kt + TILE_BYTES;
             // ---- S^T: 64 keys x 32 queries as two 32x32 blocks -----------------------------------
@@ -266,7 +246,6 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
                 if (s + 2 < KSTEPS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                 __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             }
-            ASTAMP(3 + (kb - kb0) * 6);
             const int tbase = kb * TILE_KEYS;
             if (tbase + TILE_KEYS > L) {  // only blocks that contain tree keys (or the end) need the mask
 #pragma unroll
@@ -312,7 +291,6 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
 #pragma unroll
                     for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
             }
-            ASTAMP(4 + (kb - kb0) * 6);
             // ---- O^T += V^T P^T ------------------------------------------------------------------
 #pragma unroll
             for (int j = 0; j < 2; ++j)
@@ -327,9 +305,7 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
                         oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j][st], oacc[db], 0, 0, 0);
                     }
         }
-        ASTAMP(5 + (kb - kb0) * 6);
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of the next block has landed
-        ASTAMP(6 + (kb - kb0) * 6);
         __syncthreads();
     }
 
@@ -452,7 +428,6 @@ template <int D>
 __global__ __launch_bounds__(256, 2) void attn_gang_kernel(AttnArgs a, int P, int mt_max, GangPartial part) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
     const int h = blockIdx.x, y = blockIdx.y, lane = threadIdx.x & 63;
-    WGSTAMP(0);
     const GangPlan p = gang_plan(a, P, mt_max, lane);
     // class, gang and row tile of slot y
     int base = 0, cls = 0;
@@ -505,7 +480,6 @@ __global__ __launch_bounds__(256, 2) void attn_gang_kernel(AttnArgs a, int P, in
         dst.ml = part.ml + (slot * 2 + which) * ATT_MTILE;
         tile_segment<D>(a, s_dyn, h, b, tile * ATT_MTILE, kb0, kb1, dst);
     }
-    WGSTAMP(1);
 }
 
 // Merge of the partials of the balanced schedule: one thread per (row, 4 output columns) of
@@ -586,7 +560,6 @@ template <int D, int NW>
 __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, SplitBuf sb) {
     static_assert(D == 128 && (NW == 4 || NW == 8), "shape");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
-    ASTAMP(62);
     const int G = a.Hq / a.Hkv;
     // blockIdx.x = kv head: workgroups are dealt to the 8 XCDs round-robin by linear id, so every
     // row block and split of one kv head lands on one XCD and shares its L2 copy of that head's K/V
@@ -672,13 +645,10 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
         }
     };
 
-    ASTAMP(0);
     const int kstep = KS * NW;  // the blocks are dealt round-robin over all waves of all splits
     int kb = ks * NW + w;
     if (kb < nb) fetch(kb);
-    int it_no = 0;
-    for (; kb < nb; kb += kstep, ++it_no) {
-        ASTAMP(1 + it_no * 5);
+    for (; kb < nb; kb += kstep) {
         // The prefetched block goes straight into the wave's two LDS tiles, both row-major, which
         // frees its registers for the next prefetch, issued before any arithmetic on this block.
 #pragma unroll
@@ -688,7 +658,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
             *(bf16x8 *)(vt + r * V_PITCH + 8 * dc) = vn[i];
         }
         if (kb + kstep < nb) fetch(kb + kstep);
-        ASTAMP(2 + it_no * 5);
 
         f32x16 sacc;
 #pragma unroll
@@ -698,7 +667,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
             const bf16x8 ka = *(const bf16x8 *)(kt + col * K_PITCH + 16 * s + 8 * half);
             sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc, 0, 0, 0);
         }
-        ASTAMP(3 + it_no * 5);
 
         const int tbase = kb * ATT_KB;
         if (tbase + ATT_KB > L) {  // only blocks that contain tree keys (or the end) need the mask
@@ -743,7 +711,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
 #pragma unroll
                 for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
         }
-        ASTAMP(4 + it_no * 5);
 
         // O^T += V^T P^T.  The A operand of lane (column d = 32db + col, half) holds, for e = 0..7,
         // V[key 16st + 8(e/4) + 4half + e%4][d]: two transposing LDS reads of 4 keys each.  In a
@@ -761,10 +728,8 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
                     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[db], 0, 0, 0);
                 }
         }
-        ASTAMP(5 + it_no * 5);
     }
 
-    ASTAMP(60);
     // ---- the partial results meet ----------------------------------------------------------------
     float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     __syncthreads();  // all private tiles are dead
@@ -850,7 +815,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
 #pragma unroll
         for (int q = 0; q < 4; ++q) pw[q * 64 + lane] = make_float4(res[4 * q], res[4 * q + 1], res[4 * q + 2], res[4 * q + 3]);
         if (w == 0 && half == 0) sb.ml[(unit * KS + ks) * 32 + col] = make_float2(Mx, Lsum);
-        ASTAMP(63);
         return;
     }
     if (!qvalid) return;
@@ -863,7 +827,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
         for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(res[q4 * 4 + e] * inv);
         *(bf16x4 *)(op + 8 * q4 + 4 * half) = o4;
     }
-    ASTAMP(61);
 }
 
 // Merge of the KS partials of every (sequence, kv head, 32-row block): thread (w, lane) owns the
@@ -991,26 +954,24 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a) {
 }
 
 // ------------------------------------------------------------------------------- launchers --
-// compute units of the current device (256 when there is no device to ask, e.g. when only the
-// workspace size is wanted on a machine without one)
-static int compute_units() {
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0, n = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
-            n_cu = n;
-        else
-            n_cu = 256;
-        (void)hipGetLastError();
-    }
-    return n_cu;
+// LDS beyond 64 KB has to be asked for, once per device (dt_init)
+hipError_t attn_init() {
+    hipError_t e = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       8 * WT_ELEMS * 2);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                4 * WT_ELEMS * 2);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)attn_tile_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, TILE_LDS_BYTES);
+    if (e == hipSuccess)
+        e = hipFuncSetAttribute((const void *)attn_gang_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, TILE_LDS_BYTES);
+    return e;
 }
 
 // scratch of the balanced large-batch schedule: (kv heads x slots per head) <= 2 x compute units
 // slots, two partials of 128 rows each, and the table of up to 64 sequences
-static size_t gang_bytes(int D) {
-    return (size_t)2 * compute_units() * 2 * ATT_MTILE * ((size_t)D * 4 + 8) + 64 * GS_WORDS * 4;
+static size_t gang_bytes(int D, int n_cu) {
+    return (size_t)2 * n_cu * 2 * ATT_MTILE * ((size_t)D * 4 + 8) + 64 * GS_WORDS * 4;
 }
 
 // scratch of the small-batch key splits: per (sequence, kv head, 32-row block) and split
@@ -1018,9 +979,9 @@ static size_t wave_split_bytes(int batch, int TT_cap, int Hq) {
     return (size_t)batch * ((TT_cap * Hq + 31) / 32 + Hq) * (4 * 4 * 64 * 16 + 32 * 8);
 }
 
-size_t attn_workspace_bytes(int batch, int TT_cap, int Hq, int D) {
+size_t attn_workspace_bytes(int batch, int TT_cap, int Hq, int D, int n_cu) {
     if (D != 128) return 0;
-    const size_t w8 = wave_split_bytes(batch, TT_cap, Hq) * 8, g = gang_bytes(D);
+    const size_t w8 = wave_split_bytes(batch, TT_cap, Hq) * 8, g = gang_bytes(D, n_cu);
     const size_t cap = (size_t)256 << 20;
     const size_t want = w8 > g ? w8 : g;
     return want < cap ? want : cap;
@@ -1056,24 +1017,10 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
         if (KS > 1 && (!a.ws || (size_t)KS * per_split > a.ws_bytes)) KS = a.ws ? (int)(a.ws_bytes / per_split) : 1;
         if (KS < 1) KS = 1;
         int nw_sel = KS > 1 ? 4 : 8;
-#ifdef DT_TIMESTAMPS
-        if (const char *e = getenv("DT_KS")) { KS = atoi(e); }
-        if (const char *e = getenv("DT_NW")) { nw_sel = atoi(e); }
-#endif
         SplitBuf sb;
         sb.o = (float4 *)a.ws;
         sb.ml = (float2 *)((char *)a.ws + (size_t)units * KS * 4 * 4 * 64 * 16);
         dim3 grid(a.Hkv, mblocks, a.batch * KS);
-        static bool lds_opt_in = false;
-        if (!lds_opt_in) {
-            *err = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 8>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 8 * WT_ELEMS * 2);
-            if (*err == hipSuccess)
-                *err = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 4>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 4 * WT_ELEMS * 2);
-            if (*err != hipSuccess) return DT_ERR_HIP;
-            lds_opt_in = true;
-        }
         if (nw_sel == 4)  // several workgroups per unit: four waves each (two workgroups fit a compute unit)
             launch_kernel(KID_ATTN, st, attn_wave_kernel<128, 4>, grid, dim3(256), 4 * WT_ELEMS * 2, a, KS, sb);
         else              // one workgroup per unit: eight waves (two per SIMD), 136 KB of LDS
@@ -1087,20 +1034,10 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
         *err = hipGetLastError();
         return *err == hipSuccess ? DT_OK : DT_ERR_HIP;
     }
-    static bool tile_lds_opt_in = false;
-    if (!tile_lds_opt_in) {
-        *err = hipFuncSetAttribute((const void *)attn_tile_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   TILE_LDS_BYTES);
-        if (*err == hipSuccess)
-            *err = hipFuncSetAttribute((const void *)attn_gang_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       TILE_LDS_BYTES);
-        if (*err != hipSuccess) return DT_ERR_HIP;
-        tile_lds_opt_in = true;
-    }
     // Fewer whole (sequence, kv head, row tile) items than four rounds of two workgroups per compute
     // unit: the balanced schedule (needs one lane per sequence and a slot for every tile count).
-    const int P = 2 * compute_units() / a.Hkv;
-    const bool gang = base_wgs < 8 * compute_units() && a.batch <= 64 && mtiles <= 63 && P >= mtiles * (mtiles + 1) / 2 &&
+    const int P = 2 * a.n_cu / a.Hkv;
+    const bool gang = base_wgs < 8 * a.n_cu && a.batch <= 64 && mtiles <= 63 && P >= mtiles * (mtiles + 1) / 2 &&
                       a.ws && (size_t)a.Hkv * P * 2 * ATT_MTILE * ((size_t)a.D * 4 + 8) + 64 * GS_WORDS * 4 <= a.ws_bytes;
     if (!gang) {
         launch_kernel(KID_ATTN, st, attn_tile_kernel<128>, dim3(a.Hkv, mtiles, a.batch), dim3(256), TILE_LDS_BYTES, a);

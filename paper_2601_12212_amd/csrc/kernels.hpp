@@ -47,6 +47,7 @@ struct RowArgs {
     // ROWS_LEVEL: rows of one level of every sequence, results scattered into the build state
     int level, rows_per_seq, state_rows;
     const int32_t *n_exp_prev;  // [batch] nodes expanded one level up
+    int chunks;  // set by the launch functions: workgroups per row
     // set by the launch functions: read a row's chunk before the row is known to be live (the loads then
     // overlap the reads that decide it; the row is inside the caller's buffer either way)
     int early_load;
@@ -69,7 +70,8 @@ struct TreeArgs {
     int TT_cap;
     const float *top_val;  // [batch, seq_rows, DT_K_MAX]: row results of sequence b start at row b * seq_rows
     const int32_t *top_id;
-    const float *lse;      // [total_rows]
+    const float *lse;      // [batch, seq_rows]
+    const int64_t *row_off;  // one-shot build: [batch+1] draft rows a sequence owns; null: all of its block
     int32_t *n_nodes, *tokens, *parents, *depth, *src_row;
     float *score, *logp;
     unsigned long long *anc_mask;
@@ -80,6 +82,7 @@ struct TreeArgs {
     int32_t *n_expand, *state_n_exp, *exp_token, *exp_parent_slot, *exp_row, *exp_pos;  // [batch(, DT_K_MAX)]
     unsigned long long *exp_mask;  // [batch, DT_K_MAX, 4]
 };
+hipError_t tree_init();  // once per device, before the first launch
 hipError_t tree_launch(const TreeArgs &a, hipStream_t st);
 
 // -------------------------------------------------------------- attention (attention.hip)
@@ -98,8 +101,10 @@ struct AttnArgs {
     void *out;
     void *ws;
     size_t ws_bytes;
+    int n_cu;  // compute units of the device the launch goes to
 };
-size_t attn_workspace_bytes(int batch, int TT_cap, int Hq, int D);
+size_t attn_workspace_bytes(int batch, int TT_cap, int Hq, int D, int n_cu);
+hipError_t attn_init();  // once per device, before the first launch
 int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err);  // returns dt_status
 
 // ------------------------------------------------------------------- accept (accept.hip)

@@ -13,16 +13,6 @@
 
 namespace dt {
 
-#ifdef DT_TIMESTAMPS
-// debug builds only: clock readings of thread 0 of workgroup 0 of the selection kernel
-__device__ unsigned long long dt_dbg_stamps_rows[64];
-__shared__ unsigned long long dt_lds_stamps_rows[64];
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) dt_lds_stamps_rows[i] = __builtin_amdgcn_s_memtime(); } while (0)
-#define STAMP_FLUSH() do { __syncthreads(); if (threadIdx.x < 64 && blockIdx.x == 0) dt_dbg_stamps_rows[threadIdx.x] = dt_lds_stamps_rows[threadIdx.x]; } while (0)
-#else
-#define STAMP(i) do {} while (0)
-#define STAMP_FLUSH() do {} while (0)
-#endif
 
 // ---------------------------------------------------------------- row -> (valid, k) ----
 struct RowMeta {
@@ -158,8 +148,9 @@ __device__ __forceinline__ float2 wave_lse_partial(const float (&x)[E], float mx
 template <int NL, bool BF16, bool VEC>
 __global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
     constexpr int E = 8 * NL;
-    const int64_t g = blockIdx.y;
-    const int c = blockIdx.x;
+    // workgroup (row g, chunk c) is number g * chunks + c of a one-dimensional grid
+    const int64_t g = blockIdx.x / (unsigned)a.chunks;
+    const int c = (int)(blockIdx.x % (unsigned)a.chunks);
     const int lane = lane_id(), w = threadIdx.x >> 6;
     const int base = c * (256 * E) + w * (64 * E) + lane * 8;
     float x[E];
@@ -170,7 +161,7 @@ __global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
     float mx = x[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
-    const int64_t wslot = (g * gridDim.x + c) * 4 + w;
+    const int64_t wslot = (int64_t)blockIdx.x * 4 + w;
     a.lane_max[wslot * 64 + lane] = mx;
     if (a.want_lse) {
         const float2 p = wave_lse_partial<E>(x, mx, a.inv_t);
@@ -203,7 +194,6 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     const int V = a.V, E = 8 * nl;
     const int n_lanes = S * 256;
     const float *lm = a.lane_max + g * n_lanes;
-    STAMP(0);
     // the lane maxima do not depend on the row's metadata (two dependent global reads): ask for them
     // first.  Rows that turn out to be dead have their slots in the workspace all the same.
     float it[16];
@@ -213,7 +203,6 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     }
     const RowMeta meta = row_meta(a, g);
     if (!meta.valid) return;
-    STAMP(1);
     const int k = meta.k;
 
     __shared__ float s_T[4];
@@ -248,9 +237,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     } else {
         for (int j = 0; j < S; ++j) tmax = fmaxf(tmax, lm[j * 256 + tid]);
     }
-    STAMP(2);
     const float Tw = unord32(wave_kth_largest<BF16 ? 16 : 0>(ord32(tmax), k));
-    STAMP(3);
     if (lane == 0) s_T[w] = Tw;
     if (tid == 0) s_n2 = 0;
     __syncthreads();
@@ -291,7 +278,6 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     }
     if (lane == 0) s_c1n[w] = cnt;
     __syncthreads();
-    STAMP(5);
     const int c0 = s_c1n[0], c1 = s_c1n[1], c2 = s_c1n[2], c3 = s_c1n[3];
     const int n1 = c0 + c1 + c2 + c3;
     bool slow = n1 > 64;  // uniform over the workgroup
@@ -330,9 +316,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
             if (hot) s_hot[lanes_below(m)] = gl;
             if (lane == 0) { s_h = __popcll(m); s_Trow = T; }
         }
-        STAMP(6);
         __syncthreads();
-        STAMP(7);
         const int h = s_h;
         const float T = s_Trow;
         const int nl_log2 = nl == 4 ? 2 : nl == 2 ? 1 : 0;  // chunk multipliers are 1, 2 or 4
@@ -370,9 +354,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
                 }
             }
         }
-        STAMP(8);
         __syncthreads();
-        STAMP(9);
         const int n2 = s_n2;
         if (n2 <= 64) {
             if (w == 0) {
@@ -390,8 +372,6 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
                 }
                 if (lane < n2 && r0 + r1 < k) emit(r0 + r1, mine);
             }
-            STAMP(10);
-            STAMP_FLUSH();
             return;
         }
         slow = true;
@@ -426,8 +406,8 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
 template <int NL, bool BF16, bool VEC>
 __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
     constexpr int E = 8 * NL;
-    const int64_t g = blockIdx.y;
-    const int c = blockIdx.x;
+    const int64_t g = blockIdx.x / (unsigned)a.chunks;
+    const int c = (int)(blockIdx.x % (unsigned)a.chunks);
     const int lane = lane_id(), w = threadIdx.x >> 6;
     __shared__ u64 s_wout[4];
     __shared__ float s_m[4], s_s[4];
@@ -458,7 +438,7 @@ __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
     if (lane == 0) s_wout[w] = key;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const int64_t slot = g * gridDim.x + c;
+        const int64_t slot = blockIdx.x;
         u64 b01 = s_wout[0] > s_wout[1] ? s_wout[0] : s_wout[1];
         u64 b23 = s_wout[2] > s_wout[3] ? s_wout[2] : s_wout[3];
         a.part_keys[slot] = b01 > b23 ? b01 : b23;
@@ -478,11 +458,6 @@ __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
 }
 
 // ------------------------------------------------------------------------ launchers ------
-#ifdef DT_TIMESTAMPS
-extern "C" int dt_debug_stamps_rows(unsigned long long *out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_stamps_rows), sizeof(unsigned long long) * 64);
-}
-#endif
 
 int rows_chunks_per_row(int V, int nl) { return (V + 256 * 8 * nl - 1) / (256 * 8 * nl); }
 
@@ -532,7 +507,8 @@ hipError_t rows_launch_stream(const RowArgs &a_in, int64_t n_rows, int nl, hipSt
     a.early_load = a.mode == ROWS_DRAFT || a.mode == ROWS_UNIFORM || n_rows * rows_chunks_per_row(a.V, nl) <= EARLY_LOAD_WGS;
     const bool vec = rows_vec_ok(a);
     const int kid = a.mode == ROWS_DRAFT ? KID_ROWS_DRAFT : KID_ROWS_UNIFORM;
-#define STREAM_GRID(NLV) dim3(rows_chunks_per_row(a.V, NLV), (unsigned)n_rows)
+    a.chunks = rows_chunks_per_row(a.V, nl);
+#define STREAM_GRID(NLV) dim3((unsigned)(n_rows * a.chunks))
     switch (nl) {
         case 4: DT_ROWS_DISPATCH(kid, row_stream_kernel, 4, STREAM_GRID(4)); break;
         case 2: DT_ROWS_DISPATCH(kid, row_stream_kernel, 2, STREAM_GRID(2)); break;
@@ -563,7 +539,8 @@ hipError_t rows_launch_argmax(const RowArgs &a_in, int64_t n_rows, int nl, hipSt
     RowArgs a = a_in;
     a.early_load = n_rows * rows_chunks_per_row(a.V, nl) <= EARLY_LOAD_WGS;
     const bool vec = rows_vec_ok(a);
-#define STREAM_GRID(NLV) dim3(rows_chunks_per_row(a.V, NLV), (unsigned)n_rows)
+    a.chunks = rows_chunks_per_row(a.V, nl);
+#define STREAM_GRID(NLV) dim3((unsigned)(n_rows * a.chunks))
     switch (nl) {
         case 4: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 4, STREAM_GRID(4)); break;
         case 2: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 2, STREAM_GRID(2)); break;

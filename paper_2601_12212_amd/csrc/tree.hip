@@ -19,17 +19,6 @@
 
 namespace dt {
 
-#ifdef DT_TIMESTAMPS
-// debug builds only: clock readings of thread 0 of workgroup 0, parked in LDS (a global store in front
-// of a barrier would make the wave wait for the store) and copied out when the kernel ends
-__device__ unsigned long long dt_dbg_stamps[64];
-__shared__ unsigned long long dt_lds_stamps[64];
-#define STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) dt_lds_stamps[i] = __builtin_amdgcn_s_memtime(); } while (0)
-#define STAMP_FLUSH() do { if (threadIdx.x < 64 && blockIdx.x == 0) dt_dbg_stamps[threadIdx.x] = dt_lds_stamps[threadIdx.x]; } while (0)
-#else
-#define STAMP(i) do {} while (0)
-#define STAMP_FLUSH() do {} while (0)
-#endif
 
 #define DT_P_MAX (DT_K_MAX + (DT_D_MAX - 1) * DT_K_MAX * DT_K_MAX)
 #ifndef TREE_NT
@@ -110,7 +99,6 @@ __device__ __forceinline__ int block_radix_cut(const float *score, int n, int ke
             if (in) atomicAdd(&S.hist[p][(key >> shift) & 255u], 1u);
         }
         __syncthreads();
-        STAMP(14 + p);
         // every wave: lane L holds bins 4(63-L) .. 4(63-L)+3, so an ascending lane scan walks the bins downwards
         const uint4 h = *(const uint4 *)&S.hist[p][4 * (63 - lane)];
         const int c = (int)(h.x + h.y + h.z + h.w);
@@ -441,6 +429,9 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
         el[j] = lse[e / DT_K_MAX];
     }
     const dt_params prm = a.params[b];
+    // one-shot build: rows past the span the sequence owns were never reduced; they count as rows
+    // without a viable token (the level-at-a-time state has no such span: its rows arrive level by level)
+    const int64_t span = a.row_off ? a.row_off[b + 1] - a.row_off[b] : (int64_t)DT_STATE_ROWS;
     const int TT = min(max(prm.TT, 1), a.TT_cap), d = min(max(prm.d, 1), DT_D_MAX);
     const int k = min(max(prm.k, 1), min(DT_K_MAX, a.V));
     const int xl = a.expand_level;  // > 0: only the nodes of level xl that are expanded next
@@ -451,7 +442,6 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];  // 116 KB: more than a static array may hold
     TreeLds &S = *reinterpret_cast<TreeLds *>(s_dyn);
 
-    STAMP(0);
     if (xl > 0 && (TT == 1 || xl >= d)) {  // nothing is drafted below level d
         if (tid == 0) { a.n_expand[b] = 0; a.state_n_exp[b] = 0; }
         return;
@@ -476,12 +466,13 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
     // lp in the score array; the level loop turns it into the cumulative score in place.
     // Entry (row, rank) with rank < k is candidate p = rank (row 0) or k + (row - 1) k + rank.
     const int R = xl > 0 ? 1 + (xl - 1) * k : 1 + (d - 1) * k;  // rows that hold candidates
+    const int owned = (int)min(max(span, (int64_t)0), (int64_t)DT_STATE_ROWS);
     auto place = [&](int e, float v, int token, float row_lse) {
         const int row = e / DT_K_MAX, rank = e % DT_K_MAX;
         if (row < R && rank < k) {
             const int p = row == 0 ? rank : k + (row - 1) * k + rank;
             const float own = v - row_lse;
-            const float lp = v > -INFINITY ? own : -INFINITY;
+            const float lp = v > -INFINITY && row < owned ? own : -INFINITY;
             S.score[p] = lp;
             S.lp[p] = own;
             S.tok[p] = token;
@@ -496,7 +487,6 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
     if (tid < 64 && tid >= k) S.key[1][tid] = 0u;
     for (int t = tid; t < COUNT_MAX; t += TREE_NT) S.rank[0][t] = 0;
     __syncthreads();
-    STAMP(1);
 
     // ---- expansion, level by level -----------------------------------------------------------
     int p_end = k;  // pool indices below p_end hold real scores (levels computed so far)
@@ -520,9 +510,7 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
                 else if (G == 2) level_count<2>(key, rank);
                 else if (G == 3) level_count<3>(key, rank);
                 else level_count<4>(key, rank);
-                STAMP(24 + 4 * l);
                 __syncthreads();
-                STAMP(25 + 4 * l);
             }
             if (G == 1) n_exp = level_choose<1>(key, rank, n, k, put);
             else if (G == 2) n_exp = level_choose<2>(key, rank, n, k, put);
@@ -530,7 +518,6 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
             else n_exp = level_choose<4>(key, rank, n, k, put);
         }
         if (n_exp < 0) n_exp = block_select(S.score + lo, n, k, S, put);
-        STAMP(2 + 2 * l);
         if (l == xl) {
             // ---- what the draft model is handed for its next pass: node s of the chosen set ----------
             if (tid < n_exp) {
@@ -584,7 +571,6 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
         }
         p_end = nlo + kk;
         __syncthreads();
-        STAMP(3 + 2 * l);
     }
 
     if (xl > 0) {  // an earlier level had nothing viable to expand
@@ -595,9 +581,7 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
 
     // ---- rerank: the TT-1 best of the whole pool ----------------------------------------------
     const int keep = block_select(S.score, p_end, TT - 1, S, [&](int i, int pos) { S.node[i] = (int16_t)(pos + 1); });
-    STAMP(20);
     if (tid == 0) a.n_nodes[b] = keep + 1;
-    STAMP(21);
 
     // ---- emission -------------------------------------------------------------------------------
     for (int p = tid; p < p_end; p += TREE_NT) {
@@ -623,25 +607,16 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
         a.anc_mask[(o + n) * DT_MASK_WORDS] = m0;
         a.anc_mask[(o + n) * DT_MASK_WORDS + 1] = m1;
     }
-    STAMP(22);
-    STAMP_FLUSH();
 }
 
-#ifdef DT_TIMESTAMPS
-extern "C" int dt_debug_stamps(unsigned long long *out) {
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(dt_dbg_stamps), sizeof(unsigned long long) * 64);
+
+// LDS beyond 64 KB has to be asked for, once per device (dt_init)
+hipError_t tree_init() {
+    return hipFuncSetAttribute((const void *)tree_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)sizeof(TreeLds));
 }
-#endif
 
 hipError_t tree_launch(const TreeArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;
-    static bool lds_opt_in = false;  // LDS beyond 64 KB has to be asked for once
-    if (!lds_opt_in) {
-        const hipError_t e = hipFuncSetAttribute((const void *)tree_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                 (int)sizeof(TreeLds));
-        if (e != hipSuccess) return e;
-        lds_opt_in = true;
-    }
     launch_kernel(KID_TREE, st, tree_kernel, dim3(a.batch), dim3(TREE_NT), sizeof(TreeLds), a);
     return hipGetLastError();
 }

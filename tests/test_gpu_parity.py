@@ -88,60 +88,90 @@ def test_topk_rows_unaligned_row_stride_takes_the_scalar_path():
 
 # ------------------------------------------------------------------------- whole step on the configs
 
-def check_case(case, sample_attention=None, rng_seed=0):
+# Attention bars.  The target's bar: max-abs 2e-2 (bf16) / 1e-5 (fp32).  Our own, tighter one for the bf16
+# matrix-core path: outputs are convex combinations of unit-variance values (|O| <= ~0.4 on these inputs), the
+# probabilities are rounded to bf16 before the second product (relative 2^-9 each, averaging out over the keys)
+# and the result is rounded to bf16 once (half an ulp: <= 2^-9 |O| ~ 8e-4).  Observed maxima on the MI355X are
+# printed by every test; the bound is about four times the largest of them.
+NORTH_STAR_TOL = {"f32": 1e-5, "bf16": 2e-2}
+OWN_TOL = {"f32": 2e-6, "bf16": 4e-3}
+
+_CASES, _ATTN = {}, {}
+
+
+def cached_case(ci):
+    """The oracle side of benchmark configuration ci, computed once per test session."""
+    if ci not in _CASES:
+        _CASES[ci] = oracle_case(ci)
+    return _CASES[ci]
+
+
+def oracle_attention(case, b, scale, key=None):
+    """Every attention output of sequence b from the oracle (cached when the case is a cached one)."""
+    c = case.cfg
+    q, kt, vt, kp, vp = dt_synth.qkv(c, b)
+    N = case.trees[b]["n_nodes"]
+    if key is not None and (key, b) in _ATTN:
+        return _ATTN[(key, b)]
+    want = ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, case.trees[b]["anc_mask"], scale)
+    if key is not None:
+        _ATTN[(key, b)] = want
+    return want
+
+
+def assert_attention(out, want, dtype, tag):
+    """Every output element against the oracle; NaN or inf anywhere fails."""
+    assert out.shape == want.shape, tag
+    assert np.isfinite(out).all(), (tag, "non-finite attention output")
+    err = float(np.abs(out - want).max())
+    assert err <= NORTH_STAR_TOL[dtype], (tag, "attention max-abs", err)
+    assert err <= OWN_TOL[dtype], (tag, "attention max-abs above our own bound", err)
+    return err
+
+
+def check_case(case, key=None):
     c = case.cfg
     st = make_step(case)
     st.run(philox_step=0)
     torch.cuda.synchronize()
-    tol = 1e-5 if c.dtype == "f32" else 2e-2
+    worst = 0.0
     for b in range(c.B):
         tag = "%s seq %d" % (c.name, b)
         got = st.tree(b)
         assert_tree_equal(got, case.trees[b], tag)
         assert_accept_equal(st.accepted(b), case.accepts[b], tag)
-        q, kt, vt, kp, vp = dt_synth.qkv(c, b)
-        N = got["n_nodes"]
-        out = st.attention_out(b)
-        if sample_attention is None:
-            want = ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, case.trees[b]["anc_mask"], st.scale)
-            err = np.abs(out - want).max()
-        else:
-            rng = np.random.default_rng(rng_seed + b)
-            samples = np.stack([rng.integers(0, N, sample_attention), rng.integers(0, c.Hq, sample_attention)], 1)
-            samples[0] = (0, 0); samples[1] = (N - 1, c.Hq - 1)
-            want = ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, case.trees[b]["anc_mask"], st.scale,
-                                      samples=samples)
-            err = max(np.abs(out[i, h] - want[r]).max() for r, (i, h) in enumerate(samples))
-        assert err <= tol, (tag, "attention max-abs", err)
+        worst = max(worst, assert_attention(st.attention_out(b), oracle_attention(case, b, st.scale, key), c.dtype, tag))
+    print("attention max-abs error %s: %.3e (all %d outputs compared)"
+          % (c.name, worst, sum(t["n_nodes"] for t in case.trees) * c.Hq * c.D))
     return st
 
 
 def test_config1_tiny_fp32():
-    check_case(oracle_case(1))
+    check_case(cached_case(1), key=1)
 
 
 def test_config2_llama3_8b_tt60():
-    case = oracle_case(2)
+    case = cached_case(2)
     assert case.trees[0]["n_nodes"] == 60
     assert 0 < sum(a["accept_len"] for a in case.accepts)          # acceptance is partial, not trivial
-    check_case(case)
+    check_case(case, key=2)
 
 
 def test_config3_vicuna_13b_tt64():
-    check_case(oracle_case(3), sample_attention=400)
+    check_case(cached_case(3), key=3)
 
 
 def test_config4_batch16_ragged():
-    case = oracle_case(4)
+    case = cached_case(4)
     assert len({p for p in case.cfg.params}) > 8                   # really ragged
-    check_case(case, sample_attention=40)
+    check_case(case, key=4)
 
 
 def test_config5_llama3_70b_stochastic():
-    case = oracle_case(5)
+    case = cached_case(5)
     lens = [a["accept_len"] for a in case.accepts]
     assert max(lens) > 0
-    check_case(case, sample_attention=40)
+    check_case(case, key=5)
 
 
 # ------------------------------------------------------------------------------------------ edge cases
@@ -177,7 +207,7 @@ def test_attention_key_splits_and_long_prefix():
     # few (sequence, kv head) pairs and a long prefix: the small-batch kernel splits the keys over
     # several workgroups and a merge kernel joins the partials
     check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [2000], Hq=8, Hkv=2)))
-    check_case(oracle_case(0, cfg=small_cfg([(128, 6, 6), (7, 2, 3)], [4097, 640], Hq=4, Hkv=4)), sample_attention=300)
+    check_case(oracle_case(0, cfg=small_cfg([(128, 6, 6), (7, 2, 3)], [4097, 640], Hq=4, Hkv=4)))
 
 
 def test_attention_balanced_schedule_on_ragged_batches():
@@ -192,14 +222,13 @@ def test_attention_balanced_schedule_on_ragged_batches():
         params.append((TT, int(rng.integers(1, 6)), int(rng.integers(1, 7))))
         plen.append(int(rng.choice([0, 1, 63, 64, 65, 300, 900, 2500])))
     plen[3], plen[4] = 6000, 0
-    check_case(oracle_case(0, cfg=small_cfg(params, plen, V=2053, Hq=32, Hkv=8)), sample_attention=48)
+    check_case(oracle_case(0, cfg=small_cfg(params, plen, V=2053, Hq=32, Hkv=8)))
     # one class only, sequences much longer than a slot's share: every sequence is cut several times
-    check_case(oracle_case(0, cfg=small_cfg([(96, 4, 6)] * 3, [5000, 4100, 37], V=2053, Hq=64, Hkv=8)),
-               sample_attention=64)
+    check_case(oracle_case(0, cfg=small_cfg([(96, 4, 6)] * 3, [5000, 4100, 37], V=2053, Hq=64, Hkv=8)))
     # more whole items than slots would need splitting: plain one-workgroup-per-item launch (batch > 64)
     params = [(int(rng.choice([5, 40])), 3, 3) for _ in range(70)]
     check_case(oracle_case(0, cfg=small_cfg(params, [int(rng.integers(0, 200)) for _ in range(70)], V=1031,
-                                            Hq=8, Hkv=2)), sample_attention=16)
+                                            Hq=8, Hkv=2)))
 
 
 def test_stochastic_small_and_many_steps():
@@ -295,16 +324,16 @@ def test_all_layers_attention_under_one_graph():
                 want = ref.tree_attention(h["q"][b, :N], h["kt"][b, :N], h["vt"][b, :N], h["kp"][b][:L], h["vp"][b][:L],
                                           case.trees[b]["anc_mask"], st.scale)
                 got = d["out"][b, :N].float().cpu().numpy()
-                assert np.abs(got - want).max() <= 2e-2, (rep, l, b)
+                assert_attention(got, want, "bf16", (rep, l, b))
         (torch.ones(1000, device="cuda") * 3).sum().item()
 
 
-@pytest.mark.parametrize("ci,samples", [(2, 200), (4, 24)])
-def test_whole_step_replayed_from_a_graph_matches_the_oracle(ci, samples):
+@pytest.mark.parametrize("ci", [2, 4])
+def test_whole_step_replayed_from_a_graph_matches_the_oracle(ci):
     # the launch configuration bench.py times: the three calls of the step captured once as a HIP graph and
     # replayed, at the full size of the configuration; every replay (outputs wiped before it, eager work
-    # after it) must give the oracle's tree, acceptance and (sampled) attention
-    case = oracle_case(ci)
+    # after it) must give the oracle's tree, acceptance and every attention output
+    case = cached_case(ci)
     c = case.cfg
     st = make_step(case).prepare()
     side = torch.cuda.Stream()
@@ -323,19 +352,12 @@ def test_whole_step_replayed_from_a_graph_matches_the_oracle(ci, samples):
         torch.cuda.synchronize()
         g.replay()
         torch.cuda.synchronize()
-        rng = np.random.default_rng(rep)
         for b in range(c.B):
             tag = "%s seq %d replay %d" % (c.name, b, rep)
             got = st.tree(b)
             assert_tree_equal(got, case.trees[b], tag)
             assert_accept_equal(st.accepted(b), case.accepts[b], tag)
-            q, kt, vt, kp, vp = dt_synth.qkv(c, b)
-            N = got["n_nodes"]
-            pick = np.stack([rng.integers(0, N, samples), rng.integers(0, c.Hq, samples)], 1)
-            want = ref.tree_attention(q[:N], kt[:N], vt[:N], kp, vp, case.trees[b]["anc_mask"], st.scale, samples=pick)
-            out = st.attention_out(b)
-            err = max(np.abs(out[i, h] - want[r]).max() for r, (i, h) in enumerate(pick))
-            assert err <= 2e-2, (tag, "attention max-abs", err)
+            assert_attention(st.attention_out(b), oracle_attention(case, b, st.scale, ci), c.dtype, tag)
         (torch.ones(1000, device="cuda") * 3).sum().item()
 
 
@@ -401,17 +423,25 @@ def test_masked_vocabulary_rows():
     check_case(case)
 
 
-def test_determinism_same_inputs_same_bits():
-    case = oracle_case(2)
+@pytest.mark.parametrize("ci,repeats", [(2, 100), (4, 25), (5, 10)])
+def test_determinism_same_inputs_same_bits(ci, repeats):
+    # config 2: small-batch attention with key splits and its merge; config 4: the balanced large-batch
+    # schedule with partials and their combine; config 5: the same with Philox draws in the acceptance
+    case = cached_case(ci)
     st = make_step(case)
+    st.out.fill_(5.0)
     st.run()
     torch.cuda.synchronize()
-    first = [st.tokens.clone(), st.anc_mask.clone(), st.out.clone(), st.out_tokens.clone(), st.score.clone()]
-    for _ in range(5):
+    outs = lambda: [st.n_nodes, st.tokens, st.parents, st.anc_mask, st.out, st.accept_len, st.out_tokens, st.score,
+                    st.node_argmax]
+    first = [t.clone() for t in outs()]
+    for r in range(repeats):
+        st.out.fill_(5.0)
         st.run()
-    torch.cuda.synchronize()
-    for a, b in zip(first, [st.tokens, st.anc_mask, st.out, st.out_tokens, st.score]):
-        assert torch.equal(a, b)
+        if r % 10 == 9 or r == repeats - 1:
+            torch.cuda.synchronize()
+            for i, (a, b) in enumerate(zip(first, outs())):
+                assert torch.equal(a, b), (ci, r, i)
 
 
 def test_driving_the_build_level_by_level_matches_the_oracle():
@@ -436,3 +466,141 @@ def test_driving_the_build_level_by_level_matches_the_oracle():
     rows_ref = rows_from_fn(ref.build_tree, fn, V, d, k)
     assert np.array_equal(rows_gpu, rows_ref)
     assert_tree_equal(gpu_build(rows_gpu, TT, d, k, 7), ref.build_tree(rows_ref, TT, d, k, 7))
+
+
+# ------------------------------------------------------------------ the tree mask on the device
+
+def _attention_shapes():
+    rng = np.random.default_rng(31)
+    tile_params = [(int(rng.choice([5, 40])), 3, 3) for _ in range(70)]
+    return {
+        # one workgroup per (sequence, kv head, 32 rows), no key splits
+        "wave": small_cfg([(60, 6, 10)], [300], V=1500, Hq=8, Hkv=2),
+        # the same kernel with the keys dealt over several workgroups and the merge launch
+        "wave_split": small_cfg([(60, 6, 10), (33, 4, 8)], [2000, 1700], V=1500, Hq=8, Hkv=2),
+        # balanced large-batch schedule (partials + combine)
+        "gang": small_cfg([(64, 5, 6)] * 12 + [(96, 4, 6)] * 4, [300 + 211 * i for i in range(16)], V=1031, Hq=32, Hkv=8),
+        # one workgroup per (sequence, kv head, 128-row tile): more than 64 sequences
+        "tile": small_cfg(tile_params, [int(rng.integers(0, 200)) for _ in range(70)], V=1031, Hq=8, Hkv=2),
+    }
+
+
+@pytest.mark.parametrize("shape", ["wave", "wave_split", "gang", "tile"])
+def test_keys_outside_a_nodes_ancestor_set_do_not_reach_its_output(shape):
+    """Overwrite K and V of one tree token per sequence: the outputs of the nodes that do not have it among
+    their ancestors must not change by a single bit, those of the token itself and its descendants must."""
+    cfg = _attention_shapes()[shape]
+    case = oracle_case(0, cfg=cfg)
+    st = make_step(case)
+    st.build_tree()
+    st.tree_attention()
+    torch.cuda.synchronize()
+    before = st.out.clone()
+    rng = np.random.default_rng(5)
+    hit = []
+    for b in range(cfg.B):
+        N = case.trees[b]["n_nodes"]
+        if N < 3:
+            hit.append(None)
+            continue
+        j = int(rng.integers(1, N))                      # never the root: every node sees the root
+        hit.append(j)
+        noise = torch.from_numpy(rng.standard_normal((2, cfg.Hkv, cfg.D)).astype(np.float32) * 40.0).cuda()
+        st.k_tree[b, j] = noise[0].to(st.k_tree.dtype)
+        st.v_tree[b, j] = noise[1].to(st.v_tree.dtype)
+    st.tree_attention()
+    torch.cuda.synchronize()
+    after = st.out
+    unchanged = changed = 0
+    for b in range(cfg.B):
+        j = hit[b]
+        if j is None:
+            continue
+        mask = case.trees[b]["anc_mask"]
+        for i in range(case.trees[b]["n_nodes"]):
+            sees = (int(mask[i, j // 64]) >> (j % 64)) & 1
+            same = torch.equal(before[b, i].view(torch.int16), after[b, i].view(torch.int16))
+            if sees:
+                assert not same, (shape, b, i, j, "a visible key was ignored")
+                changed += 1
+            else:
+                assert same, (shape, b, i, j, "a hidden key reached the output")
+                unchanged += 1
+    assert changed > 0 and unchanged > changed
+
+
+def test_more_rows_than_a_grid_dimension_holds():
+    # 70,000 rows in one call: rows ride in the x dimension of the launch grid
+    rng = np.random.default_rng(3)
+    x = dt_synth.f32_to_bf16_bits((rng.standard_normal((70000, 96)) * 3).astype(np.float32))
+    check_topk(x, 5)
+
+
+def test_a_sequence_that_owns_fewer_rows_than_its_tree_needs():
+    """row_off hands sequence 0 only 4 of the 1 + (d-1) k = 10 rows its parameters ask for: the missing
+    rows count as rows without a viable token, whatever the workspace held before."""
+    from paper_2601_12212_amd.step import Step
+    V, TT, d, k = 3000, 40, 4, 3
+    cfg = small_cfg([(TT, d, k), (TT, d, k)], [10, 10], V=V)
+    rows = [dt_synth.draft_rows(cfg, b) for b in range(2)]
+    st = Step(cfg.params, cfg.prefix_len, cfg.Hq, cfg.Hkv, cfg.D, V)
+    owned = 4
+    packed = np.concatenate([rows[0][:owned], rows[1]])            # sequence 1 keeps all of its rows
+    st.draft_logits[:packed.shape[0]].copy_(torch.from_numpy(packed.view(np.int16)).cuda().view(torch.bfloat16))
+    st.row_off.copy_(torch.tensor([0, owned, owned + rows[1].shape[0]], dtype=torch.int64))
+    st.total_rows = owned + rows[1].shape[0]
+    st.ws.fill_(0x7F)                                              # stale scratch: huge positive floats
+    st.build_tree()
+    torch.cuda.synchronize()
+    short = rows[0].copy()
+    short[owned:] = dt_synth.f32_to_bf16_bits(np.array([-np.inf], np.float32))[0]
+    want0 = ref.build_tree(short, TT, d, k, 0)
+    want1 = ref.build_tree(rows[1], TT, d, k, 0)
+    assert want0["min_margin"] >= 1e-4 and want1["min_margin"] >= 1e-4
+    assert want0["n_nodes"] < want1["n_nodes"]
+    assert_tree_equal(st.tree(0), want0, "short span")
+    assert_tree_equal(st.tree(1), want1, "full span")
+
+
+def test_first_library_call_of_a_process_inside_a_graph_capture():
+    """The one-time set-up (LDS opt-in, compute-unit count) happens in the first launching call; here that call
+    is recorded into a HIP graph in a fresh process, and the replayed step must equal an eager run."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    child = r"""
+import sys
+sys.path.insert(0, %r)
+import numpy as np, torch
+import dt_synth
+from paper_2601_12212_amd.step import Step
+cfg = dt_synth.StepConfig("cap", "bf16", 8, 2, 128, 5003, [(40, 5, 4), (64, 6, 6)], [700, 90], seed=3)
+st = Step(cfg.params, cfg.prefix_len, cfg.Hq, cfg.Hkv, cfg.D, cfg.V)
+dt_synth.fill_draft_and_qkv(st, cfg)
+st.target_logits.copy_(torch.randn(st.target_logits.shape, device="cuda").to(torch.bfloat16) * 3)
+torch.cuda.synchronize()
+side = torch.cuda.Stream()
+g = torch.cuda.CUDAGraph()
+with torch.cuda.stream(side):
+    with torch.cuda.graph(g, stream=side):
+        st.run(philox_step=0)              # the library's first call in this process
+torch.cuda.synchronize()
+names = ("n_nodes", "tokens", "parents", "anc_mask", "out", "accept_len", "out_tokens")
+for rep in range(3):
+    for n in names:
+        getattr(st, n).fill_(3)
+    g.replay()
+    torch.cuda.synchronize()
+    got = [getattr(st, n).clone() for n in names]
+    for n in names:
+        getattr(st, n).fill_(3)
+    st.run(philox_step=0)
+    torch.cuda.synchronize()
+    for n, a in zip(names, got):
+        assert torch.equal(a, getattr(st, n)), (rep, n)
+    assert int(st.n_nodes[0]) == 40 and int(st.n_nodes[1]) == 64
+print("FIRST-CALL-CAPTURE-OK")
+""" % root
+    r = subprocess.run([sys.executable, "-c", child], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "FIRST-CALL-CAPTURE-OK" in r.stdout, (r.returncode, r.stdout[-2000:], r.stderr[-2000:])

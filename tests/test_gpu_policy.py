@@ -41,7 +41,7 @@ def run_policy(B, F, H, bf16, N, sample, steps, seed):
     queried = torch.zeros(B, **i32)
     logits_out = torch.zeros((B, A), dtype=torch.float32, device="cuda")
     ws = torch.empty(dt.dt_policy_workspace_bytes(B, F, H), dtype=torch.uint8, device="cuda")
-    compared = 0
+    compared = close_calls = 0
     for t in range(steps):
         x = rng.standard_normal((B, F)).astype(np.float32)
         if bf16:
@@ -62,8 +62,18 @@ def run_policy(B, F, H, bf16, N, sample, steps, seed):
                 got = logits_out[b].cpu().numpy()
                 assert np.abs(got - lg).max() < LOGIT_TOL, (t, b, np.abs(got - lg).max())
                 if r["margin"] < (SAMPLE_GUARD if sample else GREEDY_GUARD):
-                    # too close to call across precisions: follow the device and go on
-                    o_cs[b], o_ca[b] = r["cache_step"], int(action_out[b])
+                    # too close to call across precisions: both neighbours of the deciding gap are correct.
+                    # The device's choice must be one of them (greedy: a logit within the guard of the
+                    # oracle's best; sampling: the chosen CDF bin or one next to it); the checker then
+                    # continues from that choice, and such steps are counted.
+                    dev_act = int(action_out[b])
+                    if sample:
+                        assert abs(dev_act - r["action"]) <= 1, (t, b, dev_act, r["action"])
+                    else:
+                        assert lg.max() - lg[dev_act] < GREEDY_GUARD, (t, b, dev_act, r["action"])
+                    assert int(cached[b]) == dev_act and int(cache_step[b]) == r["cache_step"]
+                    o_cs[b], o_ca[b] = r["cache_step"], dev_act
+                    close_calls += 1
                     continue
             else:
                 assert (logits_out[b] == -77.0).all()             # nothing evaluated for a cached action
@@ -72,7 +82,8 @@ def run_policy(B, F, H, bf16, N, sample, steps, seed):
             assert int(cache_step[b]) == r["cache_step"] and int(cached[b]) == r["cached_action"]
             assert tuple(int(v) for v in params_out[b]) == tuple(int(v) for v in table[r["action"]])
             compared += 1
-    assert compared > 0.8 * B * steps
+    print("policy parity: %d decisions compared exactly, %d inside the guard" % (compared, close_calls))
+    assert compared > 0.8 * B * steps and close_calls <= 0.1 * B * steps
 
 
 def test_policy_llama_features_greedy_with_interval():
