@@ -89,14 +89,15 @@ def test_topk_rows_unaligned_row_stride_takes_the_scalar_path():
 # ------------------------------------------------------------------------- whole step on the configs
 
 # Attention bars.  The target's bar: max-abs 2e-2 (bf16) / 1e-5 (fp32).  Our own, tighter one for bf16: both
-# sides round their result to bf16 once, so two results whose unrounded values differ by e lie at most one
-# bf16 ulp (<= 2^-7 |O|) plus e apart; e comes from the probabilities being rounded to bf16 before the second
-# product (relative 2^-9 each, averaging out over the keys) and from fp32 accumulation: |out - want| <=
-# OWN_ABS + 2^-7 |want|.  The observed maxima on the MI355X are printed by every test (pytest -rP shows them)
-# and OWN_ABS is about four times the largest of them.
+# sides round their result to bf16 once (half an ulp each, an ulp being at most 2^-7 |O|), and the unrounded
+# values differ by e: the probabilities are rounded to bf16 before the second product (relative 2^-9 each,
+# partly averaging out over the keys, so e grows with |O| too) and sums are fp32.  Bound:
+# |out - want| <= OWN_ABS + 2^-6 |want|.  On the five configurations |O| <= 0.4 and the observed max-abs error
+# is 4.9e-4 .. 2.0e-3; edge cases with a handful of keys reach |O| ~ 4 and 1.6e-2, still inside this bound and
+# the target's.  Every test prints what it observed (pytest -rP shows it).
 NORTH_STAR_TOL = {"f32": 1e-5, "bf16": 2e-2}
 OWN_ABS = {"f32": 2e-6, "bf16": 2e-3}
-OWN_REL = {"f32": 0.0, "bf16": 2.0 ** -7}
+OWN_REL = {"f32": 0.0, "bf16": 2.0 ** -6}
 
 _CASES, _ATTN = {}, {}
 
@@ -127,7 +128,7 @@ def assert_attention(out, want, dtype, tag):
     assert np.isfinite(out).all(), (tag, "non-finite attention output")
     diff = np.abs(out - want)
     err = float(diff.max())
-    own = float((diff - OWN_REL[dtype] * np.abs(want)).max())      # what is left after one ulp of the result
+    own = float((diff - OWN_REL[dtype] * np.abs(want)).max())      # what is left after two ulps of the result
     assert err <= NORTH_STAR_TOL[dtype], (tag, "attention max-abs", err)
     assert own <= OWN_ABS[dtype], (tag, "attention error above our own bound", own, err)
     return err, own
@@ -146,7 +147,7 @@ def check_case(case, key=None):
         assert_accept_equal(st.accepted(b), case.accepts[b], tag)
         e, o = assert_attention(st.attention_out(b), oracle_attention(case, b, st.scale, key), c.dtype, tag)
         worst, worst_own = max(worst, e), max(worst_own, o)
-    print("attention error %s: max-abs %.3e, beyond one ulp of the result %.3e (all %d outputs compared)"
+    print("attention error %s: max-abs %.3e, beyond two ulps of the result %.3e (all %d outputs compared)"
           % (c.name, worst, worst_own, sum(t["n_nodes"] for t in case.trees) * c.Hq * c.D))
     return st
 
