@@ -93,10 +93,11 @@ def test_topk_rows_unaligned_row_stride_takes_the_scalar_path():
 # values differ by e: the probabilities are rounded to bf16 before the second product (relative 2^-9 each,
 # partly averaging out over the keys, so e grows with |O| too) and sums are fp32.  Bound:
 # |out - want| <= OWN_ABS + 2^-6 |want|.  On the five configurations |O| <= 0.4 and the observed max-abs error
-# is 4.9e-4 .. 2.0e-3; edge cases with a handful of keys reach |O| ~ 4 and 1.6e-2, still inside this bound and
-# the target's.  Every test prints what it observed (pytest -rP shows it).
+# is 4.9e-4 .. 2.0e-3 (5e-4 beyond the two ulps); trees without a prefix (a handful of keys per node) reach
+# |O| ~ 4, 1.6e-2 max-abs and 2.0e-3 beyond the two ulps, the largest seen: OWN_ABS is twice that.
+# Every test prints what it observed (pytest -rP shows it).
 NORTH_STAR_TOL = {"f32": 1e-5, "bf16": 2e-2}
-OWN_ABS = {"f32": 2e-6, "bf16": 2e-3}
+OWN_ABS = {"f32": 2e-6, "bf16": 4e-3}
 OWN_REL = {"f32": 0.0, "bf16": 2.0 ** -6}
 
 _CASES, _ATTN = {}, {}
