@@ -66,8 +66,9 @@ typedef enum {
 
 /*
  * One-time set-up for the CURRENT device: asks the runtime for the device's number of compute
- * units (launch shapes depend on it) and gives the kernels that use more than 64 KB of LDS
- * leave to do so (hipFuncSetAttribute).  No allocation, no launch, no stream operation.
+ * units (launch shapes depend on it), gives the kernels that use more than 64 KB of LDS leave
+ * to do so (hipFuncSetAttribute) and looks up the device's address of the library's own
+ * scratch (dt_topk_rows_static).  No allocation, no launch, no stream operation.
  * Thread-safe and idempotent; every launching entry point does the same on its first call on a
  * device, so calling dt_init() is optional -- but a caller that records its first call into a
  * HIP graph, or calls from several threads at once at start-up, may prefer to have it done
@@ -102,6 +103,23 @@ int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq,
  */
 int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, int V, int64_t row_stride,
                  int k, float *top_val, int32_t *top_id, float *lse, void *ws, size_t ws_bytes);
+
+/*
+ * dt_topk_rows for callers that cannot allocate device memory and hold no workspace: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs, outputs,
+ * kernels and results as dt_topk_rows; the scratch (lane maxima and log-sum-exp partials) lives in
+ * device memory that belongs to the library -- DT_STATIC_SCRATCH_BYTES per device that runs it, held
+ * until the process ends -- and the call makes no allocation of any kind.
+ * Limit: rows * ceil(V / c) * 1056 bytes must fit (c = 2048, 4096 or 8192: the smallest that keeps a row
+ * within 16 chunks, 8192 beyond that): 496 rows of a 128,256-entry vocabulary, 1,986 of 32,000.
+ * More -> DT_ERR_LIMIT, nothing is launched.  Other errors as dt_topk_rows.
+ * All calls on one device share that device's scratch, which keeps the previous call's contents (none
+ * of it needs clearing): calls that overlap on one device -- different streams, or graphs that replay
+ * concurrently -- race; order them.
+ */
+#define DT_STATIC_SCRATCH_BYTES (8u << 20)
+int dt_topk_rows_static(void *stream, const void *logits, dt_dtype t, int64_t n_rows, int V, int64_t row_stride,
+                        int k, float *top_val, int32_t *top_id, float *lse);
 
 /*
  * Draft-tree construction for a batch (paper Section 3.2 "Draft Tree Expansion" and

@@ -43,6 +43,8 @@ def load_library():
         lib.dt_hip_error_string.argtypes = [i32]
         lib.dt_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, i32, C.POINTER(sz)]
         lib.dt_topk_rows.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, vp, vp, vp, sz]
+        lib.dt_topk_rows_static.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, vp, vp]
+        lib.dt_topk_rows_static.restype = i32
         lib.dt_build_tree.argtypes = [vp, i32, vp, vp, i32, i32, i64, vp, i64, vp, i32] + [vp] * 8 + [vp, sz]
         lib.dt_tree_attention.argtypes = [vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64,
                                           vp, i32, vp, vp, sz]
@@ -115,6 +117,13 @@ def dt_topk_rows(logits, k, top_val, top_id, lse, ws):
     _check("dt_topk_rows", load_library().dt_topk_rows(
         _stream(), _ptr(logits), _dtype(logits), n_rows, V, logits.stride(0), k, _ptr(top_val), _ptr(top_id),
         _ptr(lse), _ptr(ws), ws.numel() * ws.element_size()))
+
+
+def dt_topk_rows_static(logits, k, top_val, top_id, lse):
+    n_rows, V = logits.shape
+    _check("dt_topk_rows_static", load_library().dt_topk_rows_static(
+        _stream(), _ptr(logits), _dtype(logits), n_rows, V, logits.stride(0), k, _ptr(top_val), _ptr(top_id),
+        _ptr(lse)))
 
 
 def dt_build_tree(params, draft_logits, row_off, total_rows, root_token, TT_cap, n_nodes, tokens, parents, depth,

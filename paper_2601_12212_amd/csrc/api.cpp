@@ -20,7 +20,14 @@ constexpr int MAX_DEVICES = 64;
 struct DeviceState {
     std::atomic<int> ready{0};
     int n_cu = 0;
+    void *scratch = nullptr;  // this device's copy of g_scratch
 };
+
+// Scratch of dt_topk_rows_static: device memory that belongs to the library, so that the call needs no
+// workspace and allocates nothing.  Every device that runs the library holds its own copy, at its own
+// address, until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress: the address kernels and copies use is the one kept per device in DeviceState.
+static __device__ __align__(256) unsigned char g_scratch[DT_STATIC_SCRATCH_BYTES];
 DeviceState g_dev[MAX_DEVICES];
 std::mutex g_init_mu;
 
@@ -38,13 +45,23 @@ int ensure_init(int *n_cu) {
             e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
             if (e == hipSuccess) e = dt::tree_init();
             if (e == hipSuccess) e = dt::attn_init();
-            if (e != hipSuccess || n < 1) { g_last_hip = (int)e; (void)hipGetLastError(); return DT_ERR_HIP; }
+            void *sp = nullptr;
+            if (e == hipSuccess) e = hipGetSymbolAddress(&sp, HIP_SYMBOL(g_scratch));
+            if (e != hipSuccess || n < 1 || !sp) { g_last_hip = (int)e; (void)hipGetLastError(); return DT_ERR_HIP; }
             d.n_cu = n;
+            d.scratch = sp;
             d.ready.store(1, std::memory_order_release);
         }
     }
     if (n_cu) *n_cu = d.n_cu;
     return DT_OK;
+}
+
+// the current device's copy of the library-owned scratch (after ensure_init succeeded on it)
+void *device_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    return g_dev[dev].ready.load(std::memory_order_acquire) ? g_dev[dev].scratch : nullptr;
 }
 
 // compute units for sizing a workspace: of the current device if there is one, else of an MI355X
@@ -194,6 +211,24 @@ int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, i
     e = dt::rows_launch_select(a, n_rows, nl, top_val, top_id, lse, k, st);
     if (e != hipSuccess) return hip_fail(e);
     return DT_OK;
+}
+
+int dt_topk_rows_static(void *stream, const void *logits, dt_dtype t, int64_t n_rows, int V, int64_t row_stride, int k,
+                        float *top_val, int32_t *top_id, float *lse) {
+    // the argument checks of dt_topk_rows come first, so that both calls refuse the same inputs alike
+    if (!logits || !top_val || !top_id || !lse || n_rows < 0 || bad_dtype(t) || row_stride < V)
+        return DT_ERR_INVALID_ARG;
+    if (!topk_v_ok(V) || k < 1 || k > DT_K_MAX || k > V) return DT_ERR_LIMIT;
+    if (n_rows == 0) return DT_OK;
+    const int S = dt::rows_chunks_per_row(V, dt::rows_topk_nl(V));
+    if (n_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
+    if (topk_scratch(nullptr, n_rows, S).bytes > (size_t)DT_STATIC_SCRATCH_BYTES) return DT_ERR_LIMIT;
+    if (int rc = ensure_init(nullptr)) return rc;
+    void *ws = device_scratch();
+    if (!ws) return DT_ERR_HIP;
+    // nothing in this scratch has to start from zero: every word the selection reads is written by the
+    // streaming pass of the same call
+    return dt_topk_rows(stream, logits, t, n_rows, V, row_stride, k, top_val, top_id, lse, ws, DT_STATIC_SCRATCH_BYTES);
 }
 
 int dt_build_tree(void *stream, int batch, const dt_params *params, const void *draft_logits, dt_dtype t, int V,
