@@ -99,7 +99,7 @@ int dt_workspace_bytes(int batch, int64_t total_rows, int V, int TT_cap, int Hq,
  *   lse      [n_rows]   float  : log sum_v exp(logits[r, v])
  * Slots beyond the number of finite entries of a row hold (-inf, -1).
  * Errors: k < 1 or k > min(DT_K_MAX, V) -> DT_ERR_LIMIT; V beyond 524,288 or more than 2^31 - 1
- * (row, 8192-entry chunk) pairs in one call -> DT_ERR_LIMIT.
+ * rows in one call -> DT_ERR_LIMIT.
  */
 int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, int V, int64_t row_stride,
                  int k, float *top_val, int32_t *top_id, float *lse, void *ws, size_t ws_bytes);
@@ -211,7 +211,7 @@ int dt_tree_attention(void *stream, int batch, dt_dtype t, int Hq, int Hkv, int 
  *                                    temperature) at the uniform with node index 0xFFFFFFFF), then -1
  *   node_argmax[batch, TT_cap]       argmax of every node row (may be NULL)
  * Errors: stochastic / sampled with temperature <= 0, stochastic with logp NULL -> DT_ERR_INVALID_ARG;
- * more than 2^31 - 1 (row, chunk) pairs over the batch*TT_cap rows -> DT_ERR_LIMIT.
+ * batch*TT_cap beyond 2^31 - 1 rows -> DT_ERR_LIMIT.
  */
 int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, const void *target_logits,
               dt_dtype t, int V, int64_t row_stride, const int32_t *n_nodes, const int32_t *tokens,

@@ -76,7 +76,8 @@ int cu_count_for_sizing() {
     return 256;
 }
 
-// launch grids: x up to 2^31 - 1 workgroups, y and z up to 65535
+// launch grids: x up to 2^31 - 1 workgroups, y and z up to 65535; rows ride in y and z (65535^2 of them),
+// and the row selection takes one workgroup per row in x
 constexpr int64_t GRID_X_MAX = 2147483647ll;
 constexpr int GRID_YZ_MAX = 65535;
 
@@ -194,7 +195,7 @@ int dt_topk_rows(void *stream, const void *logits, dt_dtype t, int64_t n_rows, i
     if (!topk_v_ok(V) || k < 1 || k > DT_K_MAX || k > V) return DT_ERR_LIMIT;
     if (n_rows == 0) return DT_OK;
     const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
-    if (n_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
+    if (n_rows > GRID_X_MAX) return DT_ERR_LIMIT;
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     TopkScratch rs = topk_scratch(ws, n_rows, S);
     if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
@@ -221,7 +222,7 @@ int dt_topk_rows_static(void *stream, const void *logits, dt_dtype t, int64_t n_
     if (!topk_v_ok(V) || k < 1 || k > DT_K_MAX || k > V) return DT_ERR_LIMIT;
     if (n_rows == 0) return DT_OK;
     const int S = dt::rows_chunks_per_row(V, dt::rows_topk_nl(V));
-    if (n_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
+    if (n_rows > GRID_X_MAX) return DT_ERR_LIMIT;
     if (topk_scratch(nullptr, n_rows, S).bytes > (size_t)DT_STATIC_SCRATCH_BYTES) return DT_ERR_LIMIT;
     if (int rc = ensure_init(nullptr)) return rc;
     void *ws = device_scratch();
@@ -243,7 +244,7 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     if (!topk_v_ok(V) || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
     if (total_rows < batch) return DT_ERR_INVALID_ARG;  // every sequence owns at least its root row
     const int nl = dt::rows_topk_nl(V), S = dt::rows_chunks_per_row(V, nl);
-    if (total_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
+    if (total_rows > GRID_X_MAX) return DT_ERR_LIMIT;
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     char *wsd = (char *)ws;
     TopkScratch rs = topk_scratch(wsd, total_rows, S);
@@ -327,7 +328,7 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
     if (V < 1 || min_nl(V) == 0 || TT_cap < 1 || TT_cap > DT_TT_MAX) return DT_ERR_LIMIT;
     const int64_t rows = (int64_t)batch * TT_cap;
     const int nl = pick_nl(rows, V), S = dt::rows_chunks_per_row(V, nl);
-    if (rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
+    if (rows > GRID_X_MAX) return DT_ERR_LIMIT;
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     ArgmaxScratch rs = argmax_scratch(ws, rows, S);
     int32_t *samples = (int32_t *)((char *)ws + rs.bytes);  // target-sampled mode: one token per node
@@ -379,7 +380,7 @@ int dt_expand_level(void *stream, int batch, int level, const dt_params *params,
     if (!ws || (uintptr_t)ws % 256) return DT_ERR_WORKSPACE;
     TopkScratch rs = topk_scratch(ws, total_rows, S);
     if (rs.bytes > ws_bytes) return DT_ERR_WORKSPACE;
-    if (total_rows > GRID_X_MAX / S) return DT_ERR_LIMIT;
+    if (total_rows > GRID_X_MAX) return DT_ERR_LIMIT;
     if (int rc = ensure_init(nullptr)) return rc;
     LevelState ls = level_state(state, batch);
 

@@ -47,7 +47,7 @@ struct RowArgs {
     // ROWS_LEVEL: rows of one level of every sequence, results scattered into the build state
     int level, rows_per_seq, state_rows;
     const int32_t *n_exp_prev;  // [batch] nodes expanded one level up
-    int chunks;  // set by the launch functions: workgroups per row
+    int64_t n_rows;  // set by the launch functions: rows of the launch (the grid may overhang)
     // set by the launch functions: read a row's chunk before the row is known to be live (the loads then
     // overlap the reads that decide it; the row is inside the caller's buffer either way)
     int early_load;

@@ -148,11 +148,13 @@ __device__ __forceinline__ float2 wave_lse_partial(const float (&x)[E], float mx
 template <int NL, bool BF16, bool VEC>
 __global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
     constexpr int E = 8 * NL;
-    // workgroup (row g, chunk c) is number g * chunks + c of a one-dimensional grid
-    const int64_t g = blockIdx.x / (unsigned)a.chunks;
-    const int c = (int)(blockIdx.x % (unsigned)a.chunks);
+    // workgroup (chunk c, row g): the chunk rides in grid x, the row in y and -- past 65,535 rows -- z
+    // (no division in front of the loads: a streaming workgroup's life is one trip to memory long)
+    const int64_t g = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+    const int c = blockIdx.x;
     const int lane = lane_id(), w = threadIdx.x >> 6;
     const int base = c * (256 * E) + w * (64 * E) + lane * 8;
+    if (g >= a.n_rows) return;
     float x[E];
     if (a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
     const RowMeta meta = row_meta(a, g);
@@ -161,7 +163,7 @@ __global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
     float mx = x[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
-    const int64_t wslot = (int64_t)blockIdx.x * 4 + w;
+    const int64_t wslot = (g * gridDim.x + c) * 4 + w;
     a.lane_max[wslot * 64 + lane] = mx;
     if (a.want_lse) {
         const float2 p = wave_lse_partial<E>(x, mx, a.inv_t);
@@ -406,13 +408,14 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
 template <int NL, bool BF16, bool VEC>
 __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
     constexpr int E = 8 * NL;
-    const int64_t g = blockIdx.x / (unsigned)a.chunks;
-    const int c = (int)(blockIdx.x % (unsigned)a.chunks);
+    const int64_t g = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+    const int c = blockIdx.x;
     const int lane = lane_id(), w = threadIdx.x >> 6;
     __shared__ u64 s_wout[4];
     __shared__ float s_m[4], s_s[4];
 
     const int base = c * (256 * E) + w * (64 * E) + lane * 8;
+    if (g >= a.n_rows) return;
     float x[E];
     if (a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
     const RowMeta meta = row_meta(a, g);
@@ -438,7 +441,7 @@ __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
     if (lane == 0) s_wout[w] = key;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const int64_t slot = blockIdx.x;
+        const int64_t slot = g * gridDim.x + c;
         u64 b01 = s_wout[0] > s_wout[1] ? s_wout[0] : s_wout[1];
         u64 b23 = s_wout[2] > s_wout[3] ? s_wout[2] : s_wout[3];
         a.part_keys[slot] = b01 > b23 ? b01 : b23;
@@ -478,6 +481,13 @@ int rows_pick_nl(int64_t n_rows, int V) {
     return 1;
 }
 
+// (chunks, rows) as a launch grid: rows beyond what grid y holds continue in z; the last z-slab may
+// overhang, its workgroups leave at once
+static dim3 rows_grid(int chunks, int64_t n_rows) {
+    const int64_t ny = n_rows < 65535 ? n_rows : 65535;
+    return dim3((unsigned)chunks, (unsigned)ny, (unsigned)((n_rows + ny - 1) / ny));
+}
+
 static bool rows_vec_ok(const RowArgs &a) {
     const int esz = a.dtype == DT_BF16 ? 2 : 4;
     return ((uintptr_t)a.logits % 16 == 0) && ((a.row_stride * esz) % 16 == 0);
@@ -507,8 +517,8 @@ hipError_t rows_launch_stream(const RowArgs &a_in, int64_t n_rows, int nl, hipSt
     a.early_load = a.mode == ROWS_DRAFT || a.mode == ROWS_UNIFORM || n_rows * rows_chunks_per_row(a.V, nl) <= EARLY_LOAD_WGS;
     const bool vec = rows_vec_ok(a);
     const int kid = a.mode == ROWS_DRAFT ? KID_ROWS_DRAFT : KID_ROWS_UNIFORM;
-    a.chunks = rows_chunks_per_row(a.V, nl);
-#define STREAM_GRID(NLV) dim3((unsigned)(n_rows * a.chunks))
+    a.n_rows = n_rows;
+#define STREAM_GRID(NLV) rows_grid(rows_chunks_per_row(a.V, NLV), n_rows)
     switch (nl) {
         case 4: DT_ROWS_DISPATCH(kid, row_stream_kernel, 4, STREAM_GRID(4)); break;
         case 2: DT_ROWS_DISPATCH(kid, row_stream_kernel, 2, STREAM_GRID(2)); break;
@@ -539,8 +549,8 @@ hipError_t rows_launch_argmax(const RowArgs &a_in, int64_t n_rows, int nl, hipSt
     RowArgs a = a_in;
     a.early_load = n_rows * rows_chunks_per_row(a.V, nl) <= EARLY_LOAD_WGS;
     const bool vec = rows_vec_ok(a);
-    a.chunks = rows_chunks_per_row(a.V, nl);
-#define STREAM_GRID(NLV) dim3((unsigned)(n_rows * a.chunks))
+    a.n_rows = n_rows;
+#define STREAM_GRID(NLV) rows_grid(rows_chunks_per_row(a.V, NLV), n_rows)
     switch (nl) {
         case 4: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 4, STREAM_GRID(4)); break;
         case 2: DT_ROWS_DISPATCH(KID_ROWS_TARGET, row_argmax_kernel, 2, STREAM_GRID(2)); break;

@@ -129,15 +129,16 @@ def test_bad_arguments_are_rejected_before_any_launch():
 
 
 def test_launch_grid_limits_are_checked_on_the_host():
-    """Rows ride in the x dimension of the launch grid (2^31 - 1 workgroups): row counts beyond 65,535 are
-    ordinary, and a call whose (row, chunk) pairs would not fit returns DT_ERR_LIMIT before the workspace is
-    even looked at.  Sequences ride in the z dimension of the attention grid (with up to 8 key splits)."""
+    """Rows ride in the y and z dimensions of the streaming grids and in x of the selection grid: row counts
+    beyond 65,535 are ordinary, and a call with more than 2^31 - 1 rows returns DT_ERR_LIMIT before the
+    workspace is even looked at.  Sequences ride in the z dimension of the attention grid (with up to 8 key
+    splits)."""
     lib = dt.load_library()
     one, ws = C.c_void_p(256), C.c_void_p(4096)
     # 70,000 rows: past the limit check (the tiny workspace is what is refused)
     assert lib.dt_topk_rows(None, one, 1, 70000, 1024, 1024, 4, one, one, one, ws, 16) == -3
     assert lib.dt_topk_rows(None, one, 1, 1 << 31, 1024, 1024, 4, one, one, one, ws, 1 << 40) == -2
-    assert lib.dt_topk_rows(None, one, 1, (1 << 31) // 16 + 1, 128256, 128256, 4, one, one, one, ws, 1 << 40) == -2
+    assert lib.dt_topk_rows(None, one, 1, (1 << 31) - 1, 1024, 1024, 4, one, one, one, ws, 16) == -3
     acc = lambda batch, TT_cap, wsb: [None, batch, 0, 1.0, one, 1, 1024, 1024, one, one, one, one, one, one, TT_cap, 0, 0,
                                        one, one, one, one, None, ws, wsb]
     assert lib.dt_accept(*acc(512, 128, 16)) == -3              # 65,536 rows: fine
