@@ -174,15 +174,18 @@ __global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
 // ------------------------------------------------------------- selection kernel (top-k rows) --
 // One workgroup per row, working on the row's S*256 lane maxima:
 //   1. every thread takes the maximum of its S lane maxima; each wave finds the k-th largest of
-//      its 64 thread maxima (ballot bisection); the largest of the four is a lower bound T0 of
-//      the row's k-th largest lane maximum;
-//   2. lane maxima >= T0 (a few dozen) are compacted; their k-th largest, T, is a lower bound
-//      of the row's k-th largest ELEMENT, and only lanes whose maximum reaches T ("hot" lanes,
-//      about k of them) can hold a winner;
-//   3. the hot lanes' 8*NL elements are read again (they sit in L2), elements >= T are keyed
-//      by (value, id) and ranked.
-// Any overflow of the small lists (rows dominated by ties, fewer than k finite entries)
-// switches to an exact but slow extract-max loop over the whole row.
+//      its 64 thread maxima (ballot bisection); the largest of the four, T0, is a lower bound of
+//      the row's k-th largest lane maximum (loose: up to a few hundred lane maxima reach it);
+//   2. the lane maxima >= T0 go into a histogram over their distance from T0 in steps of the upper
+//      16 key bits (for bf16 data: in representable values), and a scan from the top names the bin
+//      of the k-th largest lane maximum.  Its lower edge T1 is a lower bound of the row's k-th
+//      largest ELEMENT (k different lanes hold an element >= T1), and only lanes whose maximum
+//      reaches T1 ("hot" lanes: k of them plus ties at the edge) can hold a winner;
+//   3. the hot lanes' 8*NL elements are read again (they sit in L2), elements >= T1 are keyed
+//      by (value, id) and ranked by counting.
+// More than 128 hot lanes or candidates (rows dominated by ties, fewer than k finite entries)
+// switch to an exact but slow extract-max loop over the whole row.
+#define SEL_CAP 128
 __device__ __forceinline__ float load_elem(const RowArgs &a, int64_t g, int id) {
     if (a.dtype == DT_BF16) return bf16_bits_to_float(((const uint16_t *)a.logits)[g * a.row_stride + id]);
     return ((const float *)a.logits)[g * a.row_stride + id];
@@ -197,24 +200,25 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     const int n_lanes = S * 256;
     const float *lm = a.lane_max + g * n_lanes;
     // the lane maxima do not depend on the row's metadata (two dependent global reads): ask for them
-    // first.  Rows that turn out to be dead have their slots in the workspace all the same.
+    // first, and wave 3 for the row's (max, sum) partials.  Rows that turn out to be dead have their
+    // slots in the workspace all the same.
     float it[16];
     if (S <= 16) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) it[j] = lm[min(j, S - 1) * 256 + tid];
     }
+    const bool lse_wave = w == 3 && a.want_lse && lse;
+    float2 pm = make_float2(-INFINITY, 0.f);
+    if (lse_wave && S <= 16) pm = a.part_ms[g * S * 4 + min(lane, S * 4 - 1)];
     const RowMeta meta = row_meta(a, g);
     if (!meta.valid) return;
     const int k = meta.k;
 
     __shared__ float s_T[4];
-    __shared__ float s_c1v[4][128];  // 64 list slots, then one spare word per lane
-    __shared__ int s_c1l[4][128];
-    __shared__ int s_c1n[4];
-    __shared__ int s_hot[64];
+    __shared__ __attribute__((aligned(16))) u32 s_hist[256];
+    __shared__ int s_hot[SEL_CAP];
     __shared__ int s_h;
-    __shared__ float s_Trow;
-    __shared__ u64 s_fin[64];
+    __shared__ u64 s_fin[SEL_CAP];
     __shared__ int s_n2;
     __shared__ u64 s_best[4];
 
@@ -241,59 +245,64 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     }
     const float Tw = unord32(wave_kth_largest<BF16 ? 16 : 0>(ord32(tmax), k));
     if (lane == 0) s_T[w] = Tw;
-    if (tid == 0) s_n2 = 0;
+    if (tid == 0) { s_n2 = 0; s_h = 0; }
+    s_hist[tid] = 0u;
     __syncthreads();
     const float T0 = fmaxf(fmaxf(s_T[0], s_T[1]), fmaxf(s_T[2], s_T[3]));
 
-    // ---- 2. lane maxima >= T0, compacted per wave ---------------------------------------------
-    int cnt = 0;
+    // ---- 2. histogram of the lane maxima >= T0; its scan from the top gives T1 ------------------
+    const u32 key0 = ord32(T0) >> 16;
     if (S <= 16) {
-        // hits are rare (a few dozen of S*256): count them per thread, place them with one wave scan
-        int mine = 0;
 #pragma unroll
-        for (int j = 0; j < 16; ++j) mine += it[j] >= T0 ? 1 : 0;
-        int at = wave_scan_incl_i32(mine);
-        cnt = __builtin_amdgcn_readlane(at, 63);
-        at -= mine;
-        if (mine > 0) {
-            // no branch per value: a miss (or a slot past the list) goes to this lane's own spare word
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const bool hit = it[j] >= T0;
-                const int dst = hit && at < 64 ? at : 64 + lane;
-                s_c1v[w][dst] = it[j];
-                s_c1l[w][dst] = j * 256 + tid;
-                at += hit ? 1 : 0;
-            }
-        }
+        for (int j = 0; j < 16; ++j)
+            if (it[j] >= T0) atomicAdd(&s_hist[min((ord32(it[j]) >> 16) - key0, 255u)], 1u);
     } else {
         for (int j = 0; j < S; ++j) {
             const float v = lm[j * 256 + tid];
-            const bool hit = v >= T0;
-            const u64 m = __ballot(hit);
-            if (m) {
-                const int slot = cnt + (int)lanes_below(m);
-                if (hit && slot < 64) { s_c1v[w][slot] = v; s_c1l[w][slot] = j * 256 + tid; }
-                cnt += __popcll(m);
-            }
+            if (v >= T0) atomicAdd(&s_hist[min((ord32(v) >> 16) - key0, 255u)], 1u);
         }
     }
-    if (lane == 0) s_c1n[w] = cnt;
     __syncthreads();
-    const int c0 = s_c1n[0], c1 = s_c1n[1], c2 = s_c1n[2], c3 = s_c1n[3];
-    const int n1 = c0 + c1 + c2 + c3;
-    bool slow = n1 > 64;  // uniform over the workgroup
+    // every wave by itself: lane L holds bins 4(63-L) .. 4(63-L)+3, so an ascending lane scan walks the
+    // bins downwards; at least k lane maxima reach T0, so the scan finds its bin
+    int n_hot;      // lane maxima >= T1
+    float T1;
+    {
+        const uint4 hb = *(const uint4 *)&s_hist[4 * (63 - lane)];
+        const int c4 = (int)(hb.x + hb.y + hb.z + hb.w);
+        const int incl = wave_scan_incl_i32(c4);
+        const u64 m = __ballot(incl >= k);
+        const int ls = m ? (int)__builtin_ctzll(m) : 63;
+        int acc = __builtin_amdgcn_readlane(incl - c4, ls);
+        const int h3 = __builtin_amdgcn_readlane((int)hb.w, ls), h2 = __builtin_amdgcn_readlane((int)hb.z, ls),
+                  h1 = __builtin_amdgcn_readlane((int)hb.y, ls), h0 = __builtin_amdgcn_readlane((int)hb.x, ls);
+        int dg;
+        if (acc + h3 >= k) { dg = 3; acc += h3; }
+        else if (acc + h3 + h2 >= k) { dg = 2; acc += h3 + h2; }
+        else if (acc + h3 + h2 + h1 >= k) { dg = 1; acc += h3 + h2 + h1; }
+        else { dg = 0; acc += h3 + h2 + h1 + h0; }
+        n_hot = acc;
+        // the lower edge of that bin: the smallest float whose upper 16 key bits are the bin's (bin 255 also
+        // holds everything farther up: its lower edge still bounds all of it)
+        T1 = unord32((key0 + (u32)(4 * (63 - ls) + dg)) << 16);
+        T1 = fmaxf(T1, T0);  // bin 0 starts at T0 itself, not at the edge below it
+    }
+    bool slow = n_hot > SEL_CAP || n_hot < k;  // uniform over the workgroup
 
-    // ---- the row's log-sum-exp, by wave 1 while wave 0 selects -----------------------------
-    if (w == 1 && a.want_lse && lse) {
+    // ---- the row's log-sum-exp, by wave 3 --------------------------------------------------------
+    if (lse_wave) {
         const float cexp = 1.4426950408889634f * a.inv_t;
         float M = -INFINITY, Ssum = 0.f;
-        for (int i = lane; i < S * 4; i += 64) {
-            const float2 p = a.part_ms[g * S * 4 + i];
-            const float M2 = fmaxf(M, p.x);
-            if (M2 != -INFINITY)
-                Ssum = Ssum * __builtin_amdgcn_exp2f((M - M2) * cexp) + p.y * __builtin_amdgcn_exp2f((p.x - M2) * cexp);
-            M = M2;
+        if (S <= 16) {
+            if (lane < S * 4) { M = pm.x; Ssum = pm.y; }
+        } else {
+            for (int i = lane; i < S * 4; i += 64) {
+                const float2 p = a.part_ms[g * S * 4 + i];
+                const float M2 = fmaxf(M, p.x);
+                if (M2 != -INFINITY)
+                    Ssum = Ssum * __builtin_amdgcn_exp2f((M - M2) * cexp) + p.y * __builtin_amdgcn_exp2f((p.x - M2) * cexp);
+                M = M2;
+            }
         }
         const float Mw = wave_max(M);
         float term = (Ssum > 0.f) ? Ssum * __builtin_amdgcn_exp2f((M - Mw) * cexp) : 0.f;
@@ -302,27 +311,30 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     }
 
     if (!slow) {
-        if (w == 0) {
-            // candidate i of the concatenated per-wave lists
-            float v = -INFINITY;
-            int gl = -1;
-            if (lane < n1) {
-                int q = lane, ww = 0;
-                if (q >= c0) { q -= c0; ww = 1; if (q >= c1) { q -= c1; ww = 2; if (q >= c2) { q -= c2; ww = 3; } } }
-                v = s_c1v[ww][q];
-                gl = s_c1l[ww][q];
+        // ---- 3. the hot lanes, in any order: a thread reserves room for its hits with one LDS add ----
+        {
+            int mine = 0;
+            if (S <= 16) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) mine += it[j] >= T1 ? 1 : 0;
+                if (mine > 0) {
+                    int at = atomicAdd(&s_h, mine);
+#pragma unroll
+                    for (int j = 0; j < 16; ++j)
+                        if (it[j] >= T1) { if (at < SEL_CAP) s_hot[at] = j * 256 + tid; ++at; }
+                }
+            } else {
+                for (int j = 0; j < S; ++j)
+                    if (lm[j * 256 + tid] >= T1) {
+                        const int at = atomicAdd(&s_h, 1);
+                        if (at < SEL_CAP) s_hot[at] = j * 256 + tid;
+                    }
             }
-            const float T = unord32(wave_kth_largest<BF16 ? 16 : 0>(ord32(v), k));
-            const bool hot = lane < n1 && v >= T;
-            const u64 m = __ballot(hot);
-            if (hot) s_hot[lanes_below(m)] = gl;
-            if (lane == 0) { s_h = __popcll(m); s_Trow = T; }
         }
         __syncthreads();
-        const int h = s_h;
-        const float T = s_Trow;
+        const int h = min(s_h, SEL_CAP);
         const int nl_log2 = nl == 4 ? 2 : nl == 2 ? 1 : 0;  // chunk multipliers are 1, 2 or 4
-        // ---- 3. re-read the hot lanes: (hot lane, load n) pairs spread over the threads ----
+        // ---- 4. re-read the hot lanes: (hot lane, load n) pairs spread over the threads ----
         for (int q = tid; q < h * nl; q += 256) {
             const int gl = s_hot[q >> nl_log2], n = q & (nl - 1);
             const int c = gl >> 8, ww = (gl >> 6) & 3, l = gl & 63;
@@ -344,13 +356,13 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
             }
             int hits = 0;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) hits += xv[e] >= T ? 1 : 0;
+            for (int e = 0; e < 8; ++e) hits += xv[e] >= T1 ? 1 : 0;
             if (hits > 0) {
                 int slot = atomicAdd(&s_n2, hits);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    if (xv[e] >= T) {
-                        if (slot < 64) s_fin[slot] = make_key(xv[e], (u32)(id0 + e));
+                    if (xv[e] >= T1) {
+                        if (slot < SEL_CAP) s_fin[slot] = make_key(xv[e], (u32)(id0 + e));
                         ++slot;
                     }
                 }
@@ -358,21 +370,22 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
         }
         __syncthreads();
         const int n2 = s_n2;
-        if (n2 <= 64) {
-            if (w == 0) {
-                const u64 mine = lane < n2 ? s_fin[lane] : 0ull;
+        if (n2 <= SEL_CAP) {
+            // ---- 5. candidate t ranks itself against all n2 keys (LDS broadcasts, eight in flight) ----
+            if (tid < SEL_CAP && (tid & ~63) < n2) {  // the waves that hold a candidate
+                const u64 mine = tid < n2 ? s_fin[tid] : 0ull;
                 int r0 = 0, r1 = 0;
-                for (int j0 = 0; j0 < n2; j0 += 8) {  // eight broadcast reads in flight, then the compares
+                for (int j0 = 0; j0 < n2; j0 += 8) {
                     u64 o[8];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) o[j] = s_fin[j0 + j];
+                    for (int j = 0; j < 8; ++j) o[j] = s_fin[min(j0 + j, SEL_CAP - 1)];
 #pragma unroll
-                    for (int j = 0; j < 8; j += 2) {  // s_fin[n2 .. 63] may hold anything: masked
+                    for (int j = 0; j < 8; j += 2) {  // s_fin[n2 ..] may hold anything: masked
                         r0 += j0 + j < n2 && o[j] > mine ? 1 : 0;
                         r1 += j0 + j + 1 < n2 && o[j + 1] > mine ? 1 : 0;
                     }
                 }
-                if (lane < n2 && r0 + r1 < k) emit(r0 + r1, mine);
+                if (tid < n2 && r0 + r1 < k) emit(r0 + r1, mine);
             }
             return;
         }
