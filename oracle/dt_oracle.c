@@ -39,7 +39,8 @@
  *     concatenation of three hidden-state vectors, the policy is a small MLP (Appendix A,
  *     "Network Architecture"), a chosen action is reused for N decision points; Appendix A,
  *     "Action Space in Implementation": the table of actions (ref_action_table,
- *     ref_policy_logits, ref_policy_step).
+ *     ref_policy_logits, ref_policy_step); Section 3.1 "Reward Function" and the averaged reward
+ *     of Section 3.3 (ref_reward_step).
  *
  * Pins: every function here is pinned by tests (library sorts, closed forms,
  * brute-force enumeration of token strings and of root-to-leaf paths, float64
@@ -780,3 +781,35 @@ int ref_policy_step(int *cache_step, int *cached_action, const double *logits, i
     if (*cache_step >= N) *cache_step = 0;
     return act;
 }
+
+/*
+ * Reward of a decision point and its average over the cache interval (Section 3.1 "Reward Function":
+ * accepted tokens divided by the elapsed time of the drafting/verification step; Section 3.3,
+ * "multi-step action persistence": the reward is averaged over the N decoding steps of the cache
+ * interval; Algorithm 1: the reward is computed after verification, before the cache step is reset).
+ *
+ * Called once per decoding step, after ref_policy_step and the verification of that step:
+ *   cache_step     the cache step as ref_policy_step left it (0 = this step was the last of its interval)
+ *   tokens         accepted tokens of the step (the caller decides whether the bonus token counts)
+ *   elapsed        seconds the step took (> 0)
+ *   sum, steps     in/out accumulators of the running interval (start: 0, 0)
+ * Adds tokens / elapsed to the interval's sum.  When the interval ends, *avg = sum / steps (steps = N for
+ * a full interval; a generation that started in the middle of one averages over what it saw), *done = 1
+ * and the accumulators return to zero; otherwise *done = 0 and *avg is left alone.
+ */
+int ref_reward_step(int cache_step, double tokens, double elapsed, double *sum, int *steps, double *avg, int *done)
+{
+    if (!sum || !steps || !avg || !done || !(elapsed > 0.0) || cache_step < 0 || *steps < 0) return REF_ERR_ARG;
+    *sum += tokens / elapsed;
+    *steps += 1;
+    if (cache_step == 0) {
+        *avg = *sum / (double)*steps;
+        *done = 1;
+        *sum = 0.0;
+        *steps = 0;
+    } else {
+        *done = 0;
+    }
+    return REF_OK;
+}
+

@@ -214,6 +214,17 @@ def policy_step(cache_step, cached_action, logits, N, mode=0, seed=0, step=0, se
     return dict(action=act, cache_step=cs.value, cached_action=ca.value, queried=bool(q.value), margin=margin.value)
 
 
+def reward_step(cache_step, tokens, elapsed, acc):
+    """Reward bookkeeping of one decoding step.  acc: dict(sum, steps), updated in place.
+    Returns (done, avg): avg is the interval's average reward when the interval ended with this step."""
+    s, n = C.c_double(acc["sum"]), C.c_int(acc["steps"])
+    avg, done = C.c_double(float("nan")), C.c_int(0)
+    _check(lib().ref_reward_step(int(cache_step), C.c_double(tokens), C.c_double(elapsed), C.byref(s), C.byref(n),
+                                 C.byref(avg), C.byref(done)), "ref_reward_step")
+    acc["sum"], acc["steps"] = s.value, n.value
+    return bool(done.value), avg.value
+
+
 def philox4x32(ctr, key):
     c = (C.c_uint32 * 4)(*ctr)
     k = (C.c_uint32 * 2)(*key)

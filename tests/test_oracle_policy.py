@@ -115,3 +115,56 @@ def test_sampled_actions_follow_the_softmax_and_the_inverse_cdf():
             assert r["action"] == int(np.searchsorted(cdf, u, side="right"))
         counts[r["action"]] += 1
     assert np.abs(counts / T - p).max() < 4 * np.sqrt(0.25 / T)
+
+
+# ------------------------------------------------------- reward averaged over the cache interval
+
+def _run_intervals(N, steps, tokens, elapsed, start=(0, -1)):
+    """Drive the action cache and the reward bookkeeping together for `steps` decision points."""
+    cs, ca = start
+    acc = dict(sum=0.0, steps=0)
+    out = []
+    lg = np.array([0.0, 1.0, 0.5])
+    for t in range(steps):
+        r = ref.policy_step(cs, ca, lg, N)
+        cs, ca = r["cache_step"], r["cached_action"]
+        done, avg = ref.reward_step(cs, tokens[t], elapsed[t], acc)
+        out.append((r["queried"], done, avg))
+    return out, acc
+
+
+@pytest.mark.parametrize("N", [1, 3, 10, 30])
+def test_reward_is_the_mean_of_tokens_per_second_over_each_cache_interval(N):
+    rng = np.random.default_rng(N)
+    steps = 3 * N + (N // 2)
+    tokens = rng.integers(1, 9, steps).astype(np.float64)
+    elapsed = rng.uniform(0.004, 0.03, steps)
+    out, acc = _run_intervals(N, steps, tokens, elapsed)
+    per_step = tokens / elapsed
+    for t, (queried, done, avg) in enumerate(out):
+        assert queried == (t % N == 0)                       # an interval opens with a policy query ...
+        assert done == (t % N == N - 1)                      # ... and closes N decision points later
+        if done:
+            want = per_step[t - N + 1:t + 1].mean()          # the averaged reward: 1/N sum tokens_i / seconds_i
+            assert abs(avg - want) <= 1e-12 * want
+        else:
+            assert np.isnan(avg)                             # nothing reported inside an interval
+    # the open interval at the end keeps its partial sum
+    tail = steps % N
+    assert acc["steps"] == tail and abs(acc["sum"] - per_step[steps - tail:].sum()) < 1e-9
+
+
+def test_reward_closed_forms_and_bad_arguments():
+    N = 10
+    # constant speed: the average is that speed; tokens 1..N in one second each: (N+1)/2
+    out, _ = _run_intervals(N, N, np.full(N, 4.0), np.full(N, 0.02))
+    assert out[-1][1] and abs(out[-1][2] - 200.0) < 1e-9
+    out, _ = _run_intervals(N, N, np.arange(1, N + 1, dtype=np.float64), np.ones(N))
+    assert abs(out[-1][2] - (N + 1) / 2) < 1e-12
+    # a generation that starts in the middle of an interval (4 of 10 steps already used by a cached action)
+    out, _ = _run_intervals(N, 6, np.full(6, 3.0), np.full(6, 0.5), start=(4, 2))
+    assert [d for _, d, _ in out] == [False] * 5 + [True] and abs(out[-1][2] - 6.0) < 1e-12   # mean over the 6 seen
+    acc = dict(sum=0.0, steps=0)
+    for bad in (0.0, -1.0):
+        with pytest.raises(RuntimeError):
+            ref.reward_step(1, 2.0, bad, acc)
