@@ -292,6 +292,25 @@ int dt_policy_step(void *stream, int batch, dt_dtype feat_t, const void *feature
                    int32_t *action_out, int32_t *queried_out, float *logits_out, void *ws, size_t ws_bytes);
 
 /*
+ * Reward bookkeeping of Algorithm 1 (paper Section 3.1 "Reward Function": accepted tokens divided by the
+ * elapsed time of the drafting/verification step; Section 3.3, multi-step action persistence: the reward is
+ * averaged over the N decoding steps of the cache interval; Algorithm 1: computed after verification, before
+ * the cache step is reset).  Call once per decoding step, after dt_policy_step and dt_accept of that step:
+ *     reward = (accept_len[b] + count_bonus) / seconds,  seconds = elapsed_per_seq[b] (device, may be NULL)
+ *              or else elapsed_seconds (host); count_bonus (0 or 1) says whether the bonus token counts as
+ *              an accepted token (the paper does not say: 1 makes the reward the step's emitted tokens / s)
+ *     reward_sum[b] += reward; reward_steps[b] += 1                    (device accumulators, start at 0)
+ *     if cache_step[b] == 0 (dt_policy_step has closed the interval with this step):
+ *         reward_avg[b] = reward_sum[b] / reward_steps[b], interval_done[b] = 1, accumulators back to 0
+ *     else interval_done[b] = 0 and reward_avg[b] is left alone.
+ * reward_steps is N for a full interval; a generation that begins inside one averages over what it saw.
+ * Float arithmetic.  Errors: null pointers, count_bonus not 0/1, no positive time -> DT_ERR_INVALID_ARG.
+ */
+int dt_reward_step(void *stream, int batch, const int32_t *accept_len, int count_bonus, float elapsed_seconds,
+                   const float *elapsed_per_seq, const int32_t *cache_step, float *reward_sum, int32_t *reward_steps,
+                   float *reward_avg, int32_t *interval_done);
+
+/*
  * Input update after verification (paper Appendix, "System Profiling and Overhead Analysis": the
  * input update brings the KV cache to the state of the next step -- accepted tokens kept, rejected
  * ones discarded, positions continued).  For every sequence b, layer l and both of K and V, the tree
@@ -324,7 +343,8 @@ int dt_commit(void *stream, int batch, int n_layers, dt_dtype t, int Hkv, int D,
  * kernel's own begin and end (not usable while the stream is being captured into a graph).
  * dt_profile_enable(0) switches it off.  dt_profile_read sums, for one kernel id
  * (0 draft row chunks, 1 row merge, 2 tree, 3 attention, 4 attention combine, 5 target row
- * chunks, 6 accept, 7 dt_topk_rows chunks, 8 commit, 9 policy layer 1, 10 policy head, 11 per-node target samples), the elapsed milliseconds of the launches recorded
+ * chunks, 6 accept, 7 dt_topk_rows chunks, 8 commit, 9 policy layer 1, 10 policy head, 11 per-node target samples,
+ * 12 reward), the elapsed milliseconds of the launches recorded
  * since the last enable, waiting for them to finish.  Not thread-safe.
  */
 int dt_profile_enable(int max_launches);

@@ -57,6 +57,8 @@ def load_library():
         lib.dt_policy_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
         lib.dt_policy_step.argtypes = [vp, i32, i32, vp, i64, i32, i32, i32] + [vp] * 7 + [i32, i32, u64, u64] + \
                                       [vp] * 6 + [vp, sz]
+        lib.dt_reward_step.argtypes = [vp, i32, vp, i32, f32, vp, vp, vp, vp, vp, vp]
+        lib.dt_reward_step.restype = i32
         lib.dt_commit.argtypes = [vp, i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, i64, i64, vp, vp, vp, vp, i32, vp, vp]
         lib.dt_profile_enable.argtypes = [i32]
         lib.dt_profile_enable.restype = i32
@@ -231,3 +233,10 @@ def dt_profile_read(kernel_id):
     lib = load_library()
     _check("dt_profile_read", lib.dt_profile_read(kernel_id, C.byref(ms), C.byref(n)))
     return lib.dt_profile_kernel_name(kernel_id).decode(), ms.value, n.value
+
+
+def dt_reward_step(accept_len, count_bonus, elapsed_seconds, cache_step, reward_sum, reward_steps, reward_avg,
+                   interval_done, elapsed_per_seq=None):
+    _check("dt_reward_step", load_library().dt_reward_step(
+        _stream(), accept_len.shape[0], _ptr(accept_len), int(count_bonus), float(elapsed_seconds), _ptr(elapsed_per_seq),
+        _ptr(cache_step), _ptr(reward_sum), _ptr(reward_steps), _ptr(reward_avg), _ptr(interval_done)))

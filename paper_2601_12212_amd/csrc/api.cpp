@@ -483,6 +483,24 @@ int dt_policy_step(void *stream, int batch, dt_dtype feat_t, const void *feature
     return DT_OK;
 }
 
+int dt_reward_step(void *stream, int batch, const int32_t *accept_len, int count_bonus, float elapsed_seconds,
+                   const float *elapsed_per_seq, const int32_t *cache_step, float *reward_sum, int32_t *reward_steps,
+                   float *reward_avg, int32_t *interval_done) {
+    if (batch < 0) return DT_ERR_INVALID_ARG;
+    if (batch == 0) return DT_OK;
+    if (!accept_len || !cache_step || !reward_sum || !reward_steps || !reward_avg || !interval_done ||
+        (count_bonus != 0 && count_bonus != 1) || (!elapsed_per_seq && !(elapsed_seconds > 0.0f)))
+        return DT_ERR_INVALID_ARG;
+    dt::RewardArgs a = {};
+    a.batch = batch; a.count_bonus = count_bonus; a.elapsed = elapsed_seconds; a.elapsed_dev = elapsed_per_seq;
+    a.accept_len = accept_len; a.cache_step = cache_step; a.reward_sum = reward_sum; a.reward_steps = reward_steps;
+    a.reward_avg = reward_avg; a.interval_done = interval_done;
+    (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
+    hipError_t e = dt::reward_launch(a, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+    return DT_OK;
+}
+
 int dt_commit(void *stream, int batch, int n_layers, dt_dtype t, int Hkv, int D, const void *const *k_tree,
               const void *const *v_tree, void *const *k_prefix, void *const *v_prefix, const int32_t *prefix_len,
               const int32_t *prefix_cap, int64_t kv_stride_tok, int64_t kv_stride_head, const int32_t *n_nodes,

@@ -13,7 +13,7 @@ namespace dt {
 // of pre-created HIP events attached to its dispatch (hipExtLaunchKernelGGL), which record the
 // kernel's own begin and end; dt_profile_read sums the elapsed times per kernel id.
 enum KernelId { KID_ROWS_DRAFT = 0, KID_ROWS_MERGE, KID_TREE, KID_ATTN, KID_ATTN_COMBINE, KID_ROWS_TARGET,
-                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COMMIT, KID_POLICY_L1, KID_POLICY_HEAD, KID_NODE_SAMPLE, KID_COUNT };
+                KID_ACCEPT, KID_ROWS_UNIFORM, KID_COMMIT, KID_POLICY_L1, KID_POLICY_HEAD, KID_NODE_SAMPLE, KID_REWARD, KID_COUNT };
 bool prof_next(int kid, hipEvent_t *start, hipEvent_t *stop);  // false when timing is off
 
 template <typename F, typename... Args>
@@ -161,5 +161,15 @@ struct PolicyArgs {
     int S;
 };
 hipError_t policy_launch(const PolicyArgs &a, hipStream_t st);
+
+struct RewardArgs {
+    int batch, count_bonus;
+    float elapsed;             // seconds of the step, used when elapsed_dev is null
+    const float *elapsed_dev;  // [batch] or null
+    const int32_t *accept_len, *cache_step;
+    float *reward_sum, *reward_avg;
+    int32_t *reward_steps, *interval_done;
+};
+hipError_t reward_launch(const RewardArgs &a, hipStream_t st);
 
 }  // namespace dt

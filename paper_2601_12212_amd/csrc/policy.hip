@@ -188,6 +188,33 @@ __global__ __launch_bounds__(256) void policy_head_kernel(PolicyArgs a) {
     }
 }
 
+// Reward of the step that has just been verified and, at the end of a cache interval, its average over
+// the interval.  One thread per sequence; float arithmetic (an interval has at most a few dozen terms).
+__global__ __launch_bounds__(256) void reward_kernel(RewardArgs a) {
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= a.batch) return;
+    const float secs = a.elapsed_dev ? a.elapsed_dev[b] : a.elapsed;
+    const float tokens = (float)(max(a.accept_len[b], 0) + a.count_bonus);
+    const float sum = a.reward_sum[b] + tokens / secs;
+    const int steps = a.reward_steps[b] + 1;
+    if (a.cache_step[b] == 0) {  // the action cache has closed its interval with this step
+        a.reward_avg[b] = sum / (float)steps;
+        a.interval_done[b] = 1;
+        a.reward_sum[b] = 0.f;
+        a.reward_steps[b] = 0;
+    } else {
+        a.interval_done[b] = 0;
+        a.reward_sum[b] = sum;
+        a.reward_steps[b] = steps;
+    }
+}
+
+hipError_t reward_launch(const RewardArgs &a, hipStream_t st) {
+    if (a.batch <= 0) return hipSuccess;
+    launch_kernel(KID_REWARD, st, reward_kernel, dim3((a.batch + 255) / 256), dim3(256), 0, a);
+    return hipGetLastError();
+}
+
 hipError_t policy_launch(const PolicyArgs &a, hipStream_t st) {
     if (a.batch <= 0) return hipSuccess;
     launch_kernel(KID_POLICY_L1, st, policy_layer1_kernel, dim3(a.S), dim3(2 * a.H), 0, a);

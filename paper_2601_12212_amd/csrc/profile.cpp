@@ -59,7 +59,8 @@ int dt_profile_read(int kernel_id, double *total_ms, int *launches) {
 
 const char *dt_profile_kernel_name(int kernel_id) {
     static const char *names[] = {"rows_draft_chunk", "rows_merge", "tree", "attention", "attention_combine",
-                                  "rows_target_chunk", "accept", "rows_uniform_chunk", "commit", "policy_layer1", "policy_head", "node_sample"};
+                                  "rows_target_chunk", "accept", "rows_uniform_chunk", "commit", "policy_layer1", "policy_head", "node_sample",
+                                  "reward"};
     return (kernel_id >= 0 && kernel_id < dt::KID_COUNT) ? names[kernel_id] : "?";
 }
 }

@@ -126,6 +126,13 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_commit(*com(TT_cap=129)) == -2
     assert lib.dt_commit(*com(batch=0)) == 0
     assert lib.dt_commit(*com(layers=0)) == 0
+    # reward bookkeeping: null accumulators, a bonus count that is not 0/1, no positive time
+    rew = lambda **kw: [None, kw.get("batch", 2), one, kw.get("bonus", 1), kw.get("secs", 0.01), kw.get("per_seq"), one,
+                        kw.get("acc", one), one, one, one]
+    assert lib.dt_reward_step(*rew(acc=None)) == -1
+    assert lib.dt_reward_step(*rew(bonus=2)) == -1
+    assert lib.dt_reward_step(*rew(secs=0.0)) == -1
+    assert lib.dt_reward_step(*rew(batch=0)) == 0
 
 
 def test_launch_grid_limits_are_checked_on_the_host():

@@ -96,3 +96,49 @@ def test_policy_sampling_small_net_and_odd_feature_size():
 
 def test_policy_every_step_and_one_sequence():
     run_policy(B=1, F=3 * 5120, H=128, bf16=True, N=1, sample=0, steps=5, seed=3)
+
+
+@pytest.mark.parametrize("N,bonus,per_seq", [(4, 1, False), (10, 0, True), (1, 1, False)])
+def test_reward_averaged_over_the_cache_interval(N, bonus, per_seq):
+    """dt_policy_step and dt_reward_step driven together over several intervals: the device accumulators,
+    the interval-closed flags and the averaged reward against the oracle's (float against double)."""
+    import paper_2601_12212_amd as dt
+    B, F, H, steps = 5, 256, 64, 3 * N + 2
+    rng = np.random.default_rng(100 + N)
+    table = np.array(dt.dt_action_table(), np.int32)
+    A = len(table)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    Wts = [dev((rng.standard_normal(sh) * sc).astype(np.float32)) for sh, sc in
+           (((F, H), F ** -0.5), ((H,), 0.1), ((H, H), H ** -0.5), ((H,), 0.1), ((H, A), 1.0), ((A,), 0.1))]
+    i32 = dict(dtype=torch.int32, device="cuda")
+    cache_step, cached = torch.zeros(B, **i32), torch.full((B,), -1, **i32)
+    cache_step[1], cached[1] = (2 % N), (5 if N > 2 else -1)          # one sequence starts inside an interval
+    params_out = torch.zeros((B, 3), **i32)
+    ws = torch.empty(dt.dt_policy_workspace_bytes(B, F, H), dtype=torch.uint8, device="cuda")
+    r_sum = torch.zeros(B, dtype=torch.float32, device="cuda")
+    r_steps = torch.zeros(B, **i32)
+    r_avg = torch.full((B,), -1.0, dtype=torch.float32, device="cuda")
+    r_done = torch.full((B,), -1, **i32)
+    acc = [dict(sum=0.0, steps=0) for _ in range(B)]
+    closed = 0
+    for t in range(steps):
+        feat = dev(rng.standard_normal((B, F)).astype(np.float32))
+        dt.dt_policy_step(feat, *Wts, dev(table), N, 0, 7, t, cache_step, cached, params_out, None, None, None, ws)
+        accept_len = rng.integers(0, 9, B).astype(np.int32)
+        secs = rng.uniform(0.003, 0.02, B).astype(np.float32)
+        if per_seq:
+            dt.dt_reward_step(dev(accept_len), bonus, 0.0, cache_step, r_sum, r_steps, r_avg, r_done, elapsed_per_seq=dev(secs))
+        else:
+            secs[:] = secs[0]
+            dt.dt_reward_step(dev(accept_len), bonus, float(secs[0]), cache_step, r_sum, r_steps, r_avg, r_done)
+        torch.cuda.synchronize()
+        cs = cache_step.cpu().numpy()
+        for b in range(B):
+            done, avg = ref.reward_step(int(cs[b]), float(accept_len[b] + bonus), float(secs[b]), acc[b])
+            assert int(r_done[b]) == int(done), (t, b)
+            assert int(r_steps[b]) == acc[b]["steps"]
+            assert abs(float(r_sum[b]) - acc[b]["sum"]) <= 2e-6 * max(1.0, acc[b]["sum"])
+            if done:
+                assert abs(float(r_avg[b]) - avg) <= 2e-6 * avg, (t, b, float(r_avg[b]), avg)
+                closed += 1
+    assert closed >= 2 * B
