@@ -2,12 +2,16 @@
 
     python -m paper_2601_12212_amd.profile_summary kernels RESULTS.db [--cmd "..."]
     python -m paper_2601_12212_amd.profile_summary pmc FETCH.db WRITE.db --copy-bytes N [--json OUT] [--cmd "..."]
+    python -m paper_2601_12212_amd.profile_summary counters RESULTS.db [--cmd "..."]
 
 `kernels`: per-kernel launch count and average / min / max duration from a
 `rocprofv3 --kernel-trace --stats` run.
 `pmc`: per-kernel HBM traffic from two `rocprofv3 --pmc` runs (FETCH_SIZE, then WRITE_SIZE, both
 in KiB per dispatch).  The counters are scaled by what they read for a plain device copy of
 known size in the same run (bench.py --calibration-copy-mb): factor = copy bytes / counter.
+`counters`: every counter of one `rocprofv3 --pmc` run per kernel (average per dispatch), and -- when the
+counters are there -- the share of the matrix pipe's busy cycles in the busy cycles of the shader engines
+and the share of LDS bank-conflict cycles in the LDS's active cycles.
 """
 import argparse
 import json
@@ -81,6 +85,36 @@ def pmc(db_fetch, db_write, copy_bytes, out_json, cmd):
             fh.write("\n")
 
 
+def counters(db, cmd):
+    c = sqlite3.connect(db)
+    rows = c.execute("select kernel_name, counter_name, count(*), avg(value) from counters_collection "
+                     "group by kernel_name, counter_name").fetchall()
+    names = sorted({r[1] for r in rows})
+    per = {}
+    for k, n, cnt, avg in rows:
+        if OURS in k:
+            per.setdefault(short(k), {})[n] = (cnt, avg)
+    if cmd:
+        print("# command: %s" % cmd)
+    print("# rocprofv3 --pmc %s; averages per dispatch (summed over the chip's shader engines / units)" % " ".join(names))
+    print("%-44s %7s %s" % ("kernel", "calls", " ".join("%26s" % n for n in names)))
+    for k in sorted(per):
+        calls = max(v[0] for v in per[k].values())
+        print("%-44s %7d %s" % (k[:44], calls, " ".join("%26.1f" % per[k].get(n, (0, 0.0))[1] for n in names)))
+    for k in sorted(per):
+        g = lambda n: per[k].get(n, (0, 0.0))[1]
+        notes = []
+        if g("SQ_VALU_MFMA_BUSY_CYCLES") and g("SQ_BUSY_CYCLES"):
+            notes.append("matrix pipe busy / shader busy cycles = %.3f" % (g("SQ_VALU_MFMA_BUSY_CYCLES") / g("SQ_BUSY_CYCLES")))
+        if g("SQ_VALU_MFMA_BUSY_CYCLES") and g("SQ_VALU_MFMA_COEXEC_CYCLES"):
+            notes.append("co-executing with vector work %.3f of the matrix pipe's busy cycles"
+                         % (g("SQ_VALU_MFMA_COEXEC_CYCLES") / g("SQ_VALU_MFMA_BUSY_CYCLES")))
+        if g("SQ_LDS_IDX_ACTIVE"):
+            notes.append("LDS bank conflicts / LDS active cycles = %.3f" % (g("SQ_LDS_BANK_CONFLICT") / g("SQ_LDS_IDX_ACTIVE")))
+        if notes:
+            print("# %s: %s" % (k, "; ".join(notes)))
+
+
 def main():
     ap = argparse.ArgumentParser()
     sub = ap.add_subparsers(dest="what", required=True)
@@ -93,9 +127,14 @@ def main():
     p.add_argument("--copy-bytes", type=int, required=True)
     p.add_argument("--json", default="")
     p.add_argument("--cmd", default="")
+    q = sub.add_parser("counters")
+    q.add_argument("db")
+    q.add_argument("--cmd", default="")
     a = ap.parse_args()
     if a.what == "kernels":
         kernels(a.db, a.cmd)
+    elif a.what == "counters":
+        counters(a.db, a.cmd)
     else:
         pmc(a.fetch_db, a.write_db, a.copy_bytes, a.json, a.cmd)
 
