@@ -10,8 +10,8 @@
 in KiB per dispatch).  The counters are scaled by what they read for a plain device copy of
 known size in the same run (bench.py --calibration-copy-mb): factor = copy bytes / counter.
 `counters`: every counter of one `rocprofv3 --pmc` run per kernel (average per dispatch), and -- when the
-counters are there -- the share of the matrix pipe's busy cycles in the busy cycles of the shader engines
-and the share of LDS bank-conflict cycles in the LDS's active cycles.
+counters are there -- the matrix pipe's busy cycles per SIMD as a share of the cycles its compute unit is busy,
+the share of them that overlap vector work, and the share of LDS bank-conflict cycles in the LDS's active cycles.
 """
 import argparse
 import json
@@ -104,8 +104,10 @@ def counters(db, cmd):
     for k in sorted(per):
         g = lambda n: per[k].get(n, (0, 0.0))[1]
         notes = []
-        if g("SQ_VALU_MFMA_BUSY_CYCLES") and g("SQ_BUSY_CYCLES"):
-            notes.append("matrix pipe busy / shader busy cycles = %.3f" % (g("SQ_VALU_MFMA_BUSY_CYCLES") / g("SQ_BUSY_CYCLES")))
+        if g("SQ_VALU_MFMA_BUSY_CYCLES") and g("SQ_BUSY_CU_CYCLES"):
+            # the first is summed over SIMDs, the second over compute units (four SIMDs each)
+            notes.append("matrix pipe busy %.3f of the cycles its compute unit is busy"
+                         % (g("SQ_VALU_MFMA_BUSY_CYCLES") / (4.0 * g("SQ_BUSY_CU_CYCLES"))))
         if g("SQ_VALU_MFMA_BUSY_CYCLES") and g("SQ_VALU_MFMA_COEXEC_CYCLES"):
             notes.append("co-executing with vector work %.3f of the matrix pipe's busy cycles"
                          % (g("SQ_VALU_MFMA_COEXEC_CYCLES") / g("SQ_VALU_MFMA_BUSY_CYCLES")))
