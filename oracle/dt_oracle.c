@@ -234,13 +234,18 @@ static int select_best(const cand_t *pool, int lo, int hi, int keep, unsigned ch
  *   exp_parent_slot  slot of the parent in level l-1's expanded set (-1: the root)
  *   exp_mask[..][4]  draft-side tree mask over draft rows: bit r set iff draft row r belongs to
  *                    the node itself or to one of its ancestors (row 0 = the root)
+ * early_stop != 0: the token-count exit of Algorithm 2's expansion loop.  token_count starts at 1
+ *   (the root) and grows by the candidates each expansion proposes (the root's k, then up to k per
+ *   expanded node); no further level is expanded once token_count >= TT.  Levels never expanded
+ *   report exp_count = 0 and their rows are not read.  With early_stop == 0, TT binds only at the
+ *   rerank (Section 3.2, "all tokens in the tree are reranked").
  */
 int ref_build_tree(const void *rows, int dtype, int V, int64_t row_stride, int n_rows_avail,
                    int TT, int d, int k, int32_t root_token, int TT_cap,
                    int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth,
                    float *score, float *logp, int32_t *src_row, uint64_t *anc_mask,
                    float *min_margin, int32_t *exp_count, int32_t *exp_tok, int32_t *exp_parent_slot,
-                   uint64_t *exp_mask)
+                   uint64_t *exp_mask, int early_stop)
 {
     if (!rows || !n_nodes || !tokens || !parents || !depth || !score || !logp || !src_row || !anc_mask)
         return REF_ERR_ARG;
@@ -284,7 +289,10 @@ int ref_build_tree(const void *rows, int dtype, int V, int64_t row_stride, int n
             c->parent_pool = -1; c->level = 1; c->from_row = 0;
         }
         int lo = 0, hi = k; /* pool range of the current level */
+        int token_count = 1 + nv; /* the root and the candidates proposed so far (Algorithm 2) */
         for (int l = 1; l < d; ++l) {
+            /* Algorithm 2 leaves the expansion loop once the tree holds TT tokens; applied on request only */
+            if (early_stop && token_count >= TT) break;
             /* choose the nodes of level l to expand: its k best by score */
             unsigned char *exp_flag = (unsigned char *)calloc((size_t)P, 1);
             if (!exp_flag) { rc = REF_ERR_INTERNAL; goto done; }
@@ -316,6 +324,7 @@ int ref_build_tree(const void *rows, int dtype, int V, int64_t row_stride, int n
                     c->score = pool[i].score + c->lp;
                     c->parent_pool = i; c->level = l + 1; c->from_row = row;
                 }
+                token_count += nvr;
                 ++slot;
             }
             free(exp_flag);

@@ -73,11 +73,13 @@ def topk_rows(logits, k):
     return val, idx, lse
 
 
-def build_tree(rows, TT, d, k, root_token=0, TT_cap=TT_MAX, with_levels=False):
+def build_tree(rows, TT, d, k, root_token=0, TT_cap=TT_MAX, with_levels=False, early_stop=False):
     """A1-A4 for one sequence.  rows [>= 1+(d-1)k, V].  Returns a dict of node arrays.
 
     with_levels: also "levels", a list indexed by level l = 1..d-1 of dicts (tokens, parent_slot, rows, mask)
-    describing the nodes expanded at that level -- what a draft model between the levels is handed."""
+    describing the nodes expanded at that level -- what a draft model between the levels is handed.
+    early_stop: leave the expansion loop once the root plus the candidates proposed so far number TT or more
+    (the token-count exit of Algorithm 2's expansion loop)."""
     rows = np.ascontiguousarray(rows)
     R, V = rows.shape
     W = (TT_cap + 63) // 64
@@ -96,7 +98,8 @@ def build_tree(rows, TT, d, k, root_token=0, TT_cap=TT_MAX, with_levels=False):
     emask = np.zeros((D_MAX, K_MAX, 4), np.uint64) if with_levels else None
     _check(lib().ref_build_tree(_p(rows), _dt(rows), V, C.c_int64(V), R, TT, d, k, root_token, TT_cap,
                                 C.byref(n), _p(tokens), _p(parents), _p(depth), _p(score), _p(logp),
-                                _p(src_row), _p(mask), C.byref(margin), _p(ecnt), _p(etok), _p(epar), _p(emask)),
+                                _p(src_row), _p(mask), C.byref(margin), _p(ecnt), _p(etok), _p(epar), _p(emask),
+                                1 if early_stop else 0),
            "ref_build_tree")
     N = n.value
     out = dict(n_nodes=N, tokens=tokens[:N], parents=parents[:N], depth=depth[:N], score=score[:N],

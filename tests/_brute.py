@@ -15,9 +15,10 @@ def toy_logits(seed, string, V, sigma=2.0):
     return (np.random.Generator(np.random.PCG64(h)).standard_normal(V) * sigma).astype(np.float32)
 
 
-def brute_tree(draft_fn, V, TT, d, k):
+def brute_tree(draft_fn, V, TT, d, k, early_stop=False):
     """Returns (set of kept strings, cumulative score of every candidate string, own log-probability
-    of every candidate string = its logit minus the log-sum-exp of the row that proposed it)."""
+    of every candidate string = its logit minus the log-sum-exp of the row that proposed it).
+    early_stop: no level is expanded once the root and all strings proposed so far number TT or more."""
     def topk(string):
         x = draft_fn(string).astype(np.float64)
         lse = logsumexp(x)
@@ -38,6 +39,8 @@ def brute_tree(draft_fn, V, TT, d, k):
         levels.append(cands)
         if not cands:
             break
+        if early_stop and 1 + sum(len(lv) for lv in levels) >= TT:
+            break
         ranked = sorted(cands, key=lambda c: -score[c])
         frontier = ranked[:k]
     everyone = [c for lv in levels for c in lv]
@@ -46,10 +49,12 @@ def brute_tree(draft_fn, V, TT, d, k):
     return kept, score, own
 
 
-def brute_frontiers(draft_fn, V, d, k):
+def brute_frontiers(draft_fn, V, d, k, stop_at=None):
     """The strings expanded at levels 1..d-1, each level as an ORDERED list: a level's chosen strings are
     listed parent by parent (in the order the parents were listed one level up) and, under one parent, in
-    the order of that parent's top-k list.  Returns [None, level 1, ..., level d-1]."""
+    the order of that parent's top-k list.  Returns [None, level 1, ..., level d-1].
+    stop_at: a token budget; a level is expanded only while the root and the strings proposed so far number
+    fewer than it."""
     def topk(string):
         x = draft_fn(string).astype(np.float64)
         lse = logsumexp(x)
@@ -65,6 +70,8 @@ def brute_frontiers(draft_fn, V, d, k):
             for t, lp in topk(s):
                 score[s + (t,)] = score[s] + lp
                 cands.append(s + (t,))
+        if stop_at is not None and len(score) >= stop_at:      # score holds the root and every proposed string
+            break
         chosen = set(sorted(cands, key=lambda c: -score[c])[:k])
         frontier = [c for c in cands if c in chosen]
         out.append(frontier)

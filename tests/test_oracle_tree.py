@@ -274,3 +274,62 @@ def test_min_margin_of_a_constructed_gap():
     want = min(kept["a2"] - gone["b3"], kept["b2"] - gone["a3"], -l0 - gone["a3"], -l0 - gone["b3"])
     assert abs(t["min_margin"] - want) < 1e-6
     assert abs(want - (kept["b2"] - gone["b3"])) > 1e-3     # the same-row pair (b2, b3) would have been smaller: it is not counted
+
+
+# ---- the token-count exit of the expansion loop (Algorithm 2), applied on request -----------------------
+
+def levels_expanded(TT, d, k):
+    """Closed form with every candidate viable: the root proposes k, every later expansion k*k; level l is
+    expanded iff 1 + k + (l-1) k^2 < TT."""
+    n = 0
+    for l in range(1, d):
+        if 1 + k + (l - 1) * k * k >= TT:
+            break
+        n += 1
+    return n
+
+
+@pytest.mark.parametrize("V,TT,d,k", [(8, 4, 4, 2), (8, 6, 4, 2), (8, 8, 4, 2), (8, 12, 4, 2), (6, 5, 3, 3), (6, 14, 3, 3),
+                                      (7, 3, 3, 2), (8, 2, 3, 2), (5, 1, 3, 2), (8, 40, 3, 3)])
+def test_early_stop_matches_brute_force_and_the_closed_form_level_count(V, TT, d, k):
+    for seed in range(4):
+        fn = lambda s: toy_logits(500 + seed, s, V)
+        rows = rows_from_fn(ref.build_tree, fn, V, d, k)
+        t = ref.build_tree(rows, TT, d, k, 3, with_levels=True, early_stop=True)
+        kept, score, _ = brute_tree(fn, V, TT, d, k, early_stop=True)
+        strs = node_strings(t)
+        assert set(strs[1:]) == kept and len(strs) == len(set(strs))
+        for i in range(1, t["n_nodes"]):
+            assert abs(t["score"][i] - score[strs[i]]) < 1e-5
+        check_invariants(t, TT, d, k)
+        n_lv = levels_expanded(TT, d, k) if TT > 1 else 0
+        assert [len(t["levels"][l]["tokens"]) > 0 for l in range(1, d)] == [l <= n_lv for l in range(1, d)]
+        assert t["n_nodes"] == 1 or t["depth"].max() <= n_lv + 1
+        want = brute_frontiers(fn, V, d, k, stop_at=TT)
+        for l in range(1, d):
+            assert len(t["levels"][l]["tokens"]) == len(want[l])
+        # the rows of levels that are never expanded are not read: poison them
+        bad = rows.copy()
+        bad[1 + n_lv * k:] = np.nan
+        t2 = ref.build_tree(bad, TT, d, k, 3, early_stop=True)
+        assert t2["n_nodes"] == t["n_nodes"] and (t2["tokens"] == t["tokens"]).all() and (t2["score"] == t["score"]).all()
+
+
+def test_early_stop_changes_nothing_when_the_budget_outlasts_the_levels_and_cuts_deep_chains_otherwise():
+    V, d, k = 8, 4, 2
+    # a draft that always continues its own string with near certainty: the best tree is one deep chain
+    def chain(s):
+        x = np.full(V, -9.0, np.float32)
+        x[(len(s) * 3 + 1) % V] = 9.0
+        x[(len(s) * 3 + 2) % V] = 0.0
+        return x
+    rows = rows_from_fn(ref.build_tree, chain, V, d, k)
+    late = 1 + k + (d - 2) * k * k + 1                      # first budget the count never reaches before the last level
+    a = ref.build_tree(rows, late, d, k)
+    b = ref.build_tree(rows, late, d, k, early_stop=True)
+    assert a["n_nodes"] == b["n_nodes"] and (a["tokens"] == b["tokens"]).all() and (a["parents"] == b["parents"]).all()
+    # TT = 4: without the exit the rerank keeps the chain down to depth 3; with it 1 + 2 + 4 >= 4 stops after level 1
+    a = ref.build_tree(rows, 4, d, k)
+    b = ref.build_tree(rows, 4, d, k, early_stop=True)
+    assert a["depth"].max() == 3 and b["depth"].max() == 2
+    assert b["n_nodes"] == 4 and set(node_strings(b)) <= {(), (1,), (2,), (1, 4), (1, 5), (2, 4), (2, 5)}
