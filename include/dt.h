@@ -152,13 +152,22 @@ int dt_topk_rows_static(void *stream, const void *logits, dt_dtype t, int64_t n_
  *   src_row [batch, TT_cap]   local draft row the node was handed (root 0), -1 if not expanded
  *   anc_mask[batch, TT_cap, DT_MASK_WORDS] bit j of node i set iff j == i or j is an ancestor of i
  * Entries at index >= n_nodes[b] are left untouched.
- * Errors: TT_cap < 1 or > DT_TT_MAX, V < 1 -> DT_ERR_LIMIT; ws too small -> DT_ERR_WORKSPACE.
+ *
+ * flags: 0, or DT_TREE_EARLY_STOP for the token-count exit of Algorithm 2's expansion loop: the count
+ * starts at 1 (the root) and grows by the viable candidates every expansion proposes (the root's k, then
+ * up to k per expanded node); no further level is expanded once it has reached TT.  The rows of levels
+ * that are then never expanded are still streamed (their number is not known before the launch) but no
+ * result depends on them.  Without the flag TT binds at the rerank only (Section 3.2: all tokens of the
+ * tree are reranked).
+ * Errors: TT_cap < 1 or > DT_TT_MAX, V < 1 -> DT_ERR_LIMIT; unknown flag bits -> DT_ERR_INVALID_ARG;
+ * ws too small -> DT_ERR_WORKSPACE.
  */
+#define DT_TREE_EARLY_STOP 1
 int dt_build_tree(void *stream, int batch, const dt_params *params, const void *draft_logits, dt_dtype t,
                   int V, int64_t row_stride, const int64_t *row_off, int64_t total_rows,
                   const int32_t *root_token, int TT_cap, int32_t *n_nodes, int32_t *tokens,
                   int32_t *parents, int32_t *depth, float *score, float *logp, int32_t *src_row,
-                  uint64_t *anc_mask, void *ws, size_t ws_bytes);
+                  uint64_t *anc_mask, void *ws, size_t ws_bytes, int flags);
 
 /*
  * Tree-masked attention of the tree tokens for ONE layer (paper Section 3.2 "Verification
@@ -237,7 +246,8 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
  * belong to the buffer, which holds batch*R rows: a small launch may read them).
  * The call scores the candidates of level l and reports the nodes of level l that are expanded
  * next, in slot order (= ascending pool index):
- *   n_expand        [batch]            how many (0 when l >= d, TT == 1, or nothing is viable)
+ *   n_expand        [batch]            how many (0 when l >= d, TT == 1, nothing is viable, or -- with
+ *                                      DT_TREE_EARLY_STOP -- the token count has reached TT)
  *   exp_token       [batch, DT_K_MAX]  their tokens
  *   exp_parent_slot [batch, DT_K_MAX]  slot of the parent in the previous call's list (-1: the root)
  *   exp_row         [batch, DT_K_MAX]  the draft row each is handed, 1 + (l-1)k + slot
@@ -246,6 +256,8 @@ int dt_accept(void *stream, int batch, dt_accept_mode mode, float temperature, c
  *                                      the node or one of its ancestors; row 0 = root)
  * Workspace: dt_workspace_bytes(batch, batch*R, V, TT_cap, 1, 1) bytes.
  * dt_finish_tree reranks and emits exactly what dt_build_tree would from the same rows.
+ * flags as for dt_build_tree, the same value in every call of a step: with DT_TREE_EARLY_STOP the draft
+ * model's loop ends at the first level whose n_expand is 0 everywhere, which is what the flag is for.
  * Errors as dt_build_tree; level outside 1..DT_D_MAX, rows_per_seq outside 1..DT_K_MAX or a
  * misaligned state -> DT_ERR_INVALID_ARG.
  */
@@ -253,10 +265,10 @@ int dt_level_state_bytes(int batch, size_t *bytes);
 int dt_expand_level(void *stream, int batch, int level, const dt_params *params, const void *level_logits, dt_dtype t,
                     int V, int64_t row_stride, int rows_per_seq, const int32_t *prefix_len, int TT_cap, void *state,
                     int32_t *n_expand, int32_t *exp_token, int32_t *exp_parent_slot, int32_t *exp_row, int32_t *exp_pos,
-                    uint64_t *exp_mask, void *ws, size_t ws_bytes);
+                    uint64_t *exp_mask, void *ws, size_t ws_bytes, int flags);
 int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, const int32_t *root_token, int TT_cap,
                    const void *state, int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth, float *score,
-                   float *logp, int32_t *src_row, uint64_t *anc_mask);
+                   float *logp, int32_t *src_row, uint64_t *anc_mask, int flags);
 
 /*
  * Action selection on the device (paper Section 3.3 and Algorithm 1 "Re-SpS with Action Caching";

@@ -7,6 +7,7 @@ _LIB_PATH = os.path.join(_HERE, "libdt.so")
 
 DT_TT_MAX, DT_D_MAX, DT_K_MAX, DT_MASK_WORDS = 128, 8, 32, 2
 DT_F32, DT_BF16 = 0, 1
+DT_TREE_EARLY_STOP = 1
 DT_ACCEPT_GREEDY, DT_ACCEPT_STOCHASTIC, DT_ACCEPT_SAMPLED = 0, 1, 2
 
 _lib = None
@@ -45,14 +46,14 @@ def load_library():
         lib.dt_topk_rows.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, vp, vp, vp, sz]
         lib.dt_topk_rows_static.argtypes = [vp, vp, i32, i64, i32, i64, i32, vp, vp, vp]
         lib.dt_topk_rows_static.restype = i32
-        lib.dt_build_tree.argtypes = [vp, i32, vp, vp, i32, i32, i64, vp, i64, vp, i32] + [vp] * 8 + [vp, sz]
+        lib.dt_build_tree.argtypes = [vp, i32, vp, vp, i32, i32, i64, vp, i64, vp, i32] + [vp] * 8 + [vp, sz, i32]
         lib.dt_tree_attention.argtypes = [vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, i32, i64, i64,
                                           vp, i32, vp, vp, sz]
         lib.dt_accept.argtypes = [vp, i32, i32, f32, vp, i32, i32, i64, vp, vp, vp, vp, vp, vp, i32, u64, u64,
                                   vp, vp, vp, vp, vp, vp, sz]
         lib.dt_level_state_bytes.argtypes = [i32, C.POINTER(sz)]
-        lib.dt_expand_level.argtypes = [vp, i32, i32, vp, vp, i32, i32, i64, i32, vp, i32, vp] + [vp] * 6 + [vp, sz]
-        lib.dt_finish_tree.argtypes = [vp, i32, vp, i32, vp, i32, vp] + [vp] * 8
+        lib.dt_expand_level.argtypes = [vp, i32, i32, vp, vp, i32, i32, i64, i32, vp, i32, vp] + [vp] * 6 + [vp, sz, i32]
+        lib.dt_finish_tree.argtypes = [vp, i32, vp, i32, vp, i32, vp] + [vp] * 8 + [i32]
         lib.dt_action_table.argtypes = [vp, i32, C.POINTER(i32)]
         lib.dt_policy_workspace_bytes.argtypes = [i32, i32, i32, C.POINTER(sz)]
         lib.dt_policy_step.argtypes = [vp, i32, i32, vp, i64, i32, i32, i32] + [vp] * 7 + [i32, i32, u64, u64] + \
@@ -129,14 +130,14 @@ def dt_topk_rows_static(logits, k, top_val, top_id, lse):
 
 
 def dt_build_tree(params, draft_logits, row_off, total_rows, root_token, TT_cap, n_nodes, tokens, parents, depth,
-                  score, logp, src_row, anc_mask, ws):
+                  score, logp, src_row, anc_mask, ws, flags=0):
     batch = params.shape[0]
     V = draft_logits.shape[1]
     _check("dt_build_tree", load_library().dt_build_tree(
         _stream(), batch, _ptr(params), _ptr(draft_logits), _dtype(draft_logits), V, draft_logits.stride(0),
         _ptr(row_off), total_rows, _ptr(root_token), TT_cap, _ptr(n_nodes), _ptr(tokens), _ptr(parents),
         _ptr(depth), _ptr(score), _ptr(logp), _ptr(src_row), _ptr(anc_mask), _ptr(ws),
-        ws.numel() * ws.element_size()))
+        ws.numel() * ws.element_size(), flags))
 
 
 def dt_tree_attention(q, k_tree, v_tree, n_nodes, k_prefix_ptrs, v_prefix_ptrs, prefix_len, max_prefix_len,
@@ -166,22 +167,22 @@ def dt_level_state_bytes(batch):
 
 
 def dt_expand_level(level, params, level_logits, rows_per_seq, prefix_len, TT_cap, state, n_expand, exp_token,
-                    exp_parent_slot, exp_row, exp_pos, exp_mask, ws):
+                    exp_parent_slot, exp_row, exp_pos, exp_mask, ws, flags=0):
     """level_logits: [batch * R, V] with R = 1 at level 1, rows_per_seq otherwise."""
     batch = params.shape[0]
     V = level_logits.shape[1]
     _check("dt_expand_level", load_library().dt_expand_level(
         _stream(), batch, level, _ptr(params), _ptr(level_logits), _dtype(level_logits), V, level_logits.stride(0),
         rows_per_seq, _ptr(prefix_len), TT_cap, _ptr(state), _ptr(n_expand), _ptr(exp_token), _ptr(exp_parent_slot),
-        _ptr(exp_row), _ptr(exp_pos), _ptr(exp_mask), _ptr(ws), ws.numel() * ws.element_size()))
+        _ptr(exp_row), _ptr(exp_pos), _ptr(exp_mask), _ptr(ws), ws.numel() * ws.element_size(), flags))
 
 
 def dt_finish_tree(params, V, root_token, TT_cap, state, n_nodes, tokens, parents, depth, score, logp, src_row,
-                   anc_mask):
+                   anc_mask, flags=0):
     batch = params.shape[0]
     _check("dt_finish_tree", load_library().dt_finish_tree(
         _stream(), batch, _ptr(params), V, _ptr(root_token), TT_cap, _ptr(state), _ptr(n_nodes), _ptr(tokens),
-        _ptr(parents), _ptr(depth), _ptr(score), _ptr(logp), _ptr(src_row), _ptr(anc_mask)))
+        _ptr(parents), _ptr(depth), _ptr(score), _ptr(logp), _ptr(src_row), _ptr(anc_mask), flags))
 
 
 def dt_action_table():

@@ -235,8 +235,8 @@ int dt_topk_rows_static(void *stream, const void *logits, dt_dtype t, int64_t n_
 int dt_build_tree(void *stream, int batch, const dt_params *params, const void *draft_logits, dt_dtype t, int V,
                   int64_t row_stride, const int64_t *row_off, int64_t total_rows, const int32_t *root_token,
                   int TT_cap, int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth, float *score,
-                  float *logp, int32_t *src_row, uint64_t *anc_mask, void *ws, size_t ws_bytes) {
-    if (batch < 0 || total_rows < 0 || bad_dtype(t)) return DT_ERR_INVALID_ARG;
+                  float *logp, int32_t *src_row, uint64_t *anc_mask, void *ws, size_t ws_bytes, int flags) {
+    if (batch < 0 || total_rows < 0 || bad_dtype(t) || (flags & ~DT_TREE_EARLY_STOP)) return DT_ERR_INVALID_ARG;
     if (batch == 0) return DT_OK;
     if (!params || !draft_logits || !row_off || !root_token || !n_nodes || !tokens || !parents || !depth ||
         !score || !logp || !src_row || !anc_mask || row_stride < V)
@@ -272,6 +272,7 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
     dt::TreeArgs ta = {};
     ta.batch = batch; ta.params = params; ta.V = V; ta.seq_rows = DT_STATE_ROWS; ta.root_token = root_token;
     ta.TT_cap = TT_cap; ta.top_val = top_val; ta.top_id = top_id; ta.lse = lse; ta.row_off = row_off;
+    ta.early_stop = flags & DT_TREE_EARLY_STOP;
     ta.n_nodes = n_nodes; ta.tokens = tokens; ta.parents = parents; ta.depth = depth; ta.src_row = src_row;
     ta.score = score; ta.logp = logp; ta.anc_mask = (unsigned long long *)anc_mask;
     e = dt::tree_launch(ta, st);
@@ -366,8 +367,8 @@ int dt_level_state_bytes(int batch, size_t *bytes) {
 int dt_expand_level(void *stream, int batch, int level, const dt_params *params, const void *level_logits, dt_dtype t,
                     int V, int64_t row_stride, int rows_per_seq, const int32_t *prefix_len, int TT_cap, void *state,
                     int32_t *n_expand, int32_t *exp_token, int32_t *exp_parent_slot, int32_t *exp_row, int32_t *exp_pos,
-                    uint64_t *exp_mask, void *ws, size_t ws_bytes) {
-    if (batch < 0 || bad_dtype(t) || level < 1 || level > DT_D_MAX) return DT_ERR_INVALID_ARG;
+                    uint64_t *exp_mask, void *ws, size_t ws_bytes, int flags) {
+    if (batch < 0 || bad_dtype(t) || level < 1 || level > DT_D_MAX || (flags & ~DT_TREE_EARLY_STOP)) return DT_ERR_INVALID_ARG;
     if (batch == 0) return DT_OK;
     if (!params || !level_logits || !state || !n_expand || !exp_token || !exp_parent_slot || !exp_row || !exp_pos ||
         !exp_mask || row_stride < V || (uintptr_t)state % 256)
@@ -403,6 +404,7 @@ int dt_expand_level(void *stream, int batch, int level, const dt_params *params,
     ta.expand_level = level; ta.prefix_len = prefix_len; ta.n_expand = n_expand; ta.state_n_exp = ls.n_exp;
     ta.exp_token = exp_token; ta.exp_parent_slot = exp_parent_slot; ta.exp_row = exp_row; ta.exp_pos = exp_pos;
     ta.exp_mask = (unsigned long long *)exp_mask;
+    ta.early_stop = flags & DT_TREE_EARLY_STOP;
     e = dt::tree_launch(ta, st);
     if (e != hipSuccess) return hip_fail(e);
     return DT_OK;
@@ -410,8 +412,8 @@ int dt_expand_level(void *stream, int batch, int level, const dt_params *params,
 
 int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, const int32_t *root_token, int TT_cap,
                    const void *state, int32_t *n_nodes, int32_t *tokens, int32_t *parents, int32_t *depth, float *score,
-                   float *logp, int32_t *src_row, uint64_t *anc_mask) {
-    if (batch < 0) return DT_ERR_INVALID_ARG;
+                   float *logp, int32_t *src_row, uint64_t *anc_mask, int flags) {
+    if (batch < 0 || (flags & ~DT_TREE_EARLY_STOP)) return DT_ERR_INVALID_ARG;
     if (batch == 0) return DT_OK;
     if (!params || !root_token || !state || !n_nodes || !tokens || !parents || !depth || !score || !logp || !src_row ||
         !anc_mask || (uintptr_t)state % 256)
@@ -424,6 +426,7 @@ int dt_finish_tree(void *stream, int batch, const dt_params *params, int V, cons
     ta.root_token = root_token; ta.TT_cap = TT_cap; ta.top_val = ls.top_val; ta.top_id = ls.top_id; ta.lse = ls.lse;
     ta.n_nodes = n_nodes; ta.tokens = tokens; ta.parents = parents; ta.depth = depth; ta.src_row = src_row;
     ta.score = score; ta.logp = logp; ta.anc_mask = (unsigned long long *)anc_mask;
+    ta.early_stop = flags & DT_TREE_EARLY_STOP;
     (void)hipGetLastError();  // a stale error left by another HIP user of this process is not ours
     hipError_t e = dt::tree_launch(ta, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e);

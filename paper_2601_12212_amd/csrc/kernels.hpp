@@ -76,6 +76,7 @@ struct TreeArgs {
     float *score, *logp;
     unsigned long long *anc_mask;
     int64_t seq_rows;
+    int early_stop;         // expansion also ends once the root and the candidates proposed so far number TT
     // level-at-a-time build
     int expand_level;       // 0: whole tree; l > 0: only the set of level-l nodes to expand
     const int32_t *prefix_len;  // may be null (positions then count from 0)

@@ -491,7 +491,10 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
     // ---- expansion, level by level -----------------------------------------------------------
     int p_end = k;  // pool indices below p_end hold real scores (levels computed so far)
     const int l_end = xl > 0 ? xl + 1 : d;
+    // token count of Algorithm 2's expansion loop: the root plus the viable candidates proposed so far
+    int tok_count = a.early_stop ? 1 + __syncthreads_count(tid < k && S.score[tid] > -INFINITY) : 0;
     for (int l = 1; l < l_end; ++l) {
+        if (a.early_stop && tok_count >= TT) break;  // uniform: no further level is expanded
         const int lo = l == 1 ? 0 : k + (l - 2) * kk;
         const int n = l == 1 ? k : kk;
         int *exp_l = S.exp[l];
@@ -557,6 +560,7 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
         // wave that wrote it (every wave writes the whole set) or after block_select's barrier.
         const int nlo = k + (l - 1) * kk;
         const int npad = kk <= COUNT_MAX ? ((kk + 63) & ~63) : kk;
+        int fresh = 0;  // viable candidates this thread has just scored (at most two: kk <= 2 TREE_NT)
         for (int t = tid; t < npad; t += TREE_NT) {
             const int tc = min(t, kk - 1);
             const int s = fdiv(tc, ps.inv_k);
@@ -564,16 +568,18 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
             const float par = S.score[exp_l[min(s, n_exp - 1)]], own = S.score[nlo + tc];
             const float sc = s < n_exp ? par + own : -INFINITY;
             if (t < kk) S.score[nlo + t] = sc;
+            fresh += t < kk && sc > -INFINITY;
             if (kk <= COUNT_MAX) {  // the other pair of arrays: slower waves may still be choosing from this level's
                 S.key[(l + 1) & 1][t] = t < kk ? score_key(sc) : 0u;
                 S.rank[(l + 1) & 1][t] = 0;
             }
         }
         p_end = nlo + kk;
-        __syncthreads();
+        if (a.early_stop) tok_count += __syncthreads_count(fresh >= 1) + __syncthreads_count(fresh >= 2);
+        else __syncthreads();
     }
 
-    if (xl > 0) {  // an earlier level had nothing viable to expand
+    if (xl > 0) {  // an earlier level had nothing viable to expand, or the token count ended the expansion
         if (tid == 0) { a.n_expand[b] = 0; a.state_n_exp[b] = 0; }
         return;
     }

@@ -20,11 +20,12 @@ def _to_torch(a, dtype, device):
 
 class Step:
     def __init__(self, params, prefix_len, Hq, Hkv, D, V, dtype=torch.bfloat16, mode=B.DT_ACCEPT_GREEDY,
-                 temperature=1.0, TT_cap=None, philox_seed=0, device="cuda"):
+                 temperature=1.0, TT_cap=None, philox_seed=0, device="cuda", tree_flags=0):
         self.device, self.dtype = device, dtype
         self.Bsz = len(params)
         self.Hq, self.Hkv, self.D, self.V = Hq, Hkv, D, V
         self.mode, self.temperature, self.philox_seed = mode, float(temperature), int(philox_seed)
+        self.tree_flags = int(tree_flags)
         self.TT_cap = int(TT_cap if TT_cap is not None else max(p[0] for p in params))
         self.host_params = [tuple(int(x) for x in p) for p in params]
         self.host_prefix_len = [int(x) for x in prefix_len]
@@ -88,7 +89,7 @@ class Step:
     def build_tree(self):
         B.dt_build_tree(self.params, self.draft_logits, self.row_off, self.total_rows, self.root_token, self.TT_cap,
                         self.n_nodes, self.tokens, self.parents, self.depth, self.score, self.logp, self.src_row,
-                        self.anc_mask, self.ws)
+                        self.anc_mask, self.ws, self.tree_flags)
 
     def tree_attention(self):
         B.dt_tree_attention(self.q, self.k_tree, self.v_tree, self.n_nodes, self.k_prefix_ptrs, self.v_prefix_ptrs,
@@ -115,7 +116,7 @@ class Step:
         self._a_build = (self.Bsz, p(self.params), p(self.draft_logits), dtc, self.V, self.draft_logits.stride(0),
                          p(self.row_off), self.total_rows, p(self.root_token), self.TT_cap, p(self.n_nodes),
                          p(self.tokens), p(self.parents), p(self.depth), p(self.score), p(self.logp),
-                         p(self.src_row), p(self.anc_mask), p(self.ws), wsb)
+                         p(self.src_row), p(self.anc_mask), p(self.ws), wsb, self.tree_flags)
         self._a_attn = (self.Bsz, dtc, self.Hq, self.Hkv, self.D, self.scale, p(self.q), p(self.k_tree),
                         p(self.v_tree), p(self.n_nodes), p(self.k_prefix_ptrs), p(self.v_prefix_ptrs),
                         p(self.prefix_len), max(self.host_prefix_len), self.Hkv * self.D, self.D, p(self.anc_mask),

@@ -17,18 +17,19 @@ class OracleCase:
     pass
 
 
-def oracle_case(ci, seed=0, cfg=None, philox_step=0, max_bumps=20):
+def oracle_case(ci, seed=0, cfg=None, philox_step=0, max_bumps=20, early_stop=False):
     for bump in range(max_bumps):
         c = dt_synth.config(ci, seed + bump) if cfg is None else cfg
         if cfg is not None:
             c.seed = seed + bump
         case = OracleCase()
         case.cfg = c
+        case.early_stop = early_stop
         case.drafts = [dt_synth.draft_rows(c, b) for b in range(c.B)]
         case.trees = []
         for b in range(c.B):
             TT, d, k = c.params[b]
-            case.trees.append(ref.build_tree(case.drafts[b], TT, d, k, dt_synth.root_token(c, b)))
+            case.trees.append(ref.build_tree(case.drafts[b], TT, d, k, dt_synth.root_token(c, b), early_stop=early_stop))
         margin = min(t["min_margin"] for t in case.trees)
         if margin < TREE_MARGIN:
             print("margin guard: %s seed %d tree margin %.3g -> seed %d" % (c.name, c.seed, margin, c.seed + 1))
@@ -56,7 +57,8 @@ def make_step(case, TT_cap=None):
     c = case.cfg
     st = Step(c.params, c.prefix_len, c.Hq, c.Hkv, c.D, c.V,
               dtype=torch.float32 if c.dtype == "f32" else torch.bfloat16, mode=c.mode,
-              temperature=c.temperature, TT_cap=TT_cap, philox_seed=c.philox_seed)
+              temperature=c.temperature, TT_cap=TT_cap, philox_seed=c.philox_seed,
+              tree_flags=1 if getattr(case, "early_stop", False) else 0)
     dt_synth.fill_draft_and_qkv(st, c, case.drafts)
     for b in range(c.B):
         st.set_target(b, case.targets[b])

@@ -71,13 +71,14 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_topk_rows(None, one, 1, 4, 1024, 1024, 4, one, one, one, C.c_void_p(4100), 1 << 20) == -3
     # build_tree: TT_cap over the limit, null params, too few rows, small workspace
     args = lambda **kw: [kw.get("stream"), kw.get("batch", 1), kw.get("params", one), one, 1, 1024, 1024, one,
-                         kw.get("rows", 5), one, kw.get("TT_cap", 8)] + [one] * 8 + [ws, kw.get("wsb", 1 << 24)]
+                         kw.get("rows", 5), one, kw.get("TT_cap", 8)] + [one] * 8 + [ws, kw.get("wsb", 1 << 24), kw.get("flags", 0)]
     assert lib.dt_build_tree(*args(TT_cap=129)) == -2
     assert lib.dt_build_tree(*args(TT_cap=0)) == -2
     assert lib.dt_build_tree(*args(params=None)) == -1
     assert lib.dt_build_tree(*args(batch=4, rows=3)) == -1
     assert lib.dt_build_tree(*args(wsb=64)) == -3
     assert lib.dt_build_tree(*args(batch=0)) == 0
+    assert lib.dt_build_tree(*args(flags=2)) == -1          # an unknown flag bit
     # attention: Hq not a multiple of Hkv, head dim over the limit, non-positive scale
     att = lambda **kw: [None, 1, 1, kw.get("Hq", 32), kw.get("Hkv", 8), kw.get("D", 128), kw.get("scale", 0.1),
                         one, one, one, one, one, one, one, 1024, 1024, 128, one, 60, one, ws, 1 << 24]
@@ -94,7 +95,8 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_accept(*acc(wsb=8)) == -3
     # level-at-a-time build: level / rows-per-sequence out of range, misaligned state, null outputs
     lev = lambda **kw: [None, kw.get("batch", 1), kw.get("level", 1), one, one, 1, 1024, 1024, kw.get("rps", 8), None, 60,
-                        kw.get("state", ws), kw.get("nexp", one), one, one, one, one, one, ws, kw.get("wsb", 1 << 24)]
+                        kw.get("state", ws), kw.get("nexp", one), one, one, one, one, one, ws, kw.get("wsb", 1 << 24),
+                        kw.get("flags", 0)]
     assert lib.dt_expand_level(*lev(level=0)) == -1
     assert lib.dt_expand_level(*lev(level=9)) == -1
     assert lib.dt_expand_level(*lev(rps=33)) == -1
@@ -102,10 +104,13 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.dt_expand_level(*lev(nexp=None)) == -1
     assert lib.dt_expand_level(*lev(wsb=16)) == -3
     assert lib.dt_expand_level(*lev(batch=0)) == 0
-    fin = lambda **kw: [None, kw.get("batch", 1), one, 1024, one, kw.get("TT_cap", 60), kw.get("state", ws)] + [one] * 8
+    assert lib.dt_expand_level(*lev(flags=4)) == -1
+    fin = lambda **kw: [None, kw.get("batch", 1), one, 1024, one, kw.get("TT_cap", 60), kw.get("state", ws)] + [one] * 8 + \
+                       [kw.get("flags", 0)]
     assert lib.dt_finish_tree(*fin(TT_cap=0)) == -2
     assert lib.dt_finish_tree(*fin(state=None)) == -1
     assert lib.dt_finish_tree(*fin(batch=0)) == 0
+    assert lib.dt_finish_tree(*fin(flags=3)) == -1
     nbytes = C.c_size_t(0)
     assert lib.dt_level_state_bytes(3, C.byref(nbytes)) == 0 and nbytes.value >= 3 * 225 * (32 * 8 + 4)
     # policy: hidden size / action count over the limits, bad interval, small workspace
@@ -150,7 +155,7 @@ def test_launch_grid_limits_are_checked_on_the_host():
                                        one, one, one, one, None, ws, wsb]
     assert lib.dt_accept(*acc(512, 128, 16)) == -3              # 65,536 rows: fine
     assert lib.dt_accept(*acc(1 << 24, 128, 1 << 40)) == -2     # 2^31 rows
-    bt = lambda rows: [None, 1, one, one, 1, 1024, 1024, one, rows, one, 8] + [one] * 8 + [ws, 16]
+    bt = lambda rows: [None, 1, one, one, 1, 1024, 1024, one, rows, one, 8] + [one] * 8 + [ws, 16, 0]
     assert lib.dt_build_tree(*bt(70000)) == -3
     assert lib.dt_build_tree(*bt(1 << 31)) == -2
     att = lambda batch, Hq: [None, batch, 1, Hq, 8, 128, 0.1, one, one, one, one, one, one, one, 1024, 1024, 128, one, 60,

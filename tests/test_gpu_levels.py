@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def drive(params, prefix_len, V, bf16, seed):
+def drive(params, prefix_len, V, bf16, seed, flags=0):
     import paper_2601_12212_amd as dt
     B = len(params)
     KR = max(p[2] for p in params)
@@ -51,7 +51,8 @@ def drive(params, prefix_len, V, bf16, seed):
         dev = torch.from_numpy(logits).cuda()
         if bf16:
             dev = dev.to(torch.bfloat16)
-        dt.dt_expand_level(level, d_params, dev, KR, d_plen, TT_cap, state, n_exp, e_tok, e_par, e_row, e_pos, e_mask, ws)
+        dt.dt_expand_level(level, d_params, dev, KR, d_plen, TT_cap, state, n_exp, e_tok, e_par, e_row, e_pos, e_mask, ws,
+                           flags=flags)
         torch.cuda.synchronize()
         for b in range(B):
             n = int(n_exp[b])
@@ -68,11 +69,12 @@ def drive(params, prefix_len, V, bf16, seed):
     score, logp = mk(torch.float32), mk(torch.float32)
     anc = torch.zeros((B, TT_cap, 2), dtype=torch.int64, device="cuda")
     roots = torch.tensor([100 + b for b in range(B)], **i32)
-    dt.dt_finish_tree(d_params, V, roots, TT_cap, state, n_nodes, tokens, parents, depth, score, logp, src_row, anc)
+    dt.dt_finish_tree(d_params, V, roots, TT_cap, state, n_nodes, tokens, parents, depth, score, logp, src_row, anc,
+                      flags=flags)
     torch.cuda.synchronize()
     for b, (TT, d, k) in enumerate(params):
         rows = dt_synth.f32_to_bf16_bits(rows_all[b]) if bf16 else rows_all[b]
-        want = ref.build_tree(rows, TT, d, k, 100 + b, with_levels=True)
+        want = ref.build_tree(rows, TT, d, k, 100 + b, with_levels=True, early_stop=bool(flags))
         assert want["min_margin"] >= TREE_MARGIN, ("pick another seed", b, want["min_margin"])
         N = int(n_nodes[b])
         got = dict(n_nodes=N, tokens=tokens[b, :N].cpu().numpy(), parents=parents[b, :N].cpu().numpy(),
@@ -96,6 +98,14 @@ def drive(params, prefix_len, V, bf16, seed):
 def test_level_by_level_fp32_ragged_batch():
     drive([(30, 4, 3), (60, 6, 4), (1, 3, 2), (12, 1, 5), (128, 8, 2), (20, 3, 8)], [5, 0, 9, 1000, 77, 3], V=300,
           bf16=False, seed=1)
+
+
+def test_level_by_level_with_the_token_count_exit():
+    # the draft model's loop ends early: levels past the exit report no node, the rows handed in for them are
+    # ignored, and the finished tree is the one-shot tree under the same flag
+    import paper_2601_12212_amd as dt
+    drive([(5, 3, 8), (12, 5, 4), (30, 4, 3), (60, 6, 10), (128, 3, 3), (1, 4, 4), (40, 8, 2)], [3, 0, 9, 100, 77, 5, 6],
+          V=300, bf16=False, seed=4, flags=dt.DT_TREE_EARLY_STOP)
 
 
 def test_level_by_level_bf16_wide_levels():

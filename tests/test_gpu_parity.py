@@ -195,6 +195,21 @@ def test_degenerate_tree_shapes(params):
     check_case(oracle_case(0, cfg=cfg))
 
 
+def test_token_count_exit_of_the_expansion_loop():
+    # DT_TREE_EARLY_STOP: expansion ends once the root and the proposed candidates number TT.  No expansion
+    # at all (1 + k >= TT), a stop after one, two and three levels, a budget that never binds, wide levels
+    # that go through the bucket selection, TT = 1; the draft rows of the unexpanded levels are still there.
+    params = [(5, 3, 8), (12, 5, 4), (30, 4, 3), (60, 6, 10), (128, 3, 3), (96, 8, 20), (1, 4, 4), (40, 8, 2)]
+    cfg = small_cfg(params, [40 + 7 * i for i in range(len(params))])
+    case = oracle_case(0, cfg=cfg, early_stop=True)
+    depths = [int(t["depth"].max()) for t in case.trees]
+    assert depths[0] == 1 and depths[1] == 2 and depths[3] == 2 and depths[4] == 3 and depths[5] == 2, depths
+    plain = oracle_case(0, cfg=small_cfg(params, [40 + 7 * i for i in range(len(params))]))
+    assert any(p["n_nodes"] != e["n_nodes"] or not np.array_equal(p["tokens"], e["tokens"])
+               for p, e in zip(plain.trees, case.trees))            # the flag does change trees here
+    check_case(case)
+
+
 def test_large_pool_uses_the_workgroup_wide_cut():
     cfg = small_cfg([(128, 8, 16)], [40], V=2000)                # pool 16 + 7*256 = 1808 > 1024
     check_case(oracle_case(0, cfg=cfg))
