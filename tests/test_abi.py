@@ -169,3 +169,25 @@ def test_action_table_matches_the_oracle_and_the_golden_sets():
     table = dt.dt_action_table()
     assert table == [tuple(int(v) for v in r) for r in ref.action_table()]
     assert len(table) == 177 and dt.dt_policy_workspace_bytes(4, 12288, 128) >= 192 * 4 * 128 * 4
+
+
+def test_binding_argument_lists_have_the_length_of_the_header_prototypes():
+    """A parameter added to a prototype and forgotten in the ctypes argument list would shift every later
+    argument silently: the binding's argtypes of each function it declares must be as long as the header's
+    parameter list."""
+    text = open(os.path.join(ROOT, "include", "dt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    protos = re.findall(r"\b(?:int|const char \*|void)\s*(dt_[a-z_0-9]+)\s*\(([^;{]*?)\)\s*;", text, flags=re.S)
+    assert len(protos) >= 20
+    lib = dt.load_library()
+    checked = 0
+    for name, args in protos:
+        args = args.strip()
+        want = 0 if args in ("", "void") else len(args.split(","))
+        fn = getattr(lib, name)
+        if fn.argtypes is None:
+            assert want == 0 or name.startswith("dt_profile") or name.endswith("_string") or name == "dt_last_hip_error", name
+            continue
+        assert len(fn.argtypes) == want, (name, len(fn.argtypes), want)
+        checked += 1
+    assert checked >= 12
