@@ -919,9 +919,19 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a) {
         if (vis) {
             const T *kp = t < L ? kpre + (int64_t)t * a.kv_stride_tok + (int64_t)h * a.kv_stride_head
                                 : ktree + ((int64_t)(t - L) * a.Hkv + h) * D;
-            float dot = 0.f;
-            for (int cidx = 0; cidx < D; ++cidx) dot = fmaf(s_q[cidx], ld(kp + cidx), dot);
-            s = dot * a.scale;
+            // four partial sums, 64 loads requested together: the row is read at memory latency once per
+            // 64 elements, not once per element
+            float d4[4] = {0.f, 0.f, 0.f, 0.f};
+            int cidx = 0;
+            for (; cidx + 64 <= D; cidx += 64) {
+                float kv[64];
+#pragma unroll
+                for (int u = 0; u < 64; ++u) kv[u] = ld(kp + cidx + u);
+#pragma unroll
+                for (int u = 0; u < 64; ++u) d4[u & 3] = fmaf(s_q[cidx + u], kv[u], d4[u & 3]);
+            }
+            for (; cidx < D; ++cidx) d4[0] = fmaf(s_q[cidx], ld(kp + cidx), d4[0]);
+            s = ((d4[0] + d4[1]) + (d4[2] + d4[3])) * a.scale;
         }
         const float m_new = fmaxf(m_run, wave_max(s));
         if (m_new == -INFINITY) continue;
@@ -930,15 +940,25 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a) {
         l_run = l_run * alpha + wave_sum(p);
         o0 *= alpha; o1 *= alpha;
         m_run = m_new;
+        // V rows sixteen at a time, all their loads requested before the first is used; keys past the end
+        // repeat the last row with probability 0
         const int cnt = min(64, Tk - t0);
-        for (int j = 0; j < cnt; ++j) {
-            const float pj = __shfl(p, j, 64);
-            if (pj == 0.f) continue;
-            const int tj = t0 + j;
-            const T *vp = tj < L ? vpre + (int64_t)tj * a.kv_stride_tok + (int64_t)h * a.kv_stride_head
-                                 : vtree + ((int64_t)(tj - L) * a.Hkv + h) * D;
-            if (lane < D) o0 = fmaf(pj, ld(vp + lane), o0);
-            if (lane + 64 < D) o1 = fmaf(pj, ld(vp + lane + 64), o1);
+        for (int j0 = 0; j0 < cnt; j0 += 16) {
+            float v0[16], v1[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const int tj = min(t0 + j0 + u, Tk - 1);
+                const T *vp = tj < L ? vpre + (int64_t)tj * a.kv_stride_tok + (int64_t)h * a.kv_stride_head
+                                     : vtree + ((int64_t)(tj - L) * a.Hkv + h) * D;
+                v0[u] = lane < D ? ld(vp + lane) : 0.f;
+                v1[u] = lane + 64 < D ? ld(vp + lane + 64) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 16; ++u) {
+                const float pj = __shfl(p, j0 + u, 64);  // lanes at and past cnt hold 0
+                o0 = pj != 0.f ? fmaf(pj, v0[u], o0) : o0;   // a hidden key's row is not even multiplied by 0
+                o1 = pj != 0.f ? fmaf(pj, v1[u], o1) : o1;
+            }
         }
     }
     const float inv = l_run > 0.f ? 1.0f / l_run : 0.f;
