@@ -210,6 +210,14 @@ def test_token_count_exit_of_the_expansion_loop():
     check_case(case)
 
 
+def test_config2_shape_with_the_token_count_exit():
+    # the Llama-3-8B configuration (TT=60, d=6, k=10) under DT_TREE_EARLY_STOP: 1 + 10 + 100 >= 60 ends the
+    # expansion after level 1's nodes have been expanded, so the tree has depth 2 and 41 of its 51 rows go unused
+    case = oracle_case(2, early_stop=True)
+    assert int(case.trees[0]["depth"].max()) == 2 and case.trees[0]["n_nodes"] == 60
+    check_case(case)
+
+
 def test_large_pool_uses_the_workgroup_wide_cut():
     cfg = small_cfg([(128, 8, 16)], [40], V=2000)                # pool 16 + 7*256 = 1808 > 1024
     check_case(oracle_case(0, cfg=cfg))
