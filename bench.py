@@ -237,6 +237,8 @@ def main():
                     help="layers of the separately timed input update (0: skip it)")
     ap.add_argument("--topk-k32", type=int, default=1,
                     help="also time the row top-k at the widest action (k = 32), outside the step (0: skip)")
+    ap.add_argument("--launch-floor", type=int, default=1,
+                    help="also time a graph of dependent one-element kernels (the cost of the step's seven launches alone)")
     ap.add_argument("--read-ceiling-mb", type=int, default=2048,
                     help="size of the read-only pass that measures what a plain stream reaches here (0: skip)")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
@@ -350,6 +352,35 @@ def main():
                    "how": "torch.amax(dim=1) over a [4096, n] fp32 matrix, best of 6, torch events; context only"}
         del probe
         log("  read-only pass over %d MiB: %.0f GB/s" % (args.read_ceiling_mb, ceiling["gbps"]))
+
+    # ---- what seven dependent launches cost on this machine when the kernels do nothing (context for the batch-1
+    #      step, which is seven dependent launches): a HIP graph of 7 x 16 one-element torch kernels ----------------
+    launch_floor = None
+    if args.launch_floor > 0 and not args.eager:
+        one = torch.zeros(1, dtype=torch.float32, device="cuda")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                one.add_(1.0)
+            torch.cuda.synchronize()
+            gf = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gf, stream=side):
+                for _ in range(7 * 16):
+                    one.add_(1.0)
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(24):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            gf.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / (7 * 16))
+        ts.sort()
+        launch_floor = {"us_per_dependent_launch": round(ts[len(ts) // 2], 3), "us_per_7_launches": round(7 * ts[len(ts) // 2], 2),
+                        "how": "graph replay of 112 dependent one-element torch kernels, median of 24; context only"}
+        del gf
+        log("  seven dependent empty launches in a graph: %.2f us" % launch_floor["us_per_7_launches"])
 
     # ---- the input update that follows the step (not part of the timed step): all layers' K/V rows of
     #      the accepted paths appended to the caches; timed on its own with dispatch-attached events ----
@@ -644,6 +675,7 @@ def main():
         "longest_kernel": longest,
         "per_config": per_config,
         "hbm_read_ceiling": ceiling,
+        "launch_floor": launch_floor,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)
