@@ -48,7 +48,7 @@ def check_topk(x, k):
 # ------------------------------------------------------------------------------------ A1 row kernels
 
 @pytest.mark.parametrize("V,k,bf16", [(1024, 2, False), (1000, 10, True), (4097, 32, True), (32000, 8, True),
-                                       (128256, 10, True), (128256, 32, True), (50001, 12, False),
+                                       (128256, 10, True), (128256, 16, True), (128256, 20, True), (128256, 32, True), (50001, 12, False),
                                        (33, 32, True), (8192 * 3 + 5, 1, True)])
 def test_topk_rows_random(V, k, bf16):
     rng = np.random.default_rng(V + k)
