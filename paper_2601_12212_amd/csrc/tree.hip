@@ -3,7 +3,7 @@
 // k + (d-1)k^2 = 7200 scores) lives in LDS.
 //
 // Selections ("the n best by (score desc, pool index asc)") never sort.
-//  * A level of up to 256 candidates is ranked by counting: every candidate counts the candidates with
+//  * A level of up to 128 candidates (k <= 11) is ranked by counting: every candidate counts the candidates with
 //    a larger key, the work split over the waves by (64 candidates) x (a slice of the others), the
 //    others read as LDS broadcasts.  Every wave then forms the chosen set by itself from the partial
 //    counts, so the next level's scores follow without another barrier.
@@ -25,7 +25,7 @@ namespace dt {
 #define TREE_NT 512               // threads of the workgroup
 #endif
 #define TREE_NW (TREE_NT / 64)    // its waves
-#define COUNT_MAX 256             // largest level ranked by counting
+#define COUNT_MAX 128             // largest level ranked by counting (beyond it the bucket cut is faster: measured)
 #define BUCKET_CAP 64             // most candidates of one score bucket that are ranked one against the other
 
 __device__ __forceinline__ u32 score_key(float s) { return ord32(s); }
@@ -356,14 +356,15 @@ __device__ __forceinline__ void count_above4(const uint4 o, u32 mine, int &c0, i
 }
 
 // ---- ranking a level by counting ---------------------------------------------------------------------
-// key[0 .. 64 G) holds the keys of the level's n candidates (zero beyond n), G = ceil(n / 64) <= 4, and
+// key[0 .. 64 G) holds the keys of the level's n candidates (zero beyond n), G = ceil(n / 64) <= 2, and
 // rank[0 .. 64 G) is zero.  Wave w counts, for the 64 candidates of group w % G, the keys above
 // theirs within slice w / G of the level, and adds that to their rank.  Ties are counted as "not above",
 // so candidates of equal key share a rank; the caller detects a tie that straddles the cut by the size
 // of the chosen set.
 template <int G>
 __device__ __forceinline__ void level_count(const u32 *key, int *rank) {
-    constexpr int H = G == 1 ? TREE_NW : G == 2 ? TREE_NW / 2 : TREE_NW / 4;  // slices
+    static_assert(G == 1 || G == 2, "groups of 64 candidates");
+    constexpr int H = G == 1 ? TREE_NW : TREE_NW / 2;  // slices
     constexpr int PER = 64 * G / H;                                           // keys per slice (padding included)
     const int lane = lane_id(), w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     if (w < G * H) {
@@ -510,15 +511,11 @@ __global__ __launch_bounds__(TREE_NT) void tree_kernel(TreeArgs a) {
             const int G = (n + 63) >> 6;
             if (n > k) {  // otherwise every viable candidate is chosen
                 if (G == 1) level_count<1>(key, rank);
-                else if (G == 2) level_count<2>(key, rank);
-                else if (G == 3) level_count<3>(key, rank);
-                else level_count<4>(key, rank);
+                else level_count<2>(key, rank);
                 __syncthreads();
             }
             if (G == 1) n_exp = level_choose<1>(key, rank, n, k, put);
-            else if (G == 2) n_exp = level_choose<2>(key, rank, n, k, put);
-            else if (G == 3) n_exp = level_choose<3>(key, rank, n, k, put);
-            else n_exp = level_choose<4>(key, rank, n, k, put);
+            else n_exp = level_choose<2>(key, rank, n, k, put);
         }
         if (n_exp < 0) n_exp = block_select(S.score + lo, n, k, S, put);
         if (l == xl) {
