@@ -238,7 +238,7 @@ static int select_best(const cand_t *pool, int lo, int hi, int keep, unsigned ch
  *   (the root) and grows by the candidates each expansion proposes (the root's k, then up to k per
  *   expanded node); no further level is expanded once token_count >= TT.  Levels never expanded
  *   report exp_count = 0 and their rows are not read.  With early_stop == 0, TT binds only at the
- *   rerank (Section 3.2, "all tokens in the tree are reranked").
+ *   rerank (Section 3.2: the rerank sees every token of the finished tree).
  */
 int ref_build_tree(const void *rows, int dtype, int V, int64_t row_stride, int n_rows_avail,
                    int TT, int d, int k, int32_t root_token, int TT_cap,
