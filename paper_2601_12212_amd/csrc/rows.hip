@@ -90,20 +90,42 @@ __device__ __forceinline__ u32 wave_kth_largest(u32 key, int k) {
 template <int NL, bool BF16, bool VEC>
 __device__ __forceinline__ void load_chunk(const RowArgs &a, int64_t g, int base, float (&x)[8 * NL]) {
     const int V = a.V;
+    // Vector path: every lane's NL loads are unconditional and therefore in flight together (a load inside a
+    // branch is waited for inside that branch: the NL trips to memory would follow one another).  A lane whose
+    // eight elements do not all lie inside the row reads the row's first eight instead (V >= 8 on this path)
+    // and replaces them afterwards: at most one lane of a row straddles its end.
     if (BF16) {
         const uint16_t *row = (const uint16_t *)a.logits + g * a.row_stride;
+        if (VEC) {
+            uint4 r[NL];
 #pragma unroll
-        for (int n = 0; n < NL; ++n) {
-            int id0 = base + n * 512;
-            if (VEC && id0 + 8 <= V) {
-                uint4 r = *(const uint4 *)(row + id0);
-                u32 rr[4] = {r.x, r.y, r.z, r.w};
+            for (int n = 0; n < NL; ++n) {
+                const int id0 = base + n * 512;
+                r[n] = *(const uint4 *)(row + (id0 + 8 <= V ? id0 : 0));
+            }
+            __builtin_amdgcn_sched_barrier(0);  // all loads requested before the first conversion
+#pragma unroll
+            for (int n = 0; n < NL; ++n) {
+                const u32 rr[4] = {r[n].x, r[n].y, r[n].z, r[n].w};
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     x[n * 8 + 2 * p] = __uint_as_float(rr[p] << 16);
                     x[n * 8 + 2 * p + 1] = __uint_as_float(rr[p] & 0xFFFF0000u);
                 }
-            } else {
+            }
+#pragma unroll
+            for (int n = 0; n < NL; ++n) {
+                const int id0 = base + n * 512;
+                if (id0 + 8 > V) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        x[n * 8 + e] = id0 + e < V ? bf16_bits_to_float(row[id0 + e]) : -INFINITY;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < NL; ++n) {
+                const int id0 = base + n * 512;
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     x[n * 8 + e] = id0 + e < V ? bf16_bits_to_float(row[id0 + e]) : -INFINITY;
@@ -111,14 +133,32 @@ __device__ __forceinline__ void load_chunk(const RowArgs &a, int64_t g, int base
         }
     } else {
         const float *row = (const float *)a.logits + g * a.row_stride;
+        if (VEC) {
+            float4 r0[NL], r1[NL];
 #pragma unroll
-        for (int n = 0; n < NL; ++n) {
-            int id0 = base + n * 512;
-            if (VEC && id0 + 8 <= V) {
-                float4 r0 = *(const float4 *)(row + id0), r1 = *(const float4 *)(row + id0 + 4);
-                x[n * 8 + 0] = r0.x; x[n * 8 + 1] = r0.y; x[n * 8 + 2] = r0.z; x[n * 8 + 3] = r0.w;
-                x[n * 8 + 4] = r1.x; x[n * 8 + 5] = r1.y; x[n * 8 + 6] = r1.z; x[n * 8 + 7] = r1.w;
-            } else {
+            for (int n = 0; n < NL; ++n) {
+                const int id0 = base + n * 512, idv = id0 + 8 <= V ? id0 : 0;
+                r0[n] = *(const float4 *)(row + idv);
+                r1[n] = *(const float4 *)(row + idv + 4);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int n = 0; n < NL; ++n) {
+                x[n * 8 + 0] = r0[n].x; x[n * 8 + 1] = r0[n].y; x[n * 8 + 2] = r0[n].z; x[n * 8 + 3] = r0[n].w;
+                x[n * 8 + 4] = r1[n].x; x[n * 8 + 5] = r1[n].y; x[n * 8 + 6] = r1[n].z; x[n * 8 + 7] = r1[n].w;
+            }
+#pragma unroll
+            for (int n = 0; n < NL; ++n) {
+                const int id0 = base + n * 512;
+                if (id0 + 8 > V) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[n * 8 + e] = id0 + e < V ? row[id0 + e] : -INFINITY;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int n = 0; n < NL; ++n) {
+                const int id0 = base + n * 512;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[n * 8 + e] = id0 + e < V ? row[id0 + e] : -INFINITY;
             }
@@ -503,7 +543,7 @@ static dim3 rows_grid(int chunks, int64_t n_rows) {
 
 static bool rows_vec_ok(const RowArgs &a) {
     const int esz = a.dtype == DT_BF16 ? 2 : 4;
-    return ((uintptr_t)a.logits % 16 == 0) && ((a.row_stride * esz) % 16 == 0);
+    return ((uintptr_t)a.logits % 16 == 0) && ((a.row_stride * esz) % 16 == 0) && a.V >= 8;
 }
 
 #define DT_ROWS_DISPATCH(KID, KERNEL, NLV, GRID)                                                          \
