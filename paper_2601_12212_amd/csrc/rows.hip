@@ -87,45 +87,59 @@ __device__ __forceinline__ u32 wave_kth_largest(u32 key, int k) {
 // -------------------------------------------------------------------- chunk loading -----
 // Element (n, e) of a lane, n < NL, e < 8, has id = base + n*512 + e with
 // base = chunk*256*8*NL + wave*64*8*NL + lane*8: one coalesced 16-byte load per (lane, n).
+// Two halves, so that a kernel can put other waits (the row's metadata) between them:
+// chunk_request asks for a lane's NL 16-byte groups (32-byte for fp32), unconditionally, so that they are in
+// flight together -- a load inside a branch is waited for inside that branch, and the NL trips to memory would
+// follow one another.  A lane whose eight elements do not all lie inside the row asks for the row's first eight
+// instead (V >= 8 on the vector path); chunk_finish converts what arrived and patches those lanes (at most one
+// lane of a row straddles its end) with element loads.  Without VEC everything happens in chunk_finish.
+template <int NL, bool BF16>
+struct RawChunk {
+    uint4 r[BF16 ? NL : 2 * NL];
+};
 template <int NL, bool BF16, bool VEC>
-__device__ __forceinline__ void load_chunk(const RowArgs &a, int64_t g, int base, float (&x)[8 * NL]) {
+__device__ __forceinline__ void chunk_request(const RowArgs &a, int64_t g, int base, RawChunk<NL, BF16> &raw) {
+    if (!VEC) return;
     const int V = a.V;
-    // Vector path: every lane's NL loads are unconditional and therefore in flight together (a load inside a
-    // branch is waited for inside that branch: the NL trips to memory would follow one another).  A lane whose
-    // eight elements do not all lie inside the row reads the row's first eight instead (V >= 8 on this path)
-    // and replaces them afterwards: at most one lane of a row straddles its end.
+    if (BF16) {
+        const uint16_t *row = (const uint16_t *)a.logits + g * a.row_stride;
+#pragma unroll
+        for (int n = 0; n < NL; ++n) {
+            const int id0 = base + n * 512;
+            raw.r[n] = *(const uint4 *)(row + (id0 + 8 <= V ? id0 : 0));
+        }
+    } else {
+        const float *row = (const float *)a.logits + g * a.row_stride;
+#pragma unroll
+        for (int n = 0; n < NL; ++n) {
+            const int id0 = base + n * 512, idv = id0 + 8 <= V ? id0 : 0;
+            raw.r[2 * n] = *(const uint4 *)(row + idv);
+            raw.r[2 * n + 1] = *(const uint4 *)(row + idv + 4);
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);  // every request is out before anything that follows
+}
+template <int NL, bool BF16, bool VEC>
+__device__ __forceinline__ void chunk_finish(const RowArgs &a, int64_t g, int base, const RawChunk<NL, BF16> &raw,
+                                             float (&x)[8 * NL]) {
+    const int V = a.V;
     if (BF16) {
         const uint16_t *row = (const uint16_t *)a.logits + g * a.row_stride;
         if (VEC) {
-            uint4 r[NL];
 #pragma unroll
             for (int n = 0; n < NL; ++n) {
-                const int id0 = base + n * 512;
-                r[n] = *(const uint4 *)(row + (id0 + 8 <= V ? id0 : 0));
-            }
-            __builtin_amdgcn_sched_barrier(0);  // all loads requested before the first conversion
-#pragma unroll
-            for (int n = 0; n < NL; ++n) {
-                const u32 rr[4] = {r[n].x, r[n].y, r[n].z, r[n].w};
+                const u32 rr[4] = {raw.r[n].x, raw.r[n].y, raw.r[n].z, raw.r[n].w};
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     x[n * 8 + 2 * p] = __uint_as_float(rr[p] << 16);
                     x[n * 8 + 2 * p + 1] = __uint_as_float(rr[p] & 0xFFFF0000u);
                 }
             }
+        }
 #pragma unroll
-            for (int n = 0; n < NL; ++n) {
-                const int id0 = base + n * 512;
-                if (id0 + 8 > V) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        x[n * 8 + e] = id0 + e < V ? bf16_bits_to_float(row[id0 + e]) : -INFINITY;
-                }
-            }
-        } else {
-#pragma unroll
-            for (int n = 0; n < NL; ++n) {
-                const int id0 = base + n * 512;
+        for (int n = 0; n < NL; ++n) {
+            const int id0 = base + n * 512;
+            if (!VEC || id0 + 8 > V) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
                     x[n * 8 + e] = id0 + e < V ? bf16_bits_to_float(row[id0 + e]) : -INFINITY;
@@ -134,31 +148,19 @@ __device__ __forceinline__ void load_chunk(const RowArgs &a, int64_t g, int base
     } else {
         const float *row = (const float *)a.logits + g * a.row_stride;
         if (VEC) {
-            float4 r0[NL], r1[NL];
 #pragma unroll
             for (int n = 0; n < NL; ++n) {
-                const int id0 = base + n * 512, idv = id0 + 8 <= V ? id0 : 0;
-                r0[n] = *(const float4 *)(row + idv);
-                r1[n] = *(const float4 *)(row + idv + 4);
+                const uint4 r0 = raw.r[2 * n], r1 = raw.r[2 * n + 1];
+                x[n * 8 + 0] = __uint_as_float(r0.x); x[n * 8 + 1] = __uint_as_float(r0.y);
+                x[n * 8 + 2] = __uint_as_float(r0.z); x[n * 8 + 3] = __uint_as_float(r0.w);
+                x[n * 8 + 4] = __uint_as_float(r1.x); x[n * 8 + 5] = __uint_as_float(r1.y);
+                x[n * 8 + 6] = __uint_as_float(r1.z); x[n * 8 + 7] = __uint_as_float(r1.w);
             }
-            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
-            for (int n = 0; n < NL; ++n) {
-                x[n * 8 + 0] = r0[n].x; x[n * 8 + 1] = r0[n].y; x[n * 8 + 2] = r0[n].z; x[n * 8 + 3] = r0[n].w;
-                x[n * 8 + 4] = r1[n].x; x[n * 8 + 5] = r1[n].y; x[n * 8 + 6] = r1[n].z; x[n * 8 + 7] = r1[n].w;
-            }
-#pragma unroll
-            for (int n = 0; n < NL; ++n) {
-                const int id0 = base + n * 512;
-                if (id0 + 8 > V) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) x[n * 8 + e] = id0 + e < V ? row[id0 + e] : -INFINITY;
-                }
-            }
-        } else {
-#pragma unroll
-            for (int n = 0; n < NL; ++n) {
-                const int id0 = base + n * 512;
+        for (int n = 0; n < NL; ++n) {
+            const int id0 = base + n * 512;
+            if (!VEC || id0 + 8 > V) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[n * 8 + e] = id0 + e < V ? row[id0 + e] : -INFINITY;
             }
@@ -195,11 +197,14 @@ __global__ __launch_bounds__(256) void row_stream_kernel(RowArgs a) {
     const int lane = lane_id(), w = threadIdx.x >> 6;
     const int base = c * (256 * E) + w * (64 * E) + lane * 8;
     if (g >= a.n_rows) return;
+    // early: the row's elements are on their way while the (dependent, scalar) reads of its metadata are waited for
     float x[E];
-    if (a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
+    RawChunk<NL, BF16> raw;
+    if (a.early_load) chunk_request<NL, BF16, VEC>(a, g, base, raw);
     const RowMeta meta = row_meta(a, g);
     if (!meta.valid) return;
-    if (!a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
+    if (!a.early_load) chunk_request<NL, BF16, VEC>(a, g, base, raw);
+    chunk_finish<NL, BF16, VEC>(a, g, base, raw, x);
     float mx = x[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
@@ -469,11 +474,14 @@ __global__ __launch_bounds__(256) void row_argmax_kernel(RowArgs a) {
 
     const int base = c * (256 * E) + w * (64 * E) + lane * 8;
     if (g >= a.n_rows) return;
+    // early: the row's elements are on their way while the (dependent, scalar) reads of its metadata are waited for
     float x[E];
-    if (a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
+    RawChunk<NL, BF16> raw;
+    if (a.early_load) chunk_request<NL, BF16, VEC>(a, g, base, raw);
     const RowMeta meta = row_meta(a, g);
     if (!meta.valid) return;
-    if (!a.early_load) load_chunk<NL, BF16, VEC>(a, g, base, x);
+    if (!a.early_load) chunk_request<NL, BF16, VEC>(a, g, base, raw);
+    chunk_finish<NL, BF16, VEC>(a, g, base, raw, x);
     float mx = x[0];
 #pragma unroll
     for (int j = 1; j < E; ++j) mx = fmaxf(mx, x[j]);
