@@ -12,20 +12,57 @@ __device__ __forceinline__ float load_logit(const void *base, int dtype, int64_t
     return dtype == DT_BF16 ? bf16_bits_to_float(((const uint16_t *)base)[idx]) : ((const float *)base)[idx];
 }
 
-// Eight consecutive entries id .. id+7 of a row (entries at or past `hi` read as -inf).  The eight
-// loads are independent, so they are in flight together; aligned bf16 octets take one 16-byte load.
-__device__ __forceinline__ void load_logits8(const void *row, int dtype, int id, int hi, bool vec_ok, float out[8]) {
-    if (dtype == DT_BF16 && vec_ok && id + 8 <= hi) {
-        const uint4 raw = *(const uint4 *)((const uint16_t *)row + id);
-        const u32 wds[4] = {raw.x, raw.y, raw.z, raw.w};
+// The up to 32 consecutive entries id0 .. id0 + epl - 1 of a row that a thread owns (epl a multiple of 8; entries
+// at or past `hi`, and octets past epl, read as -inf), as four octets.  Every load is unconditional, so that all
+// of a thread's loads are in flight together (a load inside a branch is waited for inside that branch): an
+// aligned bf16 octet that lies wholly inside the range is one 16-byte load, any other octet asks for the row's
+// first entries instead and is patched with element loads afterwards (at most one octet of a chunk straddles the
+// end of the row).  vec_ok: the row is 16-byte aligned and holds at least 8 entries.
+__device__ __forceinline__ void load_logits32(const void *row, int dtype, int id0, int epl, int hi, bool vec_ok,
+                                              float x[4][8]) {
+    if (dtype == DT_BF16 && vec_ok) {  // uniform
+        uint4 raw[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            out[2 * e] = __uint_as_float(wds[e] << 16);
-            out[2 * e + 1] = __uint_as_float(wds[e] & 0xFFFF0000u);
+        for (int j = 0; j < 4; ++j) {
+            const int id = id0 + 8 * j;
+            const bool full = 8 * j < epl && id + 8 <= hi;
+            raw[j] = *(const uint4 *)((const uint16_t *)row + (full ? id : 0));
+        }
+        __builtin_amdgcn_sched_barrier(0);  // every request is out before the first conversion
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32 wds[4] = {raw[j].x, raw[j].y, raw[j].z, raw[j].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                x[j][2 * e] = __uint_as_float(wds[e] << 16);
+                x[j][2 * e + 1] = __uint_as_float(wds[e] & 0xFFFF0000u);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int id = id0 + 8 * j;
+            if (!(8 * j < epl && id + 8 <= hi)) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    x[j][e] = 8 * j < epl && id + e < hi ? load_logit(row, dtype, id + e) : -INFINITY;
+            }
         }
     } else {
 #pragma unroll
-        for (int e = 0; e < 8; ++e) out[e] = id + e < hi ? load_logit(row, dtype, id + e) : -INFINITY;
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int id = id0 + 8 * j + e;
+                x[j][e] = load_logit(row, dtype, 8 * j < epl && id < hi ? id : 0);
+            }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int id = id0 + 8 * j + e;
+                x[j][e] = 8 * j < epl && id < hi ? x[j][e] : -INFINITY;
+            }
     }
 }
 
@@ -61,12 +98,11 @@ __device__ __forceinline__ void sample_row_block(const AcceptArgs &a, int64_t g,
     const int epl = a.chunk_elems / 256;
     const int lo = cstar * a.chunk_elems, hi = min(a.V, lo + a.chunk_elems);
     const int id0 = lo + tid * epl;
-    const bool vec_ok = ((uintptr_t)row & 15) == 0;  // id0 is a multiple of 8
+    const bool vec_ok = ((uintptr_t)row & 15) == 0 && a.V >= 8;  // id0 is a multiple of 8
     // a thread owns at most 32 entries (four octets): all asked for at once and kept, the thread that
     // holds the crossing walks its registers and nothing is read twice
     float x[4][8];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) load_logits8(row, a.dtype, id0 + 8 * j, 8 * j < epl ? hi : 0, vec_ok, x[j]);
+    load_logits32(row, a.dtype, id0, epl, hi, vec_ok, x);
     double mine = 0.0;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
