@@ -927,6 +927,7 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a) {
                 float kv[64];
 #pragma unroll
                 for (int u = 0; u < 64; ++u) kv[u] = ld(kp + cidx + u);
+                __builtin_amdgcn_sched_barrier(0);  // all requests before the first use
 #pragma unroll
                 for (int u = 0; u < 64; ++u) d4[u & 3] = fmaf(s_q[cidx + u], kv[u], d4[u & 3]);
             }
@@ -950,9 +951,10 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a) {
                 const int tj = min(t0 + j0 + u, Tk - 1);
                 const T *vp = tj < L ? vpre + (int64_t)tj * a.kv_stride_tok + (int64_t)h * a.kv_stride_head
                                      : vtree + ((int64_t)(tj - L) * a.Hkv + h) * D;
-                v0[u] = lane < D ? ld(vp + lane) : 0.f;
-                v1[u] = lane + 64 < D ? ld(vp + lane + 64) : 0.f;
+                v0[u] = ld(vp + min(lane, D - 1));        // unconditional (columns past D repeat the last one and
+                v1[u] = ld(vp + min(lane + 64, D - 1));   // are never stored): a load in a branch is waited for there
             }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int u = 0; u < 16; ++u) {
                 const float pj = __shfl(p, j0 + u, 64);  // lanes at and past cnt hold 0
