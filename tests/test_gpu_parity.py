@@ -49,7 +49,8 @@ def check_topk(x, k):
 
 @pytest.mark.parametrize("V,k,bf16", [(1024, 2, False), (1000, 10, True), (4097, 32, True), (32000, 8, True),
                                        (128256, 10, True), (128256, 16, True), (128256, 20, True), (128256, 32, True), (50001, 12, False),
-                                       (33, 32, True), (8192 * 3 + 5, 1, True)])
+                                       (33, 32, True), (8192 * 3 + 5, 1, True),
+                                       (5, 3, True), (7, 7, False), (8, 8, True), (15, 4, True), (16, 16, False)])
 def test_topk_rows_random(V, k, bf16):
     rng = np.random.default_rng(V + k)
     x = (rng.standard_normal((7, V)) * 3).astype(np.float32)
