@@ -262,6 +262,17 @@ def test_attention_balanced_schedule_on_ragged_batches():
                                             Hq=8, Hkv=2)))
 
 
+@pytest.mark.parametrize("V,dtype,mode", [(7, "bf16", dt_synth.GREEDY), (7, "f32", dt_synth.STOCHASTIC),
+                                          (13, "bf16", dt_synth.STOCHASTIC), (13, "bf16", dt_synth.SAMPLED),
+                                          (8, "bf16", dt_synth.SAMPLED)])
+def test_whole_step_on_vocabularies_around_eight_entries(V, dtype, mode):
+    # below eight entries no 16-byte group fits a row (element loads only), just above it the last group of
+    # a row straddles its end: row streams, arg-max rows and the sampler's chunk re-read all take that path
+    cfg = small_cfg([(6, 3, 2), (12, 2, 5), (1, 1, 1)], [9, 70, 3], V=V, dtype=dtype, mode=mode,
+                    D=128 if dtype == "bf16" else 64, Hq=4, Hkv=2)
+    check_case(oracle_case(0, cfg=cfg, max_bumps=200))
+
+
 def test_stochastic_small_and_many_steps():
     cfg = small_cfg([(40, 5, 4), (64, 6, 6)], [100, 31], V=3001, mode=dt_synth.STOCHASTIC)
     case = oracle_case(0, cfg=cfg)
