@@ -273,6 +273,23 @@ def test_whole_step_on_vocabularies_around_eight_entries(V, dtype, mode):
     check_case(oracle_case(0, cfg=cfg, max_bumps=200))
 
 
+@pytest.mark.parametrize("seed", [11, 12, 13, 14])
+def test_random_batches_of_random_shapes(seed):
+    # a sweep nobody chose by hand: per sequence random (TT, d, k) over the whole range of the limits, random
+    # prefix lengths, a vocabulary that is not a multiple of anything; greedy and stochastic in turn
+    rng = np.random.default_rng(seed)
+    B = 20
+    params, plen = [], []
+    for _ in range(B):
+        k = int(rng.choice([1, 2, 3, 5, 8, 11, 12, 16, 20, 32]))
+        d = int(rng.integers(1, 9))
+        params.append((int(rng.integers(1, 129)), d, k))
+        plen.append(int(rng.choice([0, 1, 31, 32, 33, 64, 200, 777])))
+    mode = dt_synth.GREEDY if seed % 2 else dt_synth.STOCHASTIC
+    cfg = small_cfg(params, plen, V=int(rng.choice([611, 1000, 4099])), Hq=8, Hkv=2, seed=seed, mode=mode)
+    check_case(oracle_case(0, seed=seed, cfg=cfg, max_bumps=60))
+
+
 def test_stochastic_small_and_many_steps():
     cfg = small_cfg([(40, 5, 4), (64, 6, 6)], [100, 31], V=3001, mode=dt_synth.STOCHASTIC)
     case = oracle_case(0, cfg=cfg)
