@@ -334,8 +334,11 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     }
     bool slow = n_hot > SEL_CAP || n_hot < k;  // uniform over the workgroup
 
-    // ---- the row's log-sum-exp, by wave 3 --------------------------------------------------------
-    if (lse_wave) {
+    // ---- the row's log-sum-exp, by wave 3: called where the other waves wait for memory anyway ----------
+    bool lse_done = false;
+    auto row_lse = [&]() {
+        lse_done = true;
+        if (!lse_wave) return;
         const float cexp = 1.4426950408889634f * a.inv_t;
         float M = -INFINITY, Ssum = 0.f;
         if (S <= 16) {
@@ -353,7 +356,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
         float term = (Ssum > 0.f) ? Ssum * __builtin_amdgcn_exp2f((M - Mw) * cexp) : 0.f;
         term = wave_sum(term);
         if (lane == 0) lse[meta.out] = (Mw == -INFINITY) ? -INFINITY : Mw * a.inv_t + __logf(term);
-    }
+    };
 
     if (!slow) {
         // ---- 3. the hot lanes, in any order: a thread reserves room for its hits with one LDS add ----
@@ -379,6 +382,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
         __syncthreads();
         const int h = min(s_h, SEL_CAP);
         const int nl_log2 = nl == 4 ? 2 : nl == 2 ? 1 : 0;  // chunk multipliers are 1, 2 or 4
+        if (h * nl <= 192) row_lse();  // wave 3 has no hot lane to re-read: it merges while the others wait for theirs
         // ---- 4. re-read the hot lanes: (hot lane, load n) pairs spread over the threads ----
         for (int q = tid; q < h * nl; q += 256) {
             const int gl = s_hot[q >> nl_log2], n = q & (nl - 1);
@@ -413,6 +417,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
                 }
             }
         }
+        if (h * nl > 192) row_lse();
         __syncthreads();
         const int n2 = s_n2;
         if (n2 <= SEL_CAP) {
@@ -438,6 +443,7 @@ __global__ __launch_bounds__(256) void row_select_kernel(RowArgs a, int nl, int 
     }
 
     // ---- exact fallback: k rounds of "largest key below the previous winner" ----------------
+    if (!lse_done) row_lse();
     u64 prev = ~0ull;
     for (int r = 0; r < k; ++r) {
         u64 best = 0ull;
