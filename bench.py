@@ -51,7 +51,7 @@ class Workload:
     """One configuration on the device: `copies` independent input sets, the tree-dependent target rows built
     from the device's own tree, argument lists marshalled once."""
 
-    def __init__(self, ci, copies):
+    def __init__(self, ci, copies, kv_head_major=False):
         import torch
 
         import dt_synth
@@ -64,7 +64,7 @@ class Workload:
         self.steps = []
         for _ in range(self.R):
             st = Step(cfg.params, cfg.prefix_len, cfg.Hq, cfg.Hkv, cfg.D, cfg.V, dtype=self.tdtype, mode=cfg.mode,
-                      temperature=cfg.temperature, philox_seed=cfg.philox_seed)
+                      temperature=cfg.temperature, philox_seed=cfg.philox_seed, kv_head_major=kv_head_major)
             dt_synth.fill_draft_and_qkv(st, cfg, self.drafts)
             self.steps.append(st)
         # the target rows follow the tree (row of node i = draft row the node owns + noise): build once
@@ -237,6 +237,8 @@ def main():
                     help="layers of the separately timed input update (0: skip it)")
     ap.add_argument("--topk-k32", type=int, default=1,
                     help="also time the row top-k at the widest action (k = 32), outside the step (0: skip)")
+    ap.add_argument("--kv-layout", choices=["token", "head"], default="token",
+                    help="prefix caches as [token, kv head, D] or [kv head, token, D]")
     ap.add_argument("--launch-floor", type=int, default=1,
                     help="also time a graph of dependent one-element kernels (the cost of the step's seven launches alone)")
     ap.add_argument("--read-ceiling-mb", type=int, default=2048,
@@ -260,7 +262,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     dt.dt_init()
-    W = Workload(args.config, args.copies)
+    W = Workload(args.config, args.copies, args.kv_layout == "head")
     cfg, R, steps, tdtype = W.cfg, W.R, W.steps, W.tdtype
     n_nodes, bytes_step = W.n_nodes, W.bytes_step
     K = -(-args.steps // R) * R              # whole rotations, never fewer steps than asked for
@@ -602,7 +604,7 @@ def main():
             if ci == args.config:
                 continue
             try:
-                Wc = Workload(ci, 16 if ci <= 3 else 2)
+                Wc = Workload(ci, 16 if ci <= 3 else 2, args.kv_layout == "head")
                 per_config.append(summary(Wc, 24, 48))
                 Wc.steps = None
                 del Wc

@@ -20,7 +20,10 @@ def _to_torch(a, dtype, device):
 
 class Step:
     def __init__(self, params, prefix_len, Hq, Hkv, D, V, dtype=torch.bfloat16, mode=B.DT_ACCEPT_GREEDY,
-                 temperature=1.0, TT_cap=None, philox_seed=0, device="cuda", tree_flags=0):
+                 temperature=1.0, TT_cap=None, philox_seed=0, device="cuda", tree_flags=0, kv_head_major=False):
+        """kv_head_major: the prefix caches are laid out [kv head, token, D] (every head's keys contiguous,
+        one common token capacity) instead of [token, kv head, D]; the library takes either through its two
+        strides."""
         self.device, self.dtype = device, dtype
         self.Bsz = len(params)
         self.Hq, self.Hkv, self.D, self.V = Hq, Hkv, D, V
@@ -51,8 +54,16 @@ class Step:
         self.k_tree = torch.zeros((Bz, TC, Hkv, D), dtype=dtype, device=dev)
         self.v_tree = torch.zeros((Bz, TC, Hkv, D), dtype=dtype, device=dev)
         self.out = torch.zeros((Bz, TC, Hq, D), dtype=dtype, device=dev)
-        self.k_prefix = [torch.zeros((max(L, 1), Hkv, D), dtype=dtype, device=dev) for L in self.host_prefix_len]
-        self.v_prefix = [torch.zeros((max(L, 1), Hkv, D), dtype=dtype, device=dev) for L in self.host_prefix_len]
+        self.kv_head_major = bool(kv_head_major)
+        if self.kv_head_major:
+            cap = max(max(self.host_prefix_len), 1)
+            shapes = [(Hkv, cap, D)] * Bz
+            self.kv_stride_tok, self.kv_stride_head = D, cap * D
+        else:
+            shapes = [(max(L, 1), Hkv, D) for L in self.host_prefix_len]
+            self.kv_stride_tok, self.kv_stride_head = Hkv * D, D
+        self.k_prefix = [torch.zeros(s, dtype=dtype, device=dev) for s in shapes]
+        self.v_prefix = [torch.zeros(s, dtype=dtype, device=dev) for s in shapes]
         self.k_prefix_ptrs = torch.tensor([t.data_ptr() for t in self.k_prefix], dtype=torch.int64, device=dev)
         self.v_prefix_ptrs = torch.tensor([t.data_ptr() for t in self.v_prefix], dtype=torch.int64, device=dev)
         self.prefix_len = torch.tensor(self.host_prefix_len, dtype=i32, device=dev)
@@ -82,8 +93,13 @@ class Step:
         self.k_tree[b, :n].copy_(_to_torch(kt, self.dtype, self.device))
         self.v_tree[b, :n].copy_(_to_torch(vt, self.dtype, self.device))
         if kp.shape[0]:
-            self.k_prefix[b][:kp.shape[0]].copy_(_to_torch(kp, self.dtype, self.device))
-            self.v_prefix[b][:vp.shape[0]].copy_(_to_torch(vp, self.dtype, self.device))
+            kd, vd = _to_torch(kp, self.dtype, self.device), _to_torch(vp, self.dtype, self.device)
+            if self.kv_head_major:
+                self.k_prefix[b][:, :kp.shape[0]].copy_(kd.permute(1, 0, 2))
+                self.v_prefix[b][:, :vp.shape[0]].copy_(vd.permute(1, 0, 2))
+            else:
+                self.k_prefix[b][:kp.shape[0]].copy_(kd)
+                self.v_prefix[b][:vp.shape[0]].copy_(vd)
 
     # ---- the three calls ------------------------------------------------------------------------
     def build_tree(self):
@@ -93,8 +109,8 @@ class Step:
 
     def tree_attention(self):
         B.dt_tree_attention(self.q, self.k_tree, self.v_tree, self.n_nodes, self.k_prefix_ptrs, self.v_prefix_ptrs,
-                            self.prefix_len, max(self.host_prefix_len), self.Hkv * self.D, self.D, self.anc_mask,
-                            self.scale, self.out, self.ws)
+                            self.prefix_len, max(self.host_prefix_len), self.kv_stride_tok, self.kv_stride_head,
+                            self.anc_mask, self.scale, self.out, self.ws)
 
     def accept(self, philox_step=0):
         B.dt_accept(self.mode, self.temperature, self.target_logits, self.n_nodes, self.tokens, self.parents,
@@ -119,8 +135,8 @@ class Step:
                          p(self.src_row), p(self.anc_mask), p(self.ws), wsb, self.tree_flags)
         self._a_attn = (self.Bsz, dtc, self.Hq, self.Hkv, self.D, self.scale, p(self.q), p(self.k_tree),
                         p(self.v_tree), p(self.n_nodes), p(self.k_prefix_ptrs), p(self.v_prefix_ptrs),
-                        p(self.prefix_len), max(self.host_prefix_len), self.Hkv * self.D, self.D, p(self.anc_mask),
-                        self.TT_cap, p(self.out), p(self.ws), wsb)
+                        p(self.prefix_len), max(self.host_prefix_len), self.kv_stride_tok, self.kv_stride_head,
+                        p(self.anc_mask), self.TT_cap, p(self.out), p(self.ws), wsb)
         self._a_acc_head = (self.Bsz, self.mode, self.temperature, p(self.target_logits), dtc, self.V,
                             self.target_logits.stride(1), p(self.n_nodes), p(self.tokens), p(self.parents),
                             p(self.depth), p(self.logp), p(self.anc_mask), self.TT_cap, self.philox_seed)

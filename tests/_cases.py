@@ -50,7 +50,7 @@ def oracle_case(ci, seed=0, cfg=None, philox_step=0, max_bumps=20, early_stop=Fa
     raise RuntimeError("margin guard: no acceptable seed found")
 
 
-def make_step(case, TT_cap=None):
+def make_step(case, TT_cap=None, kv_head_major=False):
     """Device buffers of the case with draft rows, Q/K/V and (oracle-tree-derived) targets uploaded."""
     import torch
     from paper_2601_12212_amd.step import Step
@@ -58,7 +58,7 @@ def make_step(case, TT_cap=None):
     st = Step(c.params, c.prefix_len, c.Hq, c.Hkv, c.D, c.V,
               dtype=torch.float32 if c.dtype == "f32" else torch.bfloat16, mode=c.mode,
               temperature=c.temperature, TT_cap=TT_cap, philox_seed=c.philox_seed,
-              tree_flags=1 if getattr(case, "early_stop", False) else 0)
+              tree_flags=1 if getattr(case, "early_stop", False) else 0, kv_head_major=kv_head_major)
     dt_synth.fill_draft_and_qkv(st, c, case.drafts)
     for b in range(c.B):
         st.set_target(b, case.targets[b])

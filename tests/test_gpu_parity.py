@@ -136,9 +136,9 @@ def assert_attention(out, want, dtype, tag):
     return err, own
 
 
-def check_case(case, key=None):
+def check_case(case, key=None, kv_head_major=False):
     c = case.cfg
-    st = make_step(case)
+    st = make_step(case, kv_head_major=kv_head_major)
     st.run(philox_step=0)
     torch.cuda.synchronize()
     worst, worst_own = 0.0, -1.0
@@ -239,6 +239,21 @@ def test_attention_key_splits_and_long_prefix():
     # several workgroups and a merge kernel joins the partials
     check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [2000], Hq=8, Hkv=2)))
     check_case(oracle_case(0, cfg=small_cfg([(128, 6, 6), (7, 2, 3)], [4097, 640], Hq=4, Hkv=4)))
+
+
+def test_prefix_caches_laid_out_head_major():
+    # [kv head, token, D] caches with one common token capacity instead of [token, kv head, D]: the two
+    # strides of the call are all that changes; every attention kernel is visited
+    check_case(cached_case(1), key=1, kv_head_major=True)                                            # plain ALU path
+    check_case(oracle_case(0, cfg=small_cfg([(30, 4, 3)], [300], Hq=8, Hkv=2)), kv_head_major=True)   # one workgroup per unit
+    check_case(oracle_case(0, cfg=small_cfg([(128, 6, 6), (7, 2, 3)], [4097, 640], Hq=4, Hkv=4)), kv_head_major=True)  # key splits
+    rng = np.random.default_rng(78)
+    params = [(int(rng.choice([1, 33, 64, 96])), int(rng.integers(1, 6)), int(rng.integers(1, 7))) for _ in range(24)]
+    plen = [int(rng.choice([0, 1, 63, 65, 300, 2500])) for _ in range(24)]
+    check_case(oracle_case(0, cfg=small_cfg(params, plen, V=2053, Hq=32, Hkv=8)), kv_head_major=True)  # balanced schedule
+    params = [(int(rng.choice([5, 40])), 3, 3) for _ in range(70)]
+    check_case(oracle_case(0, cfg=small_cfg(params, [int(rng.integers(0, 200)) for _ in range(70)], V=1031,
+                                            Hq=8, Hkv=2)), kv_head_major=True)                       # one workgroup per item
 
 
 def test_attention_balanced_schedule_on_ragged_batches():
