@@ -41,6 +41,47 @@ __device__ __forceinline__ bf16x4 lds_read_tr4(const __bf16 *p) {
     return __builtin_bit_cast(bf16x4, v);
 }
 
+// The same two LDS reads as bare instructions, for loops that keep the wait counters by hand: the
+// compiler neither counts them nor guards them with a wait for outstanding global_load_lds traffic
+// (it cannot tell a read of one tile from a read of the tile still being filled).  lds_wait<N> lets at
+// most N later LDS operations stay outstanding and ties the wait to the register it releases.
+__device__ __forceinline__ bf16x8 lds_load128(u32 addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
+template <int OFF>
+__device__ __forceinline__ bf16x4 lds_load_tr4(u32 addr) {
+    bf16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void lds_wait(bf16x8 &v) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(v) : "n"(N));
+}
+
+// acc *= alpha, element by element, on an accumulator that stays in the accumulator register file.
+// Written out as instructions because any ordinary vector-ALU use of the accumulators inside the
+// block loop makes the compiler keep a second copy of all of them in vector registers and move the
+// 64 values across in every iteration, although this multiply runs in the first block or two only.
+__device__ __forceinline__ void acc_scale(f32x16 &acc, float alpha) {
+    float t;
+#define ACC_SCALE4(i0)                                                                                          \
+    {                                                                                                           \
+        float e0 = acc[i0], e1 = acc[i0 + 1], e2 = acc[i0 + 2], e3 = acc[i0 + 3];                               \
+        asm volatile("v_accvgpr_read_b32 %4, %0\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %0, %4\n\t"     \
+                     "v_accvgpr_read_b32 %4, %1\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %1, %4\n\t"     \
+                     "v_accvgpr_read_b32 %4, %2\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %2, %4\n\t"     \
+                     "v_accvgpr_read_b32 %4, %3\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %3, %4"          \
+                     : "+a"(e0), "+a"(e1), "+a"(e2), "+a"(e3), "=&v"(t)                                         \
+                     : "v"(alpha));                                                                             \
+        acc[i0] = e0; acc[i0 + 1] = e1; acc[i0 + 2] = e2; acc[i0 + 3] = e3;                                     \
+    }
+    ACC_SCALE4(0) ACC_SCALE4(4) ACC_SCALE4(8) ACC_SCALE4(12)
+#undef ACC_SCALE4
+}
+
 #define ATT_KB 32           // keys per block
 #define ATT_ROWS_PER_WAVE 32
 #define ATT_WAVES 4
@@ -543,9 +584,15 @@ __global__ __launch_bounds__(256) void attn_gang_combine_kernel(AttnArgs a, int 
 // them PRIVATELY (coalesced 16-byte loads, a wave-private LDS tile to bring K into operand
 // layout and V into transposed operand layout, next block prefetched into registers), so the
 // main loop has no barrier at all.  The partial results meet in LDS once at the end; nothing
-// goes through global scratch.  Two waves per SIMD hide each other's instruction latency.
+// goes through global scratch.  Two variants: eight waves that stage each block through registers
+// into padded tiles (one workgroup per unit, short key ranges), and four waves that load straight
+// into LDS (DIRECT: several workgroups per unit, one wave per SIMD, so latency is hidden inside the
+// wave by having every operand read of a block in flight at once).
 #define KT_ELEMS (ATT_KB * K_PITCH)              // per-wave K tile: 32 rows of 272 B
 #define WT_ELEMS (KT_ELEMS + ATT_KB * V_PITCH)   // both tiles of a wave (V: 32 rows of 288 B): 17.5 KB
+#define WD_TILE (ATT_KB * 256)                  // direct layout: one K or V tile of a wave, unpadded rows
+#define WD_STAGE (2 * WD_TILE)                  // K tile + V tile of one stage
+#define WD_LDS_BYTES (4 * 2 * WD_STAGE)         // four waves, two stages: 128 KB
 
 // With KS > 1 the key blocks are additionally dealt over KS workgroups per (sequence, kv head,
 // row block); each leaves its partial (max, sum, O) in global scratch for a small merge kernel.
@@ -556,9 +603,9 @@ struct SplitBuf {
     float2 *ml;   // [unit, KS, 32]: (max, sum) per query row
 };
 
-template <int D, int NW>
+template <int D, int NW, bool DIRECT>
 __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, SplitBuf sb) {
-    static_assert(D == 128 && (NW == 4 || NW == 8), "shape");
+    static_assert(D == 128 && (NW == 4 || NW == 8) && (!DIRECT || NW == 4), "shape");
     constexpr int KSTEPS = D / 16, DBLK = D / 32;
     const int G = a.Hq / a.Hkv;
     // blockIdx.x = kv head: workgroups are dealt to the 8 XCDs round-robin by linear id, so every
@@ -587,8 +634,9 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
     __shared__ float s_m[NW][32], s_l[NW][32];
     float *s_buf = (float *)s_dyn;
-    __bf16 *kt = (__bf16 *)s_dyn + w * WT_ELEMS;
+    __bf16 *kt = (__bf16 *)s_dyn + w * WT_ELEMS;   // staged layout (!DIRECT): padded rows
     __bf16 *vt = kt + KT_ELEMS;
+    unsigned char *wtile = s_dyn + w * 2 * WD_STAGE;  // direct layout: two stages of (K tile, V tile), 256-byte rows
 
     bf16x8 qreg[KSTEPS];
     {
@@ -612,6 +660,152 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
     const gbf16p ktree = (gbf16p)a.k_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
     const gbf16p vtree = (gbf16p)a.v_tree + ((int64_t)b * a.TT_cap * a.Hkv + h) * D;
     const int64_t stok = a.kv_stride_tok, stree = (int64_t)a.Hkv * D;
+    const int kstep = KS * NW;  // the blocks are dealt round-robin over all waves of all splits
+    if constexpr (DIRECT) {
+        // Blocks go straight from global memory into the wave's own LDS tiles (global_load_lds_dwordx4:
+        // the 64 x 16 B of one instruction land contiguously, i.e. four 256-byte rows), two stages, so
+        // no staging registers and no LDS-write instructions; with one wave per SIMD the registers
+        // saved are what lets every operand read of a block be in flight at once.  Chunk c of row r sits
+        // at chunk position c ^ f(r), f as in the large-batch kernel, applied on the global side.
+        const int krow4 = lane >> 4, cpos = lane & 15;
+        u32 koffp[8], voffp[8];  // inside the prefix: byte offsets from the block's first row
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + krow4;
+            koffp[i] = (u32)(r * stok + 8 * (cpos ^ (r & 15))) * 2u;
+            voffp[i] = (u32)(r * stok + 8 * (cpos ^ (((r & 3) << 2) | ((r >> 2) & 3)))) * 2u;
+        }
+        const bool small_stride = (int64_t)ATT_KB * stok * 2 < ((int64_t)1 << 31);
+        // Every load is unconditional: keys past the end are read from the last valid row, their scores
+        // are masked to -inf below, so the duplicated V rows contribute nothing.
+        auto fetch = [&](int kb, int stage) {
+            const ldsp kdst = (ldsp)wtile + stage * WD_STAGE;
+            const ldsp vdst = kdst + WD_TILE;
+            if (small_stride && kb * ATT_KB + ATT_KB <= L) {  // block inside the prefix (uniform test)
+                const gbytep kbase = (gbytep)(kpre + (int64_t)kb * ATT_KB * stok);
+                const gbytep vbase = (gbytep)(vpre + (int64_t)kb * ATT_KB * stok);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    __builtin_amdgcn_global_load_lds(kbase + koffp[i], kdst + i * 1024, 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds(vbase + voffp[i], vdst + i * 1024, 16, 0, 0);
+                }
+            } else {                                           // block touching the tree keys or the end
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int r = 4 * i + krow4;
+                    const int t = min(kb * ATT_KB + r, Tk - 1);
+                    const int64_t o = t < L ? (int64_t)t * stok : (int64_t)(t - L) * stree;
+                    __builtin_amdgcn_global_load_lds((gbytep)((t < L ? kpre : ktree) + o + 8 * (cpos ^ (r & 15))),
+                                                     kdst + i * 1024, 16, 0, 0);
+                    __builtin_amdgcn_global_load_lds(
+                        (gbytep)((t < L ? vpre : vtree) + o + 8 * (cpos ^ (((r & 3) << 2) | ((r >> 2) & 3)))),
+                        vdst + i * 1024, 16, 0, 0);
+                }
+            }
+        };
+        // operand read offsets (bytes inside a tile), as in the large-batch kernel
+        u32 koff[KSTEPS];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) koff[s] = (u32)(col * 256 + (((2 * s + half) ^ (col & 15)) << 4));
+        const int p16 = lane & 15, r0 = p16 >> 2, q4 = p16 & 3, grp = (lane >> 4) & 1;
+        u32 voff[DBLK][2];
+#pragma unroll
+        for (int db = 0; db < DBLK; ++db)
+#pragma unroll
+            for (int hi = 0; hi < 2; ++hi)
+                voff[db][hi] = (u32)((8 * hi + 4 * half + r0) * 256 +
+                                     (((4 * db + 2 * grp + (q4 >> 1)) ^ (4 * r0 + 2 * hi + half)) << 4) + 8 * (q4 & 1));
+
+        int kb = ks * NW + w, cur = 0;
+        if (kb < nb) fetch(kb, 0);
+        for (; kb < nb; kb += kstep, cur ^= 1) {
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this block has landed
+            if (kb + kstep < nb) fetch(kb + kstep, cur ^ 1);  // the other stage was last read one block ago
+            const unsigned char *ktile = wtile + cur * WD_STAGE, *vtile = ktile + WD_TILE;
+            // Every operand of the block is asked for before it is needed (with one wave per SIMD nothing
+            // else hides LDS latency): the eight K reads first, the sixteen transposing V reads between the
+            // MFMAs of S^T, whose accumulator chain leaves the issue slots free.  K read s is followed by
+            // 7 - s K reads and 2 s V reads when its MFMA comes up.
+            const u32 kaddr = (u32)(uintptr_t)(ldsp)ktile, vaddr = kaddr + WD_TILE;
+            bf16x8 ka[KSTEPS];
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) ka[s] = lds_load128(kaddr + koff[s]);
+            bf16x4 vlo[DBLK][2], vhi[DBLK][2];
+            f32x16 sacc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+#define QK_STEP(s, db, st)                                                                  \
+            lds_wait<7 + s>(ka[s]);                                                          \
+            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s], qreg[s], sacc, 0, 0, 0);   \
+            vlo[db][st] = lds_load_tr4<16 * st * 256>(vaddr + voff[db][0]);                  \
+            vhi[db][st] = lds_load_tr4<16 * st * 256>(vaddr + voff[db][1]);                  \
+            __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(0, 0, 0) QK_STEP(1, 1, 0) QK_STEP(2, 2, 0) QK_STEP(3, 3, 0)
+            QK_STEP(4, 0, 1) QK_STEP(5, 1, 1) QK_STEP(6, 2, 1) QK_STEP(7, 3, 1)
+#undef QK_STEP
+
+            const int tbase = kb * ATT_KB;
+            if (tbase + ATT_KB > L) {  // only blocks that contain tree keys (or the end) need the mask
+                // 32-bit visibility window of this lane's query over keys tbase .. tbase+31: prefix keys
+                // are visible, tree key j is visible iff bit j of the node's ancestor set (bits >= N are 0)
+                const int off = tbase - L;  // uniform
+                u32 vis;
+                if (off >= 0) {
+                    const u64 lo = off < 64 ? mask0 : mask1, hi = off < 64 ? mask1 : 0ull;
+                    const int sh = off & 63;
+                    vis = (u32)((lo >> sh) | (sh ? hi << (64 - sh) : 0ull));
+                } else {
+                    vis = ((u32)mask0 << (-off)) | ((1u << (-off)) - 1u);
+                }
+                vis >>= 4 * half;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[i] = ((vis >> (8 * (i >> 2) + (i & 3))) & 1u) ? sacc[i] : -INFINITY;
+            }
+            float mloc = sacc[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, sacc[i]);
+            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            // lazily moved reference maximum, as in the large-batch kernel
+            const bool move = (mloc - m_run) * c > LAZY_LOG2;
+            const float m_new = move ? mloc : m_run;
+            const float m_use = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = move ? __builtin_amdgcn_exp2f((m_run - m_use) * c) : 1.0f;
+            const float nmc = -m_use * c;
+            float psum = 0.f;
+            bf16x8 pb[2];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float p = __builtin_amdgcn_exp2f(fmaf(sacc[i], c, nmc));
+                psum += p;
+                pb[i >> 3][i & 7] = (__bf16)p;
+            }
+            l_run = l_run * alpha + psum;
+            m_run = m_new;
+            if (__ballot(alpha != 1.0f)) {  // the running maximum moved for some query of this wave
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db) acc_scale(oacc[db], alpha);
+            }
+
+            bf16x8 va[2][DBLK];
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+                    va[st][db] = __builtin_shufflevector(vlo[db][st], vhi[db][st], 0, 1, 2, 3, 4, 5, 6, 7);
+            // all V reads have landed (they had the whole softmax); the "memory" clobber also keeps the next
+            // iteration's loads into this stage behind this block's reads
+            asm volatile("s_waitcnt lgkmcnt(0)"
+                         : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[0][2]), "+v"(va[0][3]), "+v"(va[1][0]), "+v"(va[1][1]),
+                           "+v"(va[1][2]), "+v"(va[1][3])
+                         :
+                         : "memory");
+#pragma unroll
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int db = 0; db < DBLK; ++db)
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st][db], pb[st], oacc[db], 0, 0, 0);
+        }
+    } else {
     const int kq = lane >> 4, dc = lane & 15;
     // Loading role of a lane, the same for K and V: load i takes key (i>>2)*16 + 4*kq + (i&3) of
     // the block, columns 8dc..8dc+7, so 16 lanes cover one 256-byte row (fully coalesced).
@@ -645,7 +839,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
         }
     };
 
-    const int kstep = KS * NW;  // the blocks are dealt round-robin over all waves of all splits
     int kb = ks * NW + w;
     if (kb < nb) fetch(kb);
     for (; kb < nb; kb += kstep) {
@@ -728,6 +921,8 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
                     oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[st], oacc[db], 0, 0, 0);
                 }
         }
+    }
+
     }
 
     // ---- the partial results meet ----------------------------------------------------------------
@@ -978,11 +1173,11 @@ __global__ __launch_bounds__(64) void attn_simple_kernel(AttnArgs a) {
 // ------------------------------------------------------------------------------- launchers --
 // LDS beyond 64 KB has to be asked for, once per device (dt_init)
 hipError_t attn_init() {
-    hipError_t e = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 8>, hipFuncAttributeMaxDynamicSharedMemorySize,
+    hipError_t e = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 8, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                        8 * WT_ELEMS * 2);
     if (e == hipSuccess)
-        e = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                4 * WT_ELEMS * 2);
+        e = hipFuncSetAttribute((const void *)attn_wave_kernel<128, 4, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                WD_LDS_BYTES);
     if (e == hipSuccess)
         e = hipFuncSetAttribute((const void *)attn_tile_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, TILE_LDS_BYTES);
     if (e == hipSuccess)
@@ -1043,10 +1238,10 @@ int attn_launch(const AttnArgs &a, hipStream_t st, hipError_t *err) {
         sb.o = (float4 *)a.ws;
         sb.ml = (float2 *)((char *)a.ws + (size_t)units * KS * 4 * 4 * 64 * 16);
         dim3 grid(a.Hkv, mblocks, a.batch * KS);
-        if (nw_sel == 4)  // several workgroups per unit: four waves each (two workgroups fit a compute unit)
-            launch_kernel(KID_ATTN, st, attn_wave_kernel<128, 4>, grid, dim3(256), 4 * WT_ELEMS * 2, a, KS, sb);
+        if (nw_sel == 4)  // several workgroups per unit: four waves each, one workgroup per compute unit (128 KB of LDS)
+            launch_kernel(KID_ATTN, st, attn_wave_kernel<128, 4, true>, grid, dim3(256), WD_LDS_BYTES, a, KS, sb);
         else              // one workgroup per unit: eight waves (two per SIMD), 136 KB of LDS
-            launch_kernel(KID_ATTN, st, attn_wave_kernel<128, 8>, grid, dim3(512), 8 * WT_ELEMS * 2, a, KS, sb);
+            launch_kernel(KID_ATTN, st, attn_wave_kernel<128, 8, false>, grid, dim3(512), 8 * WT_ELEMS * 2, a, KS, sb);
         if (KS > 1) {
             *err = hipGetLastError();
             if (*err != hipSuccess) return DT_ERR_HIP;
