@@ -51,6 +51,16 @@ __device__ __forceinline__ bf16x8 lds_load128(u32 addr) {
     return v;
 }
 template <int OFF>
+__device__ __forceinline__ bf16x8 lds_load128_at(u32 addr) {
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void lds_wait2(bf16x4 &lo, bf16x4 &hi) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(N));
+}
+template <int OFF>
 __device__ __forceinline__ bf16x4 lds_load_tr4(u32 addr) {
     bf16x4 v;
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
@@ -257,36 +267,48 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
         if (active) {
             const unsigned char *kt = s_dyn + cur * STAGE_BYTES, *vt = kt + TILE_BYTES;
             // ---- S^T: 64 keys x 32 queries as two 32x32 blocks -----------------------------------
-            // The two 32-key halves advance together, their K operands requested two k-steps ahead: an
-            // LDS read needs about two MFMA times to come back, and two chains never wait on each other.
+            // The LDS reads are bare instructions with hand-kept waits: eight K reads (four k-steps of both
+            // 32-key halves) stay in flight ahead of the MFMAs, and the first half of the V reads is issued
+            // as soon as the K operands are consumed, so that it lands during the softmax.  (Scheduled by the
+            // compiler, a read was waited for in full a dozen times per block, and a wait for the next
+            // block's global loads stood in front of the first V read.)
+            const u32 kl = (u32)(uintptr_t)(ldsp)kt, vl = kl + TILE_BYTES;
             f32x16 sacc[2];
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[j][i] = 0.f;
-            bf16x8 ka[3][2];
-#pragma unroll
-            for (int s = 0; s < 2; ++s)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) ka[s][j] = *(const bf16x8 *)(kt + j * 32 * 256 + koff[s]);
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
-                if (s + 2 < KSTEPS) {
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) ka[(s + 2) % 3][j] = *(const bf16x8 *)(kt + j * 32 * 256 + koff[s + 2]);
-                }
-#pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[s % 3][j], qreg[s], sacc[j], 0, 0, 0);
-            }
-            // keep that order: four reads ahead, then {two reads, two MFMAs} per k-step (left to itself the
-            // scheduler reuses one operand register set and waits for every read right after issuing it)
-            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
-                if (s + 2 < KSTEPS) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            }
+            bf16x8 ka[16];  // read i: k-step i / 2, half i % 2
+#define K_READ(i) ka[i] = lds_load128_at<((i) & 1) * 32 * 256>(kl + koff[(i) >> 1]);
+#define QK_STEP(i)                                                                                            \
+            lds_wait<((i) < 8 ? 7 : 15 - (i))>(ka[i]);                                                        \
+            sacc[(i) & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[i], qreg[(i) >> 1], sacc[(i) & 1], 0, 0, 0);
+            K_READ(0) K_READ(1) K_READ(2) K_READ(3) K_READ(4) K_READ(5) K_READ(6) K_READ(7)
+            QK_STEP(0) K_READ(8) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(1) K_READ(9) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(2) K_READ(10) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(3) K_READ(11) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(4) K_READ(12) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(5) K_READ(13) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(6) K_READ(14) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(7) K_READ(15) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(8) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(9) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(10) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(11) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(12) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(13) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(14) __builtin_amdgcn_sched_barrier(0);
+            QK_STEP(15) __builtin_amdgcn_sched_barrier(0);
+#undef K_READ
+#undef QK_STEP
+            // V operands of the first 32 keys (MFMA n = 4 st + db of that half): two transposing reads each
+            bf16x4 vlo[16], vhi[16];
+#define V_READ(n)                                                                                              \
+            vlo[n] = lds_load_tr4<(32 * ((n) >> 3) + 16 * (((n) >> 2) & 1)) * 256>(vl + voff[(n) & 3][0]);     \
+            vhi[n] = lds_load_tr4<(32 * ((n) >> 3) + 16 * (((n) >> 2) & 1)) * 256>(vl + voff[(n) & 3][1]);
+            V_READ(0) V_READ(1) V_READ(2) V_READ(3) V_READ(4) V_READ(5) V_READ(6) V_READ(7)
+            __builtin_amdgcn_sched_barrier(0);
             const int tbase = kb * TILE_KEYS;
             if (tbase + TILE_KEYS > L) {  // only blocks that contain tree keys (or the end) need the mask
 #pragma unroll
@@ -333,18 +355,33 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
                     for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
             }
             // ---- O^T += V^T P^T ------------------------------------------------------------------
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db)
-#pragma unroll
-                    for (int st = 0; st < 2; ++st) {
-                        const unsigned char *vb = vt + (32 * j + 16 * st) * 256;
-                        const bf16x4 lo = lds_read_tr4((const __bf16 *)(vb + voff[db][0]));
-                        const bf16x4 hi = lds_read_tr4((const __bf16 *)(vb + voff[db][1]));
-                        const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j][st], oacc[db], 0, 0, 0);
-                    }
+            // MFMA n (half n / 8, k-step (n / 4) % 2, output block n % 4); the reads of the second half are
+            // issued one MFMA at a time behind the first half's MFMAs
+#define PV_STEP(n, W)                                                                                          \
+            lds_wait2<W>(vlo[n], vhi[n]);                                                                      \
+            oacc[(n) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                                           \
+                __builtin_shufflevector(vlo[n], vhi[n], 0, 1, 2, 3, 4, 5, 6, 7), pb[(n) >> 3][((n) >> 2) & 1], \
+                oacc[(n) & 3], 0, 0, 0);
+            PV_STEP(0, 0) V_READ(8) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(1, 2) V_READ(9) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(2, 4) V_READ(10) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(3, 6) V_READ(11) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(4, 8) V_READ(12) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(5, 10) V_READ(13) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(6, 12) V_READ(14) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(7, 14) V_READ(15) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(8, 14) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(9, 12) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(10, 10) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(11, 8) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(12, 6) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(13, 4) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(14, 2) __builtin_amdgcn_sched_barrier(0);
+            PV_STEP(15, 0)
+            // the "memory" clobber keeps the next iteration's loads into this stage behind this block's reads
+            asm volatile("" ::: "memory");
+#undef PV_STEP
+#undef V_READ
         }
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's part of the next block has landed
         __syncthreads();
