@@ -92,6 +92,28 @@ __device__ __forceinline__ void acc_scale(f32x16 &acc, float alpha) {
 #undef ACC_SCALE4
 }
 
+// The value of the partner lane (lane ^ 32) next to the own one, without a trip through the LDS
+// crossbar: v_permlane32_swap exchanges the upper half of one register with the lower half of another,
+// so from two copies of x every lane ends up holding {x[lane], x[lane ^ 32]} in the two registers (in
+// either order; layout checked on the device).  Written as an instruction: the compiler's builtin
+// returned the same element for both results when they met in one expression.  The waits around it
+// cover the vector-write -> swap-read distance the hardware asks for.
+__device__ __forceinline__ void half_swap(float x, float &a, float &b) {
+    a = x;
+    b = x;
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float half_swap_max(float x) {
+    float a, b;
+    half_swap(x, a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+    float a, b;
+    half_swap(x, a, b);
+    return a + b;
+}
+
 #define ATT_KB 32           // keys per block
 #define ATT_ROWS_PER_WAVE 32
 #define ATT_WAVES 4
@@ -325,7 +347,7 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
             for (int j = 0; j < 2; ++j)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) mloc = fmaxf(mloc, sacc[j][i]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            mloc = half_swap_max(mloc);
             // m_run is a reference, not the exact running maximum: it moves only when a block's maximum
             // lies more than LAZY_LOG2 binary orders above it.  Until then probabilities may reach
             // 2^LAZY_LOG2 instead of 1 (harmless in fp32 sums and in bf16's relative precision) and the 64
@@ -388,7 +410,7 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
     }
 
     // ---- epilogue -------------------------------------------------------------------------------
-    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    const float l_tot = half_swap_sum(l_run);
     if (!qvalid) return;
     if (dst.direct) {
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
@@ -801,7 +823,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
             float mloc = sacc[0];
 #pragma unroll
             for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, sacc[i]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+            mloc = half_swap_max(mloc);
             // lazily moved reference maximum, as in the large-batch kernel
             const bool move = (mloc - m_run) * c > LAZY_LOG2;
             const float m_new = move ? mloc : m_run;
@@ -823,24 +845,22 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
                 for (int db = 0; db < DBLK; ++db) acc_scale(oacc[db], alpha);
             }
 
-            bf16x8 va[2][DBLK];
-#pragma unroll
-            for (int st = 0; st < 2; ++st)
-#pragma unroll
-                for (int db = 0; db < DBLK; ++db)
-                    va[st][db] = __builtin_shufflevector(vlo[db][st], vhi[db][st], 0, 1, 2, 3, 4, 5, 6, 7);
-            // all V reads have landed (they had the whole softmax); the "memory" clobber also keeps the next
-            // iteration's loads into this stage behind this block's reads
+            // All V reads have landed (they had the whole softmax).  The wait is tied to the very registers
+            // the reads fill, and the halves are joined only behind it: a register copy made before the
+            // data arrives would copy the old contents.  The "memory" clobber also keeps the next
+            // iteration's loads into this stage behind this block's reads.
             asm volatile("s_waitcnt lgkmcnt(0)"
-                         : "+v"(va[0][0]), "+v"(va[0][1]), "+v"(va[0][2]), "+v"(va[0][3]), "+v"(va[1][0]), "+v"(va[1][1]),
-                           "+v"(va[1][2]), "+v"(va[1][3])
+                         : "+v"(vlo[0][0]), "+v"(vhi[0][0]), "+v"(vlo[1][0]), "+v"(vhi[1][0]), "+v"(vlo[2][0]), "+v"(vhi[2][0]),
+                           "+v"(vlo[3][0]), "+v"(vhi[3][0]), "+v"(vlo[0][1]), "+v"(vhi[0][1]), "+v"(vlo[1][1]), "+v"(vhi[1][1]),
+                           "+v"(vlo[2][1]), "+v"(vhi[2][1]), "+v"(vlo[3][1]), "+v"(vhi[3][1])
                          :
                          : "memory");
 #pragma unroll
             for (int st = 0; st < 2; ++st)
 #pragma unroll
                 for (int db = 0; db < DBLK; ++db)
-                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[st][db], pb[st], oacc[db], 0, 0, 0);
+                    oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_shufflevector(vlo[db][st], vhi[db][st], 0, 1, 2, 3, 4, 5, 6, 7), pb[st], oacc[db], 0, 0, 0);
         }
     } else {
     const int kq = lane >> 4, dc = lane & 15;
@@ -918,7 +938,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
         float mloc = sacc[0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) mloc = fmaxf(mloc, sacc[i]);
-        mloc = fmaxf(mloc, __shfl_xor(mloc, 32, 64));
+        mloc = half_swap_max(mloc);
         // lazily moved reference maximum, as in the large-batch kernel
         const bool move = (mloc - m_run) * c > LAZY_LOG2;
         const float m_new = move ? mloc : m_run;
@@ -963,7 +983,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
     }
 
     // ---- the partial results meet ----------------------------------------------------------------
-    float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    float l_tot = half_swap_sum(l_run);
     __syncthreads();  // all private tiles are dead
     // exchange layout: float4 slot (slice, q, lane) at ((slice*16 + q)*64 + lane), q = 4 db + i/4
     float4 *xb = (float4 *)s_dyn;
