@@ -287,7 +287,7 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
         const int cur = (kb - kb0) & 1;
         if (kb + 1 < kb1) fetch(kb + 1, cur ^ 1);  // the other stage was last read before the previous barrier
         if (active) {
-            const unsigned char *kt = s_dyn + cur * STAGE_BYTES, *vt = kt + TILE_BYTES;
+            const unsigned char *kt = s_dyn + cur * STAGE_BYTES;  // K tile of this stage, its V tile behind it
             // ---- S^T: 64 keys x 32 queries as two 32x32 blocks -----------------------------------
             // The LDS reads are bare instructions with hand-kept waits: eight K reads (four k-steps of both
             // 32-key halves) stay in flight ahead of the MFMAs, and the first half of the V reads is issued
@@ -692,7 +692,6 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
     // LDS: NW private tiles during the loop, then the exchange area of the partial results
     extern __shared__ __attribute__((aligned(16))) unsigned char s_dyn[];
     __shared__ float s_m[NW][32], s_l[NW][32];
-    float *s_buf = (float *)s_dyn;
     __bf16 *kt = (__bf16 *)s_dyn + w * WT_ELEMS;   // staged layout (!DIRECT): padded rows
     __bf16 *vt = kt + KT_ELEMS;
     unsigned char *wtile = s_dyn + w * 2 * WD_STAGE;  // direct layout: two stages of (K tile, V tile), 256-byte rows
@@ -780,7 +779,7 @@ __global__ __launch_bounds__(64 * NW) void attn_wave_kernel(AttnArgs a, int KS, 
         for (; kb < nb; kb += kstep, cur ^= 1) {
             __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this block has landed
             if (kb + kstep < nb) fetch(kb + kstep, cur ^ 1);  // the other stage was last read one block ago
-            const unsigned char *ktile = wtile + cur * WD_STAGE, *vtile = ktile + WD_TILE;
+            const unsigned char *ktile = wtile + cur * WD_STAGE;  // K tile of this stage, its V tile behind it
             // Every operand of the block is asked for before it is needed (with one wave per SIMD nothing
             // else hides LDS latency): the eight K reads first, the sixteen transposing V reads between the
             // MFMAs of S^T, whose accumulator chain leaves the issue slots free.  K read s is followed by

@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256) void commit_kernel(CommitArgs a) {
     const int cap = max(a.prefix_cap[b], 0);
     const int L = min(max(a.prefix_len[b], 0), cap);
     const int rows = min(len + 1, cap - L);  // rows that still fit
-    if (threadIdx.x <= len)  // a node index outside the tree (bad input) is clamped, never followed
+    if ((int)threadIdx.x <= len)  // a node index outside the tree (bad input) is clamped, never followed
         s_node[threadIdx.x] = min(max(a.path_nodes[(int64_t)b * (DT_D_MAX + 1) + threadIdx.x], 0), N - 1);
     __syncthreads();
     if (layer == 0 && kv == 0 && threadIdx.x == 0) {
