@@ -178,7 +178,10 @@ int dt_build_tree(void *stream, int batch, const dt_params *params, const void *
  *   q, out         [batch, TT_cap, Hq, D]  type t (rows >= n_nodes[b] are neither read nor written)
  *   k_tree, v_tree [batch, TT_cap, Hkv, D] type t
  *   k_prefix[b], v_prefix[b] : device arrays (length batch) of device pointers; element
- *       (token, kv head, c) at token*kv_stride_tok + head*kv_stride_head + c (strides in elements)
+ *       (token, kv head, c) at token*kv_stride_tok + head*kv_stride_head + c (strides in elements);
+ *       [token, kv head, D] and [kv head, token, D] caches are both expressed by the two strides.
+ *       The pointers themselves must be 16-byte aligned (they live in device memory, so the host
+ *       cannot check them; the kernels read 16 bytes at a time from them)
  *   max_prefix_len : host upper bound of prefix_len[] (sizes the launch)
  * Arithmetic: bf16 inputs, fp32 accumulation, fp32 softmax, output rounded to bf16; fp32 inputs are
  * handled entirely in fp32.  bf16 with D == 128 and both strides multiples of 8 elements runs on the
