@@ -50,6 +50,19 @@ __device__ __forceinline__ bf16x8 lds_load128(u32 addr) {
     asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
     return v;
 }
+// One global_load_lds_dwordx4 with the address split into a wave-uniform base (scalar registers) and a 32-bit
+// per-lane byte offset, the LDS destination (wave-uniform, the lanes' 16 bytes follow each other) in M0: no
+// vector arithmetic per load, and no 64-bit per-lane pointers to keep and advance.
+__device__ __forceinline__ void load_to_lds16(const void __attribute__((address_space(1))) *base, u32 lane_off, u32 lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(base), "s"(lds_addr)
+                 : "memory", "m0");
+}
+// a 64-bit value that is the same in every lane, moved to scalar registers where the compiler has not seen that
+__device__ __forceinline__ int64_t uniform_i64(int64_t v) {
+    const u32 lo = __builtin_amdgcn_readfirstlane((u32)v), hi = __builtin_amdgcn_readfirstlane((u32)((u64)v >> 32));
+    return (int64_t)(((u64)hi << 32) | lo);
+}
+__device__ __forceinline__ gbytep uniform_ptr(gbytep p) { return (gbytep)uniform_i64((int64_t)(uintptr_t)p); }
 template <int OFF>
 __device__ __forceinline__ bf16x8 lds_load128_at(u32 addr) {
     bf16x8 v;
@@ -226,12 +239,8 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
     // 16 lanes of a row still cover its 256 bytes.  f(row) does not depend on i (16 | 16 i).
     const int krow = tid >> 4, cpos = tid & 15;
     const int kchunk = cpos ^ krow, vchunk = cpos ^ (((krow & 3) << 2) | (krow >> 2));
-    u32 koffp[4], voffp[4];  // inside the prefix: byte offsets from the block's first row
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        koffp[i] = (u32)((16 * i + krow) * stok + 8 * kchunk) * 2u;
-        voffp[i] = (u32)((16 * i + krow) * stok + 8 * vchunk) * 2u;
-    }
+    // inside the prefix: a lane's byte offset from the first of its load's sixteen rows (the same for all four loads)
+    const u32 koffp = (u32)(krow * stok + 8 * kchunk) * 2u, voffp = (u32)(krow * stok + 8 * vchunk) * 2u;
     const bool small_stride = (int64_t)TILE_KEYS * stok * 2 < ((int64_t)1 << 31);
 
     // Every load is unconditional.  Keys past the end are read from the last valid row; their
@@ -241,12 +250,14 @@ __device__ __forceinline__ void tile_segment(const AttnArgs &a, unsigned char *s
         const ldsp kdst = (ldsp)s_dyn + stage * STAGE_BYTES + 4 * w * 256;
         const ldsp vdst = kdst + TILE_BYTES;
         if (small_stride && kb * TILE_KEYS + TILE_KEYS <= L) {  // block inside the prefix (uniform test)
-            const gbytep kbase = (gbytep)(kpre + (int64_t)kb * TILE_KEYS * stok);
-            const gbytep vbase = (gbytep)(vpre + (int64_t)kb * TILE_KEYS * stok);
+            const u32 kl = (u32)(uintptr_t)kdst, vl = (u32)(uintptr_t)vdst;
+            const gbytep kbase = uniform_ptr((gbytep)(kpre + (int64_t)kb * TILE_KEYS * stok));
+            const gbytep vbase = uniform_ptr((gbytep)(vpre + (int64_t)kb * TILE_KEYS * stok));
+            const int64_t step = uniform_i64(16 * stok * 2);  // bytes between the first rows of two loads
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                __builtin_amdgcn_global_load_lds(kbase + koffp[i], kdst + i * 16 * 256, 16, 0, 0);
-                __builtin_amdgcn_global_load_lds(vbase + voffp[i], vdst + i * 16 * 256, 16, 0, 0);
+                load_to_lds16(kbase + i * step, koffp, kl + i * 16 * 256);
+                load_to_lds16(vbase + i * step, voffp, vl + i * 16 * 256);
             }
         } else {                                                 // block touching the tree keys or the end
 #pragma unroll
