@@ -88,15 +88,20 @@ __device__ __forceinline__ void lds_wait(bf16x8 &v) {
 // Written out as instructions because any ordinary vector-ALU use of the accumulators inside the
 // block loop makes the compiler keep a second copy of all of them in vector registers and move the
 // 64 values across in every iteration, although this multiply runs in the first block or two only.
+// The idle cycles in front and behind keep the distances the hardware asks for between an MFMA that
+// writes or reads an accumulator register and a vector instruction that reads or writes it (the
+// compiler does not look inside the instruction group); on this rarely taken path they cost nothing.
 __device__ __forceinline__ void acc_scale(f32x16 &acc, float alpha) {
     float t;
 #define ACC_SCALE4(i0)                                                                                          \
     {                                                                                                           \
         float e0 = acc[i0], e1 = acc[i0 + 1], e2 = acc[i0 + 2], e3 = acc[i0 + 3];                               \
-        asm volatile("v_accvgpr_read_b32 %4, %0\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %0, %4\n\t"     \
+        asm volatile("s_nop 7\n\ts_nop 7\n\t"                                                                  \
+                     "v_accvgpr_read_b32 %4, %0\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %0, %4\n\t"     \
                      "v_accvgpr_read_b32 %4, %1\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %1, %4\n\t"     \
                      "v_accvgpr_read_b32 %4, %2\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %2, %4\n\t"     \
-                     "v_accvgpr_read_b32 %4, %3\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %3, %4"          \
+                     "v_accvgpr_read_b32 %4, %3\n\tv_mul_f32 %4, %4, %5\n\tv_accvgpr_write_b32 %3, %4\n\t"     \
+                     "s_nop 7"                                                                                  \
                      : "+a"(e0), "+a"(e1), "+a"(e2), "+a"(e3), "=&v"(t)                                         \
                      : "v"(alpha));                                                                             \
         acc[i0] = e0; acc[i0 + 1] = e1; acc[i0 + 2] = e2; acc[i0 + 3] = e3;                                     \
