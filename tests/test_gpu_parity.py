@@ -124,7 +124,7 @@ def oracle_attention(case, b, scale, key=None):
     return want
 
 
-def assert_attention(out, want, dtype, tag):
+def assert_attention(out, want, dtype, tag, own_abs=None):
     """Every output element against the oracle; NaN or inf anywhere fails."""
     assert out.shape == want.shape, tag
     assert np.isfinite(out).all(), (tag, "non-finite attention output")
@@ -132,7 +132,7 @@ def assert_attention(out, want, dtype, tag):
     err = float(diff.max())
     own = float((diff - OWN_REL[dtype] * np.abs(want)).max())      # what is left after two ulps of the result
     assert err <= NORTH_STAR_TOL[dtype], (tag, "attention max-abs", err)
-    assert own <= OWN_ABS[dtype], (tag, "attention error above our own bound", own, err)
+    assert own <= (OWN_ABS[dtype] if own_abs is None else own_abs), (tag, "attention error above our own bound", own, err)
     return err, own
 
 
@@ -601,6 +601,39 @@ def test_keys_outside_a_nodes_ancestor_set_do_not_reach_its_output(shape):
                 assert same, (shape, b, i, j, "a hidden key reached the output")
                 unchanged += 1
     assert changed > 0 and unchanged > changed
+
+
+@pytest.mark.parametrize("shape", ["wave", "wave_split", "gang", "tile"])
+def test_scores_that_grow_along_the_keys_move_the_softmax_reference_late(shape):
+    """The kernels move their softmax reference lazily and rescale the output accumulators only then.  Keys
+    whose length grows with their position (prefix and tree) make the scores of every query climb by many
+    powers of two along the key axis, so the reference moves several times while the accumulators are far
+    from zero; every output is still compared with the oracle."""
+    cfg = _attention_shapes()[shape]
+    case = oracle_case(0, cfg=cfg)
+    st = make_step(case)
+    st.build_tree()
+    worst = 0.0
+    want_all = []
+    for b in range(cfg.B):
+        q, kt, vt, kp, vp = (dt_synth.as_f32(x).copy() for x in dt_synth.qkv(cfg, b))
+        N, L = case.trees[b]["n_nodes"], kp.shape[0]
+        q[:] = np.abs(q)                                      # q . k then grows with |k| instead of cancelling
+        ramp = np.linspace(0.05, 6.0, L + N, dtype=np.float32)
+        kp[:] = np.abs(kp) * ramp[:L, None, None]
+        kt[:N] = np.abs(kt[:N]) * ramp[L:, None, None]
+        rnd = lambda x: dt_synth.f32_to_bf16_bits(x)
+        qb, ktb, vtb, kpb, vpb = rnd(q), rnd(kt), rnd(vt), rnd(kp), rnd(vp)
+        st.set_qkv(b, qb, ktb, vtb, kpb, vpb)
+        want_all.append(ref.tree_attention(qb[:N], ktb[:N], vtb[:N], kpb, vpb, case.trees[b]["anc_mask"], st.scale))
+    st.tree_attention()
+    torch.cuda.synchronize()
+    for b in range(cfg.B):
+        # A softmax this peaked puts nearly all weight on one or two keys with |v| up to 4: the bf16 rounding of
+        # the probabilities (2^-9 relative) alone is then worth 8e-3, twice the bound derived for N(0,1) scores.
+        e, _ = assert_attention(st.attention_out(b), want_all[b], cfg.dtype, "%s seq %d" % (shape, b), own_abs=1e-2)
+        worst = max(worst, e)
+    print("growing scores, %s: max-abs %.3e" % (shape, worst))
 
 
 def test_more_rows_than_a_grid_dimension_holds():
